@@ -1,0 +1,14 @@
+"""Seeded synthetic workloads shared by tests, the benchmark and the oracle checks.
+
+This package holds no arithmetic of the method (no basis, no projection, no
+attention): only shapes, random draws and dtype rounding.
+"""
+
+from .configs import FAConfig, CONFIGS, get_config, small_variants  # noqa: F401
+from .synth import (  # noqa: F401
+    round_to_bf16,
+    bf16_bits,
+    make_masks,
+    make_context,
+    rel_err,
+)

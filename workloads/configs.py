@@ -1,0 +1,122 @@
+"""The five benchmark configurations and a few small parity shapes.
+
+Field names follow the paper's notation (Section 3.3): `Li` = L_init sink
+tokens, `Lw` = L_local recent-window tokens, `N` = compressed middle segment,
+`Dkc`/`Dvc` = number of compressed K / V head dimensions, `M` = number of real
+Fourier states kept per compressed dimension, `T` = period of the basis.
+"""
+
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+
+
+@dataclass(frozen=True)
+class FAConfig:
+    name: str
+    index: int          # selects the seeds (1000+index tensors, 2000+index masks)
+    B: int
+    Hq: int
+    Hkv: int
+    D: int
+    dtype: str          # "f32" or "bf16"
+    Li: int
+    Lw: int
+    N: int
+    Dkc: int
+    Dvc: int
+    M: int
+    num_splits: int = 0  # 0 = library chooses
+
+    @property
+    def W(self) -> int:
+        return self.Li + self.Lw
+
+    @property
+    def L(self) -> int:
+        return self.Li + self.N + self.Lw
+
+    @property
+    def T(self) -> int:
+        # One period spans the compressed segment (the only choice for which
+        # the basis is orthogonal on it); never shorter than the band.
+        return max(self.N, self.M)
+
+    @property
+    def G(self) -> int:
+        return self.Hq // self.Hkv
+
+    @property
+    def tol(self) -> float:
+        return 1e-5 if self.dtype == "f32" else 2e-3
+
+    def elem_bytes(self) -> int:
+        return 4 if self.dtype == "f32" else 2
+
+    def decode_bytes(self) -> int:
+        """Algorithmic bytes of one decode step: q, coefficients (fp32), kept
+        middle dims, full-width sink/window rows, masks, output (fp32)."""
+        e = self.elem_bytes()
+        bh = self.B * self.Hkv
+        return (self.B * self.Hq * self.D * e
+                + bh * self.M * (self.Dkc + self.Dvc) * 4
+                + bh * self.N * ((self.D - self.Dkc) + (self.D - self.Dvc)) * e
+                + bh * self.W * self.D * 2 * e
+                + bh * self.D * 2
+                + self.B * self.Hq * self.D * 4)
+
+    def compress_bytes(self, Dc: int) -> int:
+        """Algorithmic bytes of one fa_compress call (K or V): read full rows,
+        write coefficients, write kept dims."""
+        e = self.elem_bytes()
+        bh = self.B * self.Hkv
+        return bh * (self.N * self.D * e + self.M * Dc * 4 + self.N * (self.D - Dc) * e + self.D)
+
+    def compress_flops(self, Dc: int) -> int:
+        return 2 * self.B * self.Hkv * self.N * self.M * Dc
+
+
+CONFIGS = (
+    FAConfig("tiny", 1, B=1, Hq=4, Hkv=1, D=64, dtype="f32", Li=4, Lw=128, N=380,
+             Dkc=48, Dvc=48, M=32),
+    FAConfig("llama3_8b_32k", 2, B=1, Hq=32, Hkv=8, D=128, dtype="bf16", Li=4, Lw=1024,
+             N=31740, Dkc=96, Dvc=96, M=256),
+    FAConfig("batched_16x8k", 3, B=16, Hq=32, Hkv=8, D=128, dtype="bf16", Li=4, Lw=512,
+             N=7676, Dkc=96, Dvc=96, M=128),
+    FAConfig("long_128k", 4, B=1, Hq=32, Hkv=8, D=128, dtype="bf16", Li=4, Lw=2048,
+             N=129020, Dkc=112, Dvc=112, M=512, num_splits=64),
+    FAConfig("llama2_7b_mha_prefill", 5, B=8, Hq=32, Hkv=32, D=128, dtype="bf16", Li=4,
+             Lw=512, N=4096, Dkc=96, Dvc=96, M=256),
+)
+
+
+def get_config(key) -> FAConfig:
+    """Look a config up by 1-based index or by name."""
+    for c in CONFIGS:
+        if key == c.index or key == c.name or str(key) == str(c.index):
+            return c
+    raise KeyError(key)
+
+
+def small_variants():
+    """Parity shapes the oracle finishes in seconds: several tiles, ragged
+    tails, K/V with different compressed counts, odd M, degenerate splits."""
+    base = CONFIGS[0]
+    return (
+        base,
+        replace(base, name="tiny_bf16", index=11, dtype="bf16"),
+        replace(base, name="gqa8_oddM", index=12, Hq=8, Hkv=1, D=128, N=777, Lw=61,
+                Dkc=96, Dvc=112, M=63, dtype="bf16"),
+        replace(base, name="mha_ragged", index=13, B=2, Hq=3, Hkv=3, D=128, N=1301, Lw=37,
+                Dkc=80, Dvc=64, M=128, dtype="bf16"),
+        replace(base, name="no_compress", index=14, B=2, Hq=4, Hkv=2, D=64, N=300, Lw=20,
+                Dkc=0, Dvc=0, M=16, dtype="f32"),
+        replace(base, name="all_compress", index=15, B=1, Hq=2, Hkv=2, D=64, N=515, Lw=0, Li=1,
+                Dkc=64, Dvc=64, M=17, dtype="f32"),
+        replace(base, name="window_only", index=16, B=1, Hq=4, Hkv=2, D=128, N=0, Lw=200,
+                Dkc=96, Dvc=96, M=8, dtype="bf16"),
+        replace(base, name="middle_only", index=17, B=1, Hq=4, Hkv=2, D=128, N=2100, Lw=0, Li=0,
+                Dkc=104, Dvc=88, M=200, dtype="bf16"),
+        replace(base, name="g2_m1", index=18, B=3, Hq=4, Hkv=2, D=64, N=130, Lw=7,
+                Dkc=8, Dvc=56, M=1, dtype="f32"),
+    )
