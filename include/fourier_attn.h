@@ -1,0 +1,150 @@
+/*
+ * fourier_attn.h -- C ABI of the MI355X (gfx950) FourierAttention hot path.
+ *
+ * Two operations of the paper's Section 3.3 ("Online Compression via
+ * HiPPO-FourierT"):
+ *
+ *   fa_compress  Eq. 1-4 (and Eq. 5 when `accumulate` is set): split the head
+ *                dimensions of a middle token segment of K or of V into
+ *                compressed and kept ones, project the compressed ones onto
+ *                the first M real Fourier basis functions, and pack the kept
+ *                ones.
+ *   fa_decode    Eq. 6: single-query attention over cat(sink+window rows,
+ *                reconstructed middle rows) where the compressed dimensions
+ *                of the middle rows are evaluated from their coefficients on
+ *                the fly and never written to memory.
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates nothing, keeps no global state and never synchronises: work
+ *     is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns immediately.
+ *   - Arguments are validated on the host before anything is launched; an
+ *     invalid call launches nothing and returns a negative status.
+ *   - Nothing throws, aborts or prints.
+ *
+ * Basis (Eq. 4, with the identically-zero sine of order 0 dropped): for
+ * position p (relative to the first compressed token of the sequence),
+ *   phi_0(p) = 1,  phi_{2n-1}(p) = cos(2 pi n p / T),  phi_{2n}(p) = sin(2 pi n p / T).
+ * Coefficients are the plain inner products C[m,i] = sum_j phi_m(t0+j) X[j,i];
+ * reconstruction weights each function by the inverse of its squared norm over
+ * one period (1/T for the constant and for the cosine with 2n = T, else 2/T).
+ */
+#ifndef FOURIER_ATTN_H
+#define FOURIER_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes: 0 = success, negative = error */
+enum {
+  FA_OK = 0,
+  FA_ERR_NULL = -1,        /* a required pointer is NULL                      */
+  FA_ERR_SHAPE = -2,       /* inconsistent or out-of-range sizes              */
+  FA_ERR_UNSUPPORTED = -3, /* legal problem, but outside the compiled limits  */
+  FA_ERR_WORKSPACE = -4,   /* workspace too small or misaligned               */
+  FA_ERR_HIP = -5          /* a HIP launch reported an error                  */
+};
+
+/* element type of q / K / V / kept-dimension tensors */
+enum { FA_F32 = 0, FA_BF16 = 1 };
+
+/* layout of the packed kept dimensions (K^mu / V^mu of Eq. 2), Du = D - Dc columns
+ *   FA_KEEP_ROWS  [n_tokens, Du]            one row per token  (what fa_decode reads for K)
+ *   FA_KEEP_TOK8  [ceil(n_tokens/8), Du, 8] eight consecutive tokens of one
+ *                 dimension are contiguous    (what fa_decode reads for V)   */
+enum { FA_KEEP_ROWS = 0, FA_KEEP_TOK8 = 1 };
+
+/* compiled limits */
+#define FA_MAX_HEAD_DIM 256   /* D, must be a multiple of 8                     */
+#define FA_MAX_GROUP 16       /* query heads per KV head                         */
+#define FA_MAX_STATES 1024    /* M                                               */
+#define FA_MAX_SPLITS 256     /* token-axis chunks of fa_decode                  */
+
+/*
+ * fa_compress -- Eq. 2-3 for one tensor (K or V), optionally Eq. 5.
+ *
+ *   x           [B,H,N,D] middle segment (rows L_init .. L - L_local of Eq. 1),
+ *               element type `dtype`, element strides sx_b/sx_h/sx_n, dim stride 1.
+ *               Strides and base address must keep rows 16-byte aligned.
+ *   dim_mask    [B,H,D] bytes, 1 = dimension is compressed.  Each row must
+ *               contain exactly Dc ones (not checked: it would need a sync).
+ *   M, T, t0    number of basis functions kept, period, position of x's
+ *               first row;  1 <= M <= T, t0 >= 0, t0 + N <= T.
+ *   accumulate  0: coeffs = projection;  1: coeffs += projection (Eq. 5 is the
+ *               N = 1 case with t0 = number of tokens compressed so far).
+ *   coeffs      [B,H,M,Dc] fp32, columns in ascending dimension order.
+ *   x_keep      kept dimensions in ascending dimension order, layout
+ *               `keep_layout`, element type `dtype`; slab (b,h) starts at
+ *               x_keep + (b*H+h)*keep_stride_bh elements and token j of x is
+ *               stored at token index keep_offset + j of that slab.  May be
+ *               NULL (nothing is written).  keep_stride_bh = 0 means dense.
+ *   workspace   at least fa_compress_workspace_bytes(...) bytes, 256-byte aligned.
+ *
+ * N = 0 is legal (coeffs are zeroed unless accumulating).  Dc = 0 writes only
+ * x_keep; Dc = D writes only coeffs.
+ */
+int fa_compress(const void* x, int dtype,
+                int64_t sx_b, int64_t sx_h, int64_t sx_n,
+                int B, int H, int N, int D,
+                const uint8_t* dim_mask, int Dc,
+                int M, int T, int t0, int accumulate,
+                float* coeffs,
+                void* x_keep, int keep_layout, int64_t keep_stride_bh, int keep_offset,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+size_t fa_compress_workspace_bytes(int B, int H, int N, int D, int Dc, int M);
+
+/*
+ * fa_decode -- Eq. 6 for one new query token per sequence.
+ *
+ *   q           [B,Hq,D] `dtype`; query head i uses KV head i / (Hq/Hkv).
+ *   ck, cv      [B,Hkv,M,Dkc], [B,Hkv,M,Dvc] fp32 coefficients (K^mc, V^mc).
+ *   kmask,vmask [B,Hkv,D] bytes; popcount Dkc / Dvc per row.
+ *   M, T, t0, N basis size, period, position of the first middle row, number
+ *               of middle rows (t0 + N <= T).
+ *   k_keep      K^mu, FA_KEEP_ROWS layout, N tokens per (b,h) slab, slab stride
+ *               kk_stride_bh elements (0 = dense).
+ *   v_keep      V^mu, FA_KEEP_TOK8 layout, slab stride vk_stride_bh (0 = dense).
+ *   k_full,v_full [B,Hkv,W,D] `dtype`: the L_init sink rows followed by the
+ *               L_local window rows (their order does not affect the result);
+ *               slab stride full_stride_bh elements (0 = dense).
+ *   scale       softmax scale; <= 0 selects 1/sqrt(D).
+ *   num_splits  token-axis chunks per (sequence, KV head) for the middle rows;
+ *               0 lets the library choose.  The result does not depend on it
+ *               beyond fp32 summation order.
+ *   out         [B,Hq,D] fp32.
+ *   workspace   at least fa_decode_workspace_bytes(...) bytes, 256-byte aligned.
+ *
+ * N = 0, W = 0, Dkc/Dvc = 0 or D are legal; N + W = 0 is FA_ERR_SHAPE.
+ */
+int fa_decode(const void* q, int dtype,
+              int B, int Hq, int Hkv, int D,
+              const float* ck, const uint8_t* kmask, int Dkc,
+              const float* cv, const uint8_t* vmask, int Dvc,
+              int M, int T, int t0, int N,
+              const void* k_keep, int64_t kk_stride_bh,
+              const void* v_keep, int64_t vk_stride_bh,
+              const void* k_full, const void* v_full, int W, int64_t full_stride_bh,
+              float scale, int num_splits,
+              float* out,
+              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+size_t fa_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int Dkc, int Dvc,
+                                 int M, int N, int W, int num_splits);
+
+/* Number of middle-row chunks fa_decode will use for these sizes when
+ * num_splits = 0 (exposed so callers can size and report). */
+int fa_decode_default_splits(int B, int Hkv, int N);
+
+/* Static description of a status code (never NULL). */
+const char* fa_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOURIER_ATTN_H */

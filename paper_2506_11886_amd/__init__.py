@@ -1,0 +1,15 @@
+"""MI355X-native FourierAttention hot path: `fa_compress` and `fa_decode`.
+
+A thin ctypes binding over the C ABI declared in include/fourier_attn.h.
+Every step of the path runs in the HIP kernels of libfourier_attn.so; this
+package only marshals torch tensors (device memory, streams) into pointers
+and sizes.  There is no CPU fallback: a missing library is an ImportError.
+"""
+
+from .binding import (  # noqa: F401
+    FA_OK, FA_F32, FA_BF16, FA_KEEP_ROWS, FA_KEEP_TOK8,
+    FourierAttnError, lib, library_path, status_string,
+    compress_workspace_bytes, decode_workspace_bytes, decode_default_splits,
+    fa_compress, fa_decode,
+    keep_rows_from_tok8, tok8_numel,
+)

@@ -1,0 +1,160 @@
+"""ctypes binding of libfourier_attn.so (argument marshalling only)."""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # imported before the library so both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfourier_attn.so")
+
+FA_OK = 0
+FA_F32, FA_BF16 = 0, 1
+FA_KEEP_ROWS, FA_KEEP_TOK8 = 0, 1
+
+
+class FourierAttnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2506_11886_amd.build` "
+            "(there is no fallback implementation)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    c = ctypes
+    vp, i32, i64, f32, sz = c.c_void_p, c.c_int, c.c_int64, c.c_float, c.c_size_t
+    lib.fa_compress.restype = i32
+    lib.fa_compress.argtypes = [vp, i32, i64, i64, i64, i32, i32, i32, i32, vp, i32,
+                                i32, i32, i32, i32, vp, vp, i32, i64, i32, vp, sz, vp]
+    lib.fa_compress_workspace_bytes.restype = sz
+    lib.fa_compress_workspace_bytes.argtypes = [i32] * 6
+    lib.fa_decode.restype = i32
+    lib.fa_decode.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp, i32,
+                              i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, i32, i64,
+                              f32, i32, vp, vp, sz, vp]
+    lib.fa_decode_workspace_bytes.restype = sz
+    lib.fa_decode_workspace_bytes.argtypes = [i32] * 10
+    lib.fa_decode_default_splits.restype = i32
+    lib.fa_decode_default_splits.argtypes = [i32] * 3
+    lib.fa_status_string.restype = c.c_char_p
+    lib.fa_status_string.argtypes = [i32]
+    return lib
+
+
+lib = _load()
+
+
+def status_string(status: int) -> str:
+    return lib.fa_status_string(int(status)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return FA_F32
+    if t.dtype == torch.bfloat16:
+        return FA_BF16
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def compress_workspace_bytes(B, H, N, D, Dc, M) -> int:
+    return int(lib.fa_compress_workspace_bytes(B, H, N, D, Dc, M))
+
+
+def decode_workspace_bytes(B, Hq, Hkv, D, Dkc, Dvc, M, N, W, num_splits=0) -> int:
+    return int(lib.fa_decode_workspace_bytes(B, Hq, Hkv, D, Dkc, Dvc, M, N, W, num_splits))
+
+
+def decode_default_splits(B, Hkv, N) -> int:
+    return int(lib.fa_decode_default_splits(B, Hkv, N))
+
+
+def tok8_numel(n_tokens: int, Du: int) -> int:
+    """Elements of one FA_KEEP_TOK8 slab holding n_tokens tokens of Du dims."""
+    return (n_tokens + 7) // 8 * 8 * Du
+
+
+def keep_rows_from_tok8(t: torch.Tensor, n_tokens: int, Du: int) -> torch.Tensor:
+    """View helper for tests: [..., ceil(n/8), Du, 8] slab -> [..., n, Du] rows."""
+    lead = t.shape[:-1]
+    g = (n_tokens + 7) // 8
+    x = t.reshape(*lead, g, Du, 8).transpose(-1, -2).reshape(*lead, g * 8, Du)
+    return x[..., :n_tokens, :]
+
+
+def fa_compress(x, dim_mask, Dc, M, T, t0=0, accumulate=False, coeffs=None, x_keep=None,
+                keep_layout=FA_KEEP_ROWS, keep_offset=0, keep_stride_bh=0,
+                workspace=None, stream=None):
+    """Enqueue fa_compress on `stream`.
+
+    x [B,H,N,D] (last dim contiguous), dim_mask uint8 [B,H,D].  Allocates the
+    outputs / workspace with torch when they are not passed.  Returns
+    (coeffs [B,H,M,Dc] fp32, x_keep).
+    """
+    B, H, N, D = x.shape
+    assert x.stride(3) == 1 or N == 0
+    dev = x.device
+    if coeffs is None:
+        coeffs = torch.empty((B, H, M, Dc), dtype=torch.float32, device=dev)
+    Du = D - Dc
+    if x_keep is None:
+        n_tok = keep_offset + N
+        if keep_layout == FA_KEEP_ROWS:
+            x_keep = torch.empty((B, H, n_tok, Du), dtype=x.dtype, device=dev)
+        else:
+            x_keep = torch.zeros((B, H, tok8_numel(n_tok, Du)), dtype=x.dtype, device=dev)
+    need = compress_workspace_bytes(B, H, N, D, Dc, M)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    st = lib.fa_compress(_ptr(x), _dtype_code(x), x.stride(0), x.stride(1), x.stride(2),
+                         B, H, N, D, _ptr(dim_mask), Dc, M, T, t0, int(bool(accumulate)),
+                         _ptr(coeffs), _ptr(x_keep), keep_layout, keep_stride_bh, keep_offset,
+                         _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    if st != FA_OK:
+        raise FourierAttnError(st, "fa_compress")
+    return coeffs, x_keep
+
+
+def fa_decode(q, ck, kmask, cv, vmask, M, T, t0, N, k_keep, v_keep, k_full, v_full,
+              scale=0.0, num_splits=0, out=None, workspace=None, stream=None,
+              kk_stride_bh=0, vk_stride_bh=0, full_stride_bh=0):
+    """Enqueue fa_decode on `stream`; returns out [B,Hq,D] fp32."""
+    B, Hq, D = q.shape
+    Hkv = kmask.shape[1]
+    Dkc = ck.shape[-1] if ck is not None else 0
+    Dvc = cv.shape[-1] if cv is not None else 0
+    W = k_full.shape[2] if k_full is not None else 0
+    dev = q.device
+    if out is None:
+        out = torch.empty((B, Hq, D), dtype=torch.float32, device=dev)
+    if workspace is None:
+        need = decode_workspace_bytes(B, Hq, Hkv, D, Dkc, Dvc, M, N, W, num_splits)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    st = lib.fa_decode(_ptr(q), _dtype_code(q), B, Hq, Hkv, D,
+                       _ptr(ck), _ptr(kmask), Dkc, _ptr(cv), _ptr(vmask), Dvc,
+                       M, T, t0, N, _ptr(k_keep), kk_stride_bh, _ptr(v_keep), vk_stride_bh,
+                       _ptr(k_full), _ptr(v_full), W, full_stride_bh,
+                       float(scale), num_splits, _ptr(out),
+                       _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    if st != FA_OK:
+        raise FourierAttnError(st, "fa_decode")
+    return out

@@ -1,0 +1,88 @@
+"""The C-ABI library loads, exports every declared symbol and rejects bad
+arguments on the host without touching a device (no compute calls here)."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _fa():
+    import paper_2506_11886_amd as fa
+    return fa
+
+
+def test_library_exports_every_declared_symbol():
+    fa = _fa()
+    hdr = open(os.path.join(ROOT, "include", "fourier_attn.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(fa_[a-z_0-9]+)\s*\(", hdr))
+    assert {"fa_compress", "fa_decode", "fa_compress_workspace_bytes",
+            "fa_decode_workspace_bytes", "fa_decode_default_splits", "fa_status_string"} <= names
+    for n in names:
+        assert hasattr(fa.lib, n), n
+
+
+def test_status_strings():
+    fa = _fa()
+    assert fa.status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -5, -99):
+        assert fa.status_string(code)
+
+
+FAKE = ctypes.c_void_p(0x10000)   # never dereferenced: validation fails first
+
+
+def _decode(fa, **kw):
+    a = dict(q=FAKE, dtype=1, B=1, Hq=8, Hkv=2, D=128, ck=FAKE, kmask=FAKE, Dkc=96, cv=FAKE,
+             vmask=FAKE, Dvc=96, M=32, T=512, t0=0, N=512, k_keep=FAKE, kks=0, v_keep=FAKE, vks=0,
+             k_full=FAKE, v_full=FAKE, W=16, fs=0, scale=0.0, splits=0, out=FAKE, ws=FAKE,
+             ws_bytes=0, stream=None)
+    a.update(kw)
+    return fa.lib.fa_decode(a["q"], a["dtype"], a["B"], a["Hq"], a["Hkv"], a["D"], a["ck"], a["kmask"],
+                            a["Dkc"], a["cv"], a["vmask"], a["Dvc"], a["M"], a["T"], a["t0"], a["N"],
+                            a["k_keep"], a["kks"], a["v_keep"], a["vks"], a["k_full"], a["v_full"],
+                            a["W"], a["fs"], a["scale"], a["splits"], a["out"], a["ws"], a["ws_bytes"],
+                            a["stream"])
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(Hq=7), -2), (dict(Dkc=129), -2), (dict(M=0), -2), (dict(M=600), -2),
+    (dict(t0=1), -2), (dict(N=0, W=0), -2), (dict(D=100), -3), (dict(Hq=64, Hkv=2), -3),
+    (dict(dtype=7), -3), (dict(q=None), -1), (dict(ck=None), -1), (dict(k_full=None), -1),
+    (dict(out=None), -1), (dict(ws_bytes=16), -4), (dict(kks=5), -2), (dict(splits=-1), -2),
+])
+def test_decode_rejects_bad_arguments(kw, code):
+    assert _decode(_fa(), **kw) == code
+
+
+def _compress(fa, **kw):
+    a = dict(x=FAKE, dtype=1, sb=8 * 512 * 128, sh=512 * 128, sn=128, B=1, H=8, N=512, D=128,
+             mask=FAKE, Dc=96, M=32, T=512, t0=0, acc=0, coeffs=FAKE, keep=FAKE, layout=0, ks=0,
+             koff=0, ws=FAKE, ws_bytes=0, stream=None)
+    a.update(kw)
+    return fa.lib.fa_compress(a["x"], a["dtype"], a["sb"], a["sh"], a["sn"], a["B"], a["H"], a["N"],
+                              a["D"], a["mask"], a["Dc"], a["M"], a["T"], a["t0"], a["acc"], a["coeffs"],
+                              a["keep"], a["layout"], a["ks"], a["koff"], a["ws"], a["ws_bytes"],
+                              a["stream"])
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(Dc=200), -2), (dict(M=513), -2), (dict(t0=4), -2), (dict(sn=100), -2), (dict(sn=132), -2),
+    (dict(layout=3), -2), (dict(koff=-1), -2), (dict(D=100, Dc=50), -3), (dict(M=2000, T=4000), -3),
+    (dict(x=None), -1), (dict(mask=None), -1), (dict(coeffs=None), -1), (dict(ws_bytes=8), -4),
+    (dict(x=ctypes.c_void_p(0x10004)), -2),
+])
+def test_compress_rejects_bad_arguments(kw, code):
+    assert _compress(_fa(), **kw) == code
+
+
+def test_workspace_queries():
+    fa = _fa()
+    assert fa.decode_workspace_bytes(1, 32, 8, 128, 96, 96, 256, 31740, 1028, 0) > 0
+    assert fa.decode_workspace_bytes(1, 7, 2, 128, 96, 96, 256, 100, 10, 0) == 0
+    assert fa.compress_workspace_bytes(8, 32, 4096, 128, 96, 256) >= 256
+    assert fa.decode_default_splits(1, 8, 31740) >= 1

@@ -1,0 +1,155 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 oracle.
+
+Tolerances (the benchmark spec): max |gpu - oracle| / max |oracle| per tensor
+<= 2e-3 for bf16 inputs (fp32 accumulation), <= 1e-5 for fp32 inputs.
+Kept dimensions are a copy and must be bit-exact.
+"""
+
+import numpy as np
+import pytest
+import torch
+
+from workloads import CONFIGS, rel_err, small_variants
+from fa_testlib import (cached_context, oracle_decode_heads, oracle_state, rows_to_tok8,
+                        sample_heads, to_dev)
+
+pytestmark = pytest.mark.gpu
+
+
+def _fa():
+    import paper_2506_11886_amd as fa
+    return fa
+
+
+def _gpu_compress(cfg, ctx):
+    fa = _fa()
+    k_mid, v_mid = to_dev(ctx["k_mid"], cfg), to_dev(ctx["v_mid"], cfg)
+    kmask, vmask = to_dev(ctx["kmask"]), to_dev(ctx["vmask"])
+    ck, kk = fa.fa_compress(k_mid, kmask, cfg.Dkc, cfg.M, cfg.T, keep_layout=fa.FA_KEEP_ROWS)
+    cv, vk = fa.fa_compress(v_mid, vmask, cfg.Dvc, cfg.M, cfg.T, keep_layout=fa.FA_KEEP_TOK8)
+    torch.cuda.synchronize()
+    return ck, kk, cv, vk, kmask, vmask
+
+
+def _check_compress(cfg, heads):
+    fa = _fa()
+    ctx = cached_context(cfg)
+    st = oracle_state(cfg, ctx, heads)
+    ck, kk, cv, vk, _, _ = _gpu_compress(cfg, ctx)
+    ck, cv = ck.cpu().numpy(), cv.cpu().numpy()
+    kk = kk.float().cpu().numpy()
+    vk = fa.keep_rows_from_tok8(vk, cfg.N, cfg.D - cfg.Dvc).float().cpu().numpy()
+    for b, h in heads:
+        # A coefficient is a sum of N terms of size ~rms(x): it cannot be resolved
+        # below eps * sqrt(N) * rms(x) however small the exact sum is, so that
+        # scale bounds the denominator (it only matters when the kept band misses
+        # the signal, e.g. M = 1 on a zero-mean sinusoid).
+        if cfg.Dkc and cfg.N:
+            xc = ctx["k_mid"][b, h][:, ctx["kmask"][b, h] == 1].astype(np.float64)
+            fl = np.sqrt(cfg.N * np.mean(xc ** 2))
+            assert rel_err(ck[b, h], st["ck"][b, h], fl) <= cfg.tol, ("ck", b, h)
+        if cfg.Dvc and cfg.N:
+            xc = ctx["v_mid"][b, h][:, ctx["vmask"][b, h] == 1].astype(np.float64)
+            fl = np.sqrt(cfg.N * np.mean(xc ** 2))
+            assert rel_err(cv[b, h], st["cv"][b, h], fl) <= cfg.tol, ("cv", b, h)
+        assert np.array_equal(kk[b, h], st["kk"][b, h]), ("k_keep", b, h)
+        assert np.array_equal(vk[b, h], st["vk"][b, h]), ("v_keep", b, h)
+    return ctx, st
+
+
+def _gpu_decode(cfg, ctx, ck, cv, kk_rows, vk_tok8, num_splits=None):
+    fa = _fa()
+    return fa.fa_decode(
+        to_dev(ctx["q"], cfg), ck, to_dev(ctx["kmask"]), cv, to_dev(ctx["vmask"]),
+        cfg.M, cfg.T, 0, cfg.N, kk_rows, vk_tok8,
+        to_dev(ctx["k_full"], cfg), to_dev(ctx["v_full"], cfg),
+        num_splits=cfg.num_splits if num_splits is None else num_splits)
+
+
+def _check_decode(cfg, heads, ctx=None, st=None, num_splits=None):
+    ctx = ctx or cached_context(cfg)
+    st = st or oracle_state(cfg, ctx, heads)
+    # decode is handed the oracle's coefficients (fp32) and exact kept dims
+    out = _gpu_decode(cfg, ctx, to_dev(st["ck32"]), to_dev(st["cv32"]),
+                      to_dev(st["kk"], cfg), to_dev(rows_to_tok8(st["vk"]), cfg), num_splits)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    want = oracle_decode_heads(cfg, ctx, st, heads)
+    G = cfg.G
+    for (b, h), w in want.items():
+        got = out[b, h * G:(h + 1) * G]
+        assert np.isfinite(got).all()
+        assert rel_err(got, w) <= cfg.tol, ("out", b, h, rel_err(got, w))
+
+
+SMALL = small_variants()
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+def test_compress_small(cfg):
+    print(f"[case] compress {cfg}", flush=True)
+    _check_compress(cfg, sample_heads(cfg, None))
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+def test_decode_small(cfg):
+    print(f"[case] decode {cfg}", flush=True)
+    _check_decode(cfg, sample_heads(cfg, None))
+
+
+@pytest.mark.parametrize("cfg", SMALL[:4], ids=[c.name for c in SMALL[:4]])
+def test_end_to_end_small(cfg):
+    """GPU compress feeding GPU decode against oracle compress -> oracle decode."""
+    print(f"[case] end-to-end {cfg}", flush=True)
+    ctx = cached_context(cfg)
+    heads = sample_heads(cfg, None)
+    st = oracle_state(cfg, ctx, heads)
+    ck, kk, cv, vk, _, _ = _gpu_compress(cfg, ctx)
+    out = _gpu_decode(cfg, ctx, ck, cv, kk, vk)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    want = oracle_decode_heads(cfg, ctx, st, heads, from_f32_coeffs=False)
+    for (b, h), w in want.items():
+        assert rel_err(out[b, h * cfg.G:(h + 1) * cfg.G], w) <= cfg.tol
+
+
+@pytest.mark.parametrize("splits", [1, 2, 7, 64])
+def test_decode_split_count_invariance(splits):
+    cfg = SMALL[3]
+    print(f"[case] split invariance {cfg.name} splits={splits}", flush=True)
+    _check_decode(cfg, sample_heads(cfg, None), num_splits=splits)
+
+
+FULL = {2: 3, 3: 6, 4: 2, 5: 8}   # config index -> number of (b, kv head) pairs the oracle checks
+
+
+@pytest.mark.parametrize("idx", sorted(FULL))
+def test_full_size_config(idx):
+    """BASELINE sizes in the launch configuration the benchmark times; the
+    oracle evaluates a sample of (sequence, KV head) pairs."""
+    cfg = CONFIGS[idx - 1]
+    print(f"[case] full-size {cfg}", flush=True)
+    heads = sample_heads(cfg, FULL[idx], seed=idx)
+    ctx, st = _check_compress(cfg, heads)
+    print("[case] full-size compress ok, decode next", flush=True)
+    _check_decode(cfg, heads, ctx, st)
+
+
+def test_compress_streaming_update_matches_one_shot():
+    """Eq. 5: appending tokens one chunk at a time equals compressing at once."""
+    fa = _fa()
+    cfg = SMALL[2]
+    ctx = cached_context(cfg)
+    x = to_dev(ctx["k_mid"], cfg)
+    mask = to_dev(ctx["kmask"])
+    full, keep_full = fa.fa_compress(x, mask, cfg.Dkc, cfg.M, cfg.T)
+    a = 500
+    slab = keep_full.stride(1)
+    c, keep = fa.fa_compress(x[:, :, :a], mask, cfg.Dkc, cfg.M, cfg.T,
+                             x_keep=torch.zeros_like(keep_full), keep_stride_bh=slab)
+    for j0, j1 in ((a, a + 1), (a + 1, a + 2), (a + 2, cfg.N)):
+        fa.fa_compress(x[:, :, j0:j1], mask, cfg.Dkc, cfg.M, cfg.T, t0=j0, accumulate=True,
+                       coeffs=c, x_keep=keep, keep_offset=j0, keep_stride_bh=slab)
+    torch.cuda.synchronize()
+    assert rel_err(c.cpu().numpy(), full.cpu().numpy()) <= 1e-5
+    assert torch.equal(keep, keep_full)

@@ -109,16 +109,18 @@ def make_context(cfg):
     }
 
 
-def rel_err(got, want) -> float:
+def rel_err(got, want, floor: float = 0.0) -> float:
     """max |got - want| / max |want| over one tensor: the parity metric.
 
     Elementwise relative error is meaningless for entries that are ~0
     (out-of-band coefficients, near-cancelling outputs), so the error is
-    normalised by the largest magnitude of the reference tensor.
+    normalised by the largest magnitude of the reference tensor.  `floor`
+    bounds the denominator from below for tensors that are small only through
+    cancellation (e.g. a band that misses every component of the signal).
     """
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
-    denom = float(np.max(np.abs(want))) if want.size else 0.0
+    denom = max(float(np.max(np.abs(want))) if want.size else 0.0, float(floor))
     if denom == 0.0:
         return float(np.max(np.abs(got))) if got.size else 0.0
     return float(np.max(np.abs(got - want)) / denom)
