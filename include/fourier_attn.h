@@ -137,6 +137,38 @@ int fa_decode(const void* q, int dtype,
 size_t fa_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int Dkc, int Dvc,
                                  int M, int N, int W, int num_splits);
 
+/*
+ * Measurement aids.  Same arguments and effect as fa_compress / fa_decode, but
+ * synchronous: HIP events are recorded on `hip_stream` around every kernel of
+ * the call, the call waits for the last one, and the per-kernel durations in
+ * milliseconds are written to `kernel_ms`, a HOST array:
+ *   fa_compress_timed: 2 floats (projection, chunk reduction)
+ *   fa_decode_timed  : 3 floats (prepare, per-chunk partial, finish)
+ * A kernel that was not launched for these sizes reports ~0.
+ */
+int fa_compress_timed(const void* x, int dtype,
+                      int64_t sx_b, int64_t sx_h, int64_t sx_n,
+                      int B, int H, int N, int D,
+                      const uint8_t* dim_mask, int Dc,
+                      int M, int T, int t0, int accumulate,
+                      float* coeffs,
+                      void* x_keep, int keep_layout, int64_t keep_stride_bh, int keep_offset,
+                      void* workspace, size_t workspace_bytes, void* hip_stream,
+                      float* kernel_ms);
+
+int fa_decode_timed(const void* q, int dtype,
+                    int B, int Hq, int Hkv, int D,
+                    const float* ck, const uint8_t* kmask, int Dkc,
+                    const float* cv, const uint8_t* vmask, int Dvc,
+                    int M, int T, int t0, int N,
+                    const void* k_keep, int64_t kk_stride_bh,
+                    const void* v_keep, int64_t vk_stride_bh,
+                    const void* k_full, const void* v_full, int W, int64_t full_stride_bh,
+                    float scale, int num_splits,
+                    float* out,
+                    void* workspace, size_t workspace_bytes, void* hip_stream,
+                    float* kernel_ms);
+
 /* Number of middle-row chunks fa_decode will use for these sizes when
  * num_splits = 0 (exposed so callers can size and report). */
 int fa_decode_default_splits(int B, int Hkv, int N);

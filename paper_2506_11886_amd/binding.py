@@ -36,12 +36,16 @@ def _load():
     lib.fa_compress.restype = i32
     lib.fa_compress.argtypes = [vp, i32, i64, i64, i64, i32, i32, i32, i32, vp, i32,
                                 i32, i32, i32, i32, vp, vp, i32, i64, i32, vp, sz, vp]
+    lib.fa_compress_timed.restype = i32
+    lib.fa_compress_timed.argtypes = lib.fa_compress.argtypes + [c.POINTER(c.c_float)]
     lib.fa_compress_workspace_bytes.restype = sz
     lib.fa_compress_workspace_bytes.argtypes = [i32] * 6
     lib.fa_decode.restype = i32
     lib.fa_decode.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp, i32,
                               i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, i32, i64,
                               f32, i32, vp, vp, sz, vp]
+    lib.fa_decode_timed.restype = i32
+    lib.fa_decode_timed.argtypes = lib.fa_decode.argtypes + [c.POINTER(c.c_float)]
     lib.fa_decode_workspace_bytes.restype = sz
     lib.fa_decode_workspace_bytes.argtypes = [i32] * 10
     lib.fa_decode_default_splits.restype = i32
@@ -103,12 +107,13 @@ def keep_rows_from_tok8(t: torch.Tensor, n_tokens: int, Du: int) -> torch.Tensor
 
 def fa_compress(x, dim_mask, Dc, M, T, t0=0, accumulate=False, coeffs=None, x_keep=None,
                 keep_layout=FA_KEEP_ROWS, keep_offset=0, keep_stride_bh=0,
-                workspace=None, stream=None):
+                workspace=None, stream=None, kernel_ms=None):
     """Enqueue fa_compress on `stream`.
 
     x [B,H,N,D] (last dim contiguous), dim_mask uint8 [B,H,D].  Allocates the
     outputs / workspace with torch when they are not passed.  Returns
-    (coeffs [B,H,M,Dc] fp32, x_keep).
+    (coeffs [B,H,M,Dc] fp32, x_keep).  With `kernel_ms` (a list) the timed,
+    synchronous entry point is used and the per-kernel milliseconds appended.
     """
     B, H, N, D = x.shape
     assert x.stride(3) == 1 or N == 0
@@ -125,10 +130,16 @@ def fa_compress(x, dim_mask, Dc, M, T, t0=0, accumulate=False, coeffs=None, x_ke
     need = compress_workspace_bytes(B, H, N, D, Dc, M)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
-    st = lib.fa_compress(_ptr(x), _dtype_code(x), x.stride(0), x.stride(1), x.stride(2),
-                         B, H, N, D, _ptr(dim_mask), Dc, M, T, t0, int(bool(accumulate)),
-                         _ptr(coeffs), _ptr(x_keep), keep_layout, keep_stride_bh, keep_offset,
-                         _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    args = (_ptr(x), _dtype_code(x), x.stride(0), x.stride(1), x.stride(2),
+            B, H, N, D, _ptr(dim_mask), Dc, M, T, t0, int(bool(accumulate)),
+            _ptr(coeffs), _ptr(x_keep), keep_layout, keep_stride_bh, keep_offset,
+            _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    if kernel_ms is None:
+        st = lib.fa_compress(*args)
+    else:
+        ms = (ctypes.c_float * 2)()
+        st = lib.fa_compress_timed(*args, ms)
+        kernel_ms.extend(ms)
     if st != FA_OK:
         raise FourierAttnError(st, "fa_compress")
     return coeffs, x_keep
@@ -136,8 +147,10 @@ def fa_compress(x, dim_mask, Dc, M, T, t0=0, accumulate=False, coeffs=None, x_ke
 
 def fa_decode(q, ck, kmask, cv, vmask, M, T, t0, N, k_keep, v_keep, k_full, v_full,
               scale=0.0, num_splits=0, out=None, workspace=None, stream=None,
-              kk_stride_bh=0, vk_stride_bh=0, full_stride_bh=0):
-    """Enqueue fa_decode on `stream`; returns out [B,Hq,D] fp32."""
+              kk_stride_bh=0, vk_stride_bh=0, full_stride_bh=0, kernel_ms=None):
+    """Enqueue fa_decode on `stream`; returns out [B,Hq,D] fp32.  With
+    `kernel_ms` (a list) the timed, synchronous entry point is used and the
+    per-kernel milliseconds (prepare, partial, finish) appended."""
     B, Hq, D = q.shape
     Hkv = kmask.shape[1]
     Dkc = ck.shape[-1] if ck is not None else 0
@@ -149,12 +162,18 @@ def fa_decode(q, ck, kmask, cv, vmask, M, T, t0, N, k_keep, v_keep, k_full, v_fu
     if workspace is None:
         need = decode_workspace_bytes(B, Hq, Hkv, D, Dkc, Dvc, M, N, W, num_splits)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
-    st = lib.fa_decode(_ptr(q), _dtype_code(q), B, Hq, Hkv, D,
-                       _ptr(ck), _ptr(kmask), Dkc, _ptr(cv), _ptr(vmask), Dvc,
-                       M, T, t0, N, _ptr(k_keep), kk_stride_bh, _ptr(v_keep), vk_stride_bh,
-                       _ptr(k_full), _ptr(v_full), W, full_stride_bh,
-                       float(scale), num_splits, _ptr(out),
-                       _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    args = (_ptr(q), _dtype_code(q), B, Hq, Hkv, D,
+            _ptr(ck), _ptr(kmask), Dkc, _ptr(cv), _ptr(vmask), Dvc,
+            M, T, t0, N, _ptr(k_keep), kk_stride_bh, _ptr(v_keep), vk_stride_bh,
+            _ptr(k_full), _ptr(v_full), W, full_stride_bh,
+            float(scale), num_splits, _ptr(out),
+            _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    if kernel_ms is None:
+        st = lib.fa_decode(*args)
+    else:
+        ms = (ctypes.c_float * 3)()
+        st = lib.fa_decode_timed(*args, ms)
+        kernel_ms.extend(ms)
     if st != FA_OK:
         raise FourierAttnError(st, "fa_decode")
     return out

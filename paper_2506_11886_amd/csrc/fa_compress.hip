@@ -292,10 +292,11 @@ size_t fa_compress_workspace_bytes(int B, int H, int N, int D, int Dc, int M) {
   return t ? t : 256;
 }
 
-int fa_compress(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n, int B, int H,
-                int N, int D, const uint8_t* dim_mask, int Dc, int M, int T, int t0, int accumulate,
-                float* coeffs, void* x_keep, int keep_layout, int64_t keep_stride_bh,
-                int keep_offset, void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n, int B,
+                         int H, int N, int D, const uint8_t* dim_mask, int Dc, int M, int T, int t0,
+                         int accumulate, float* coeffs, void* x_keep, int keep_layout,
+                         int64_t keep_stride_bh, int keep_offset, void* workspace,
+                         size_t workspace_bytes, void* hip_stream, hipEvent_t* ev) {
   using namespace fa;
   const int st = check_compress_shapes(dtype, B, H, N, D, Dc, M, T, t0);
   if (st != FA_OK) return st;
@@ -330,17 +331,50 @@ int fa_compress(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const size_t total = static_cast<size_t>(B) * H * M * Dc;
+  if (ev) (void)hipEventRecord(ev[0], stream);
   if (pl.Sc > 0) {
     dim3 grid(pl.Sc, pl.MC * pl.DCn, B * H);
     if (dtype == FA_F32) hipLaunchKernelGGL(compress_project<float>, grid, dim3(kCBlock), 0, stream, p);
     else hipLaunchKernelGGL(compress_project<bf16_t>, grid, dim3(kCBlock), 0, stream, p);
   }
+  if (ev) (void)hipEventRecord(ev[1], stream);
   if (total > 0 && (pl.Sc > 1 || (pl.Sc == 0 && !accumulate))) {
     const unsigned blocks = static_cast<unsigned>((total + 255) / 256);
     hipLaunchKernelGGL(compress_reduce, dim3(blocks), dim3(256), 0, stream, p.part, coeffs, total,
                        pl.Sc, p.accumulate);
   }
+  if (ev) (void)hipEventRecord(ev[2], stream);
   return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
+}
+
+int fa_compress(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n, int B, int H,
+                int N, int D, const uint8_t* dim_mask, int Dc, int M, int T, int t0, int accumulate,
+                float* coeffs, void* x_keep, int keep_layout, int64_t keep_stride_bh,
+                int keep_offset, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return compress_impl(x, dtype, sx_b, sx_h, sx_n, B, H, N, D, dim_mask, Dc, M, T, t0, accumulate,
+                       coeffs, x_keep, keep_layout, keep_stride_bh, keep_offset, workspace,
+                       workspace_bytes, hip_stream, nullptr);
+}
+
+int fa_compress_timed(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n, int B,
+                      int H, int N, int D, const uint8_t* dim_mask, int Dc, int M, int T, int t0,
+                      int accumulate, float* coeffs, void* x_keep, int keep_layout,
+                      int64_t keep_stride_bh, int keep_offset, void* workspace,
+                      size_t workspace_bytes, void* hip_stream, float* kernel_ms) {
+  if (!kernel_ms) return FA_ERR_NULL;
+  hipEvent_t ev[3];
+  for (int i = 0; i < 3; ++i)
+    if (hipEventCreate(&ev[i]) != hipSuccess) return FA_ERR_HIP;
+  int st = compress_impl(x, dtype, sx_b, sx_h, sx_n, B, H, N, D, dim_mask, Dc, M, T, t0, accumulate,
+                         coeffs, x_keep, keep_layout, keep_stride_bh, keep_offset, workspace,
+                         workspace_bytes, hip_stream, ev);
+  if (st == FA_OK) {
+    if (hipEventSynchronize(ev[2]) != hipSuccess) st = FA_ERR_HIP;
+    for (int i = 0; i < 2 && st == FA_OK; ++i)
+      if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = FA_ERR_HIP;
+  }
+  for (int i = 0; i < 3; ++i) (void)hipEventDestroy(ev[i]);
+  return st;
 }
 
 const char* fa_status_string(int status) {

@@ -430,16 +430,21 @@ static int check_decode_shapes(int dtype, int B, int Hq, int Hkv, int D, int Dkc
   return FA_OK;
 }
 
+// ev (optional): 4 events recorded before/after each kernel, for fa_decode_timed
 template <typename T>
-static int launch_decode(const DecodeParams& p, hipStream_t st) {
+static int launch_decode(const DecodeParams& p, hipStream_t st, hipEvent_t* ev) {
   const int BH = p.B * p.Hkv;
+  if (ev) (void)hipEventRecord(ev[0], st);
   if (p.Sm > 0) {
     dim3 g1((p.M + kPrepRows - 1) / kPrepRows, BH);
     hipLaunchKernelGGL(decode_prepare<T>, g1, dim3(kBlock), 0, st, p);
   }
+  if (ev) (void)hipEventRecord(ev[1], st);
   dim3 g2(p.Sw + p.Sm, BH);
   hipLaunchKernelGGL(decode_partial<T>, g2, dim3(kBlock), 0, st, p);
+  if (ev) (void)hipEventRecord(ev[2], st);
   hipLaunchKernelGGL(decode_finish<T>, dim3(BH), dim3(kBlock), 0, st, p);
+  if (ev) (void)hipEventRecord(ev[3], st);
   return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
 }
 
@@ -461,12 +466,13 @@ size_t fa_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int Dkc, int Dvc
   return fa::make_plan(B, Hq, Hkv, D, M, N, W, num_splits).total;
 }
 
-int fa_decode(const void* q, int dtype, int B, int Hq, int Hkv, int D, const float* ck,
-              const uint8_t* kmask, int Dkc, const float* cv, const uint8_t* vmask, int Dvc, int M,
-              int T, int t0, int N, const void* k_keep, int64_t kk_stride_bh, const void* v_keep,
-              int64_t vk_stride_bh, const void* k_full, const void* v_full, int W,
-              int64_t full_stride_bh, float scale, int num_splits, float* out, void* workspace,
-              size_t workspace_bytes, void* hip_stream) {
+static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, const float* ck,
+                       const uint8_t* kmask, int Dkc, const float* cv, const uint8_t* vmask, int Dvc,
+                       int M, int T, int t0, int N, const void* k_keep, int64_t kk_stride_bh,
+                       const void* v_keep, int64_t vk_stride_bh, const void* k_full,
+                       const void* v_full, int W, int64_t full_stride_bh, float scale,
+                       int num_splits, float* out, void* workspace, size_t workspace_bytes,
+                       void* hip_stream, hipEvent_t* ev) {
   using namespace fa;
   const int st = check_decode_shapes(dtype, B, Hq, Hkv, D, Dkc, Dvc, M, T, t0, N, W, num_splits);
   if (st != FA_OK) return st;
@@ -503,7 +509,41 @@ int fa_decode(const void* q, int dtype, int B, int Hq, int Hkv, int D, const flo
   p.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + pl.off_part);
   p.out = out;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  return dtype == FA_F32 ? launch_decode<float>(p, stream) : launch_decode<bf16_t>(p, stream);
+  return dtype == FA_F32 ? launch_decode<float>(p, stream, ev) : launch_decode<bf16_t>(p, stream, ev);
+}
+
+int fa_decode(const void* q, int dtype, int B, int Hq, int Hkv, int D, const float* ck,
+              const uint8_t* kmask, int Dkc, const float* cv, const uint8_t* vmask, int Dvc, int M,
+              int T, int t0, int N, const void* k_keep, int64_t kk_stride_bh, const void* v_keep,
+              int64_t vk_stride_bh, const void* k_full, const void* v_full, int W,
+              int64_t full_stride_bh, float scale, int num_splits, float* out, void* workspace,
+              size_t workspace_bytes, void* hip_stream) {
+  return decode_impl(q, dtype, B, Hq, Hkv, D, ck, kmask, Dkc, cv, vmask, Dvc, M, T, t0, N, k_keep,
+                     kk_stride_bh, v_keep, vk_stride_bh, k_full, v_full, W, full_stride_bh, scale,
+                     num_splits, out, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+int fa_decode_timed(const void* q, int dtype, int B, int Hq, int Hkv, int D, const float* ck,
+                    const uint8_t* kmask, int Dkc, const float* cv, const uint8_t* vmask, int Dvc,
+                    int M, int T, int t0, int N, const void* k_keep, int64_t kk_stride_bh,
+                    const void* v_keep, int64_t vk_stride_bh, const void* k_full,
+                    const void* v_full, int W, int64_t full_stride_bh, float scale, int num_splits,
+                    float* out, void* workspace, size_t workspace_bytes, void* hip_stream,
+                    float* kernel_ms) {
+  if (!kernel_ms) return FA_ERR_NULL;
+  hipEvent_t ev[4];
+  for (int i = 0; i < 4; ++i)
+    if (hipEventCreate(&ev[i]) != hipSuccess) return FA_ERR_HIP;
+  int st = decode_impl(q, dtype, B, Hq, Hkv, D, ck, kmask, Dkc, cv, vmask, Dvc, M, T, t0, N, k_keep,
+                       kk_stride_bh, v_keep, vk_stride_bh, k_full, v_full, W, full_stride_bh, scale,
+                       num_splits, out, workspace, workspace_bytes, hip_stream, ev);
+  if (st == FA_OK) {
+    if (hipEventSynchronize(ev[3]) != hipSuccess) st = FA_ERR_HIP;
+    for (int i = 0; i < 3 && st == FA_OK; ++i)
+      if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = FA_ERR_HIP;
+  }
+  for (int i = 0; i < 4; ++i) (void)hipEventDestroy(ev[i]);
+  return st;
 }
 
 }  // extern "C"
