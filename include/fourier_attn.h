@@ -62,7 +62,8 @@ enum { FA_KEEP_ROWS = 0, FA_KEEP_TOK8 = 1 };
 /* compiled limits */
 #define FA_MAX_HEAD_DIM 256   /* D, must be a multiple of 8                     */
 #define FA_MAX_GROUP 16       /* query heads per KV head                         */
-#define FA_MAX_STATES 1024    /* M                                               */
+#define FA_MAX_STATES 1024    /* M accepted by fa_compress                        */
+#define FA_MAX_DECODE_STATES 512 /* M accepted by fa_decode (256 for FA_F32)       */
 #define FA_MAX_SPLITS 256     /* token-axis chunks of fa_decode                  */
 
 /*
@@ -171,7 +172,7 @@ int fa_decode_timed(const void* q, int dtype,
 
 /* Number of middle-row chunks fa_decode will use for these sizes when
  * num_splits = 0 (exposed so callers can size and report). */
-int fa_decode_default_splits(int B, int Hkv, int N);
+int fa_decode_default_splits(int B, int Hq, int Hkv, int N);
 
 /* Static description of a status code (never NULL). */
 const char* fa_status_string(int status);
