@@ -78,7 +78,7 @@ def main():
         s = {k: v.clone() for k, v in master.items()}
         s["ck"] = torch.empty((B, Hkv, M, cfg.Dkc), dtype=torch.float32, device="cuda")
         s["cv"] = torch.empty((B, Hkv, M, cfg.Dvc), dtype=torch.float32, device="cuda")
-        s["kk"] = torch.empty((B, Hkv, N, Dku), dtype=dt, device="cuda")
+        s["kk"] = torch.empty((B, Hkv, N, fa.keep_rows_pitch(Dku)), dtype=dt, device="cuda")
         s["vk"] = torch.zeros((B, Hkv, fa.tok8_numel(N, Dvu)), dtype=dt, device="cuda")
         s["out"] = torch.empty((B, Hq, D), dtype=torch.float32, device="cuda")
         sets.append(s)

@@ -54,7 +54,8 @@ enum {
 enum { FA_F32 = 0, FA_BF16 = 1 };
 
 /* layout of the packed kept dimensions (K^mu / V^mu of Eq. 2), Du = D - Dc columns
- *   FA_KEEP_ROWS  [n_tokens, Du]            one row per token  (what fa_decode reads for K)
+ *   FA_KEEP_ROWS  [n_tokens, Dup]           one row per token, Dup = Du rounded up to a
+ *                 multiple of 8; pad columns hold zeros (what fa_decode reads for K)
  *   FA_KEEP_TOK8  [ceil(n_tokens/8), Du, 8] eight consecutive tokens of one
  *                 dimension are contiguous    (what fa_decode reads for V)   */
 enum { FA_KEEP_ROWS = 0, FA_KEEP_TOK8 = 1 };

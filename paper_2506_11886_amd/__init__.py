@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     FourierAttnError, lib, library_path, status_string,
     compress_workspace_bytes, decode_workspace_bytes, decode_default_splits,
     fa_compress, fa_decode,
-    keep_rows_from_tok8, tok8_numel,
+    keep_rows_from_tok8, tok8_numel, keep_rows_pitch,
 )

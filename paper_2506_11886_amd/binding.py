@@ -25,12 +25,12 @@ def library_path() -> str:
     return _LIB_PATH
 
 
-def _load():
-    if not os.path.exists(_LIB_PATH):
+def _load(path: str = _LIB_PATH):
+    if not os.path.exists(path):
         raise ImportError(
-            f"{_LIB_PATH} is missing: build it with `python -m paper_2506_11886_amd.build` "
+            f"{path} is missing: build it with `python -m paper_2506_11886_amd.build` "
             "(there is no fallback implementation)")
-    lib = ctypes.CDLL(_LIB_PATH)
+    lib = ctypes.CDLL(path)
     c = ctypes
     vp, i32, i64, f32, sz = c.c_void_p, c.c_int, c.c_int64, c.c_float, c.c_size_t
     lib.fa_compress.restype = i32
@@ -92,6 +92,11 @@ def decode_default_splits(B, Hq, Hkv, N) -> int:
     return int(lib.fa_decode_default_splits(B, Hq, Hkv, N))
 
 
+def keep_rows_pitch(Du: int) -> int:
+    """Row pitch (elements) of the FA_KEEP_ROWS layout: Du rounded up to 8."""
+    return (Du + 7) // 8 * 8
+
+
 def tok8_numel(n_tokens: int, Du: int) -> int:
     """Elements of one FA_KEEP_TOK8 slab holding n_tokens tokens of Du dims."""
     return (n_tokens + 7) // 8 * 8 * Du
@@ -124,7 +129,7 @@ def fa_compress(x, dim_mask, Dc, M, T, t0=0, accumulate=False, coeffs=None, x_ke
     if x_keep is None:
         n_tok = keep_offset + N
         if keep_layout == FA_KEEP_ROWS:
-            x_keep = torch.empty((B, H, n_tok, Du), dtype=x.dtype, device=dev)
+            x_keep = torch.empty((B, H, n_tok, keep_rows_pitch(Du)), dtype=x.dtype, device=dev)
         else:
             x_keep = torch.zeros((B, H, tok8_numel(n_tok, Du)), dtype=x.dtype, device=dev)
     need = compress_workspace_bytes(B, H, N, D, Dc, M)

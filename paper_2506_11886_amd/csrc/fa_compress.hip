@@ -40,6 +40,7 @@ struct CompressParams {
   float* coeffs;
   void* keep;
   int keep_layout;
+  int keep_pitch;   // FA_KEEP_ROWS: elements per row, Du rounded up to 8
   int64_t keep_stride;
   int keep_offset;
   int Sc, chunk;  // token chunks and their length (multiple of kKT)
@@ -172,10 +173,18 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
         } else if (write_keep && j < jend) {
           const int64_t tok = static_cast<int64_t>(p.keep_offset) + j;
           const int64_t off = (p.keep_layout == FA_KEEP_ROWS)
-                                  ? tok * p.Du + cp
+                                  ? tok * p.keep_pitch + cp
                                   : ((tok >> 3) * p.Du + cp) * 8 + (tok & 7);
           keep[off] = v[e];
         }
+      }
+    }
+    if (write_keep && p.keep_layout == FA_KEEP_ROWS && p.keep_pitch > p.Du) {
+      const int npad = p.keep_pitch - p.Du;
+      for (int it = tid; it < kKT * npad; it += kCBlock) {
+        const int j = js + it / npad;
+        if (j < jend)
+          keep[(static_cast<int64_t>(p.keep_offset) + j) * p.keep_pitch + p.Du + it % npad] = zero_elem(keep);
       }
     }
     if (project) {
@@ -309,7 +318,8 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
     if (reinterpret_cast<uintptr_t>(x) & 15u) return FA_ERR_SHAPE;
   }
   const int64_t tokens = static_cast<int64_t>(keep_offset) + N;
-  const int64_t dense = (keep_layout == FA_KEEP_ROWS) ? tokens * Du : ((tokens + 7) / 8) * 8 * Du;
+  const int keep_pitch = (Du + 7) & ~7;
+  const int64_t dense = (keep_layout == FA_KEEP_ROWS) ? tokens * keep_pitch : ((tokens + 7) / 8) * 8 * Du;
   if (keep_stride_bh == 0) keep_stride_bh = dense;
   if (x_keep && keep_stride_bh < dense) return FA_ERR_SHAPE;
 
@@ -325,7 +335,7 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
   p.B = B; p.H = H; p.N = N; p.D = D; p.Dc = Dc; p.Du = Du; p.M = M; p.T = T; p.t0 = t0;
   p.accumulate = accumulate ? 1 : 0;
   p.mask = dim_mask; p.coeffs = coeffs;
-  p.keep = x_keep; p.keep_layout = keep_layout; p.keep_stride = keep_stride_bh; p.keep_offset = keep_offset;
+  p.keep = x_keep; p.keep_layout = keep_layout; p.keep_pitch = keep_pitch; p.keep_stride = keep_stride_bh; p.keep_offset = keep_offset;
   p.Sc = pl.Sc; p.chunk = pl.chunk; p.MC = pl.MC; p.DCn = pl.DCn; p.P = pl.P;
   p.part = static_cast<float*>(workspace);
 

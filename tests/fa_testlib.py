@@ -29,6 +29,15 @@ def rows_to_tok8(x: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(pad.reshape(*lead, g, 8, du).swapaxes(-1, -2)).reshape(*lead, g * du * 8)
 
 
+def rows_pad8(x: np.ndarray) -> np.ndarray:
+    """[..., n, Du] rows -> [..., n, Du rounded up to 8] with zero pad columns."""
+    *lead, n, du = x.shape
+    pitch = (du + 7) // 8 * 8
+    out = np.zeros((*lead, n, pitch), dtype=x.dtype)
+    out[..., :du] = x
+    return out
+
+
 def oracle_state(cfg, ctx, heads=None):
     """Oracle compression of the middle segment.  `heads`: list of (b, hkv) to
     evaluate (others left as zeros), None = all.  Coefficients are rounded to

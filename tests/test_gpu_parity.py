@@ -10,7 +10,7 @@ import pytest
 import torch
 
 from workloads import CONFIGS, rel_err, small_variants
-from fa_testlib import (cached_context, oracle_decode_heads, oracle_state, rows_to_tok8,
+from fa_testlib import (cached_context, oracle_decode_heads, oracle_state, rows_pad8, rows_to_tok8,
                         sample_heads, to_dev)
 
 pytestmark = pytest.mark.gpu
@@ -38,6 +38,9 @@ def _check_compress(cfg, heads):
     ck, kk, cv, vk, _, _ = _gpu_compress(cfg, ctx)
     ck, cv = ck.cpu().numpy(), cv.cpu().numpy()
     kk = kk.float().cpu().numpy()
+    Dku = cfg.D - cfg.Dkc
+    assert kk.shape[-1] == fa.keep_rows_pitch(Dku) and not kk[..., Dku:].any()   # zero pad columns
+    kk = kk[..., :Dku]
     vk = fa.keep_rows_from_tok8(vk, cfg.N, cfg.D - cfg.Dvc).float().cpu().numpy()
     for b, h in heads:
         # A coefficient is a sum of N terms of size ~rms(x): it cannot be resolved
@@ -71,7 +74,7 @@ def _check_decode(cfg, heads, ctx=None, st=None, num_splits=None):
     st = st or oracle_state(cfg, ctx, heads)
     # decode is handed the oracle's coefficients (fp32) and exact kept dims
     out = _gpu_decode(cfg, ctx, to_dev(st["ck32"]), to_dev(st["cv32"]),
-                      to_dev(st["kk"], cfg), to_dev(rows_to_tok8(st["vk"]), cfg), num_splits)
+                      to_dev(rows_pad8(st["kk"]), cfg), to_dev(rows_to_tok8(st["vk"]), cfg), num_splits)
     torch.cuda.synchronize()
     out = out.cpu().numpy()
     want = oracle_decode_heads(cfg, ctx, st, heads)

@@ -117,6 +117,8 @@ def small_variants():
                 Dkc=96, Dvc=96, M=8, dtype="bf16"),
         replace(base, name="middle_only", index=17, B=1, Hq=4, Hkv=2, D=128, N=2100, Lw=0, Li=0,
                 Dkc=104, Dvc=88, M=200, dtype="bf16"),
+        replace(base, name="odd_dims", index=19, B=1, Hq=6, Hkv=2, D=128, N=900, Lw=33,
+                Dkc=91, Dvc=101, M=40, dtype="bf16"),
         replace(base, name="g2_m1", index=18, B=3, Hq=4, Hkv=2, D=64, N=130, Lw=7,
                 Dkc=8, Dvc=56, M=1, dtype="f32"),
     )
