@@ -4,21 +4,23 @@
 //   C[m,i] = sum_j phi_m(t0+j) X[j, idx_c[i]]         (a contraction over tokens)
 //   X_keep[j,i'] = X[j, idx_u[i']]                     (packed kept dimensions)
 //
-// One workgroup owns (sequence, head, token chunk, block of 256 basis rows,
-// block of 128 compressed columns).  Per 32-token step it
-//   * reads the [32, D] slab of X once with 128-bit loads, scatters the
-//     compressed columns transposed into LDS ([column][token]) and writes the
-//     kept columns straight to x_keep,
-//   * produces the [256, 32] slab of the basis in LDS by advancing per-thread
-//     (cos, sin) pairs with one complex rotation per entry (exact integer-
-//     reduced phases at the start of the chunk and every 32 steps),
-//   * issues 16x16x32 MFMAs with the basis slab as A and the X slab as B.
-// Token chunks are reduced in a second, deterministic pass.
+// The basis never exists as a matrix.  With j = tau + u (tau = start of a
+// 64-token block, u < 64) the angle-addition identity gives, per harmonic n,
+//   [C_cos; C_sin] = sum_blocks Rot(omega_n tau) [E_cos X_blk; E_sin X_blk],
+// where E[rho,u] = cos|sin(omega_n u) is a 64-column table that every wave keeps
+// in registers as its MFMA A operand for the whole kernel.  Instead of rotating
+// each block's product, the accumulators live in a frame that moves with the
+// blocks: before a block is added they are rotated by -omega_n * 64 (four FMAs
+// per (cos, sin) pair, in place in the MFMA accumulator registers), and once at
+// the end by the exact phase of the last block.
 //
-// Internal row order of the basis block (so that every (cos, sin) pair is two
-// adjacent rows owned by one thread): row 0 = constant, row 1 = cosine of order
-// M/2 when M is even (it has no sine partner in the kept set), rows 2n, 2n+1 =
-// cos, sin of order n for n = 1 .. (M-1)/2.
+// One workgroup owns (sequence, head, token chunk, 128 harmonics = 256 basis
+// rows, 128 compressed columns).  Per block it reads the [64, D] slab of X once
+// with 128-bit loads (the next slab is in flight while the current one is
+// multiplied), scatters the compressed columns transposed into LDS and the kept
+// columns into an LDS staging tile that is written out with 128-bit stores.
+// The constant function (m = 0) is a plain column sum.  Token chunks are reduced
+// in a second, deterministic pass.
 
 #include "fa_common.hpp"
 #include "fa_mma.hpp"
@@ -26,11 +28,11 @@
 namespace fa {
 
 constexpr int kCBlock = 256;
-constexpr int kKT = 32;         // tokens per MFMA step
-constexpr int kLd = kKT + 8;    // LDS row pitch in elements (keeps 16-byte alignment, spreads banks)
-constexpr int kRows = 256;      // basis rows per workgroup
-constexpr int kCols = 128;      // compressed columns per workgroup
-constexpr int kReanchor = 32;   // steps between exact re-evaluations of the rotating basis
+constexpr int kTB = 64;          // tokens per block
+constexpr int kLdX = kTB + 8;    // LDS pitch (elements) of a transposed column: 16-byte aligned, bank-spread
+constexpr int kPairs = 128;      // harmonics per workgroup (256 basis rows)
+constexpr int kCols = 128;       // compressed columns per workgroup
+constexpr unsigned kMaxCLds = 160 * 1024 - 8192;
 
 struct CompressParams {
   const void* x;
@@ -43,242 +45,426 @@ struct CompressParams {
   int keep_pitch;   // FA_KEEP_ROWS: elements per row, Du rounded up to 8
   int64_t keep_stride;
   int keep_offset;
-  int Sc, chunk;  // token chunks and their length (multiple of kKT)
-  int MC, DCn;    // row blocks, column blocks
-  int P;          // (M-1)/2 complete (cos, sin) pairs
-  float* part;    // [Sc][B*H][M][Dc] when Sc > 1
+  int stage_keep;   // kept dims go through an LDS tile and leave as 128-bit stores
+  int Sc, chunk;    // token chunks and their length (multiple of kTB)
+  int MC, DCn;      // row blocks (128 harmonics each), column blocks
+  int nmax;         // highest harmonic: M / 2
+  unsigned ks_elems;   // elements of one keep-staging buffer
+  double ph_scale;  // 2^32 / T
+  float* part;      // [Sc][part_stride] when Sc > 1, chunk s holds [B*H][M][Dc]
+  size_t part_stride;   // B*H*M*Dc rounded up to 4 floats
 };
 
-template <typename T> struct Pack16;
-template <> struct Pack16<bf16_t> {
-  // 16 consecutive tokens of one basis row -> two 128-bit LDS stores
-  __device__ static __forceinline__ void store(bf16_t* dst, const float* v) {
-    u32x4 a, b;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      a[e] = static_cast<uint32_t>(f32_to_bf16(v[2 * e])) |
-             (static_cast<uint32_t>(f32_to_bf16(v[2 * e + 1])) << 16);
-      b[e] = static_cast<uint32_t>(f32_to_bf16(v[8 + 2 * e])) |
-             (static_cast<uint32_t>(f32_to_bf16(v[8 + 2 * e + 1])) << 16);
-    }
-    *reinterpret_cast<u32x4*>(dst) = a;
-    *reinterpret_cast<u32x4*>(dst + 8) = b;
-  }
-};
-template <> struct Pack16<float> {
-  __device__ static __forceinline__ void store(float* dst, const float* v) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      *reinterpret_cast<f32x4*>(dst + 4 * e) = f32x4{v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]};
-  }
-};
-
-// 8 consecutive elements of a row of X (16-byte aligned)
-__device__ __forceinline__ void load8(const bf16_t* p, bf16_t* out) {
-  *reinterpret_cast<u32x4*>(out) = *reinterpret_cast<const u32x4*>(p);
+__device__ __forceinline__ void load8(const bf16_t* p, Frag<bf16_t>& f) { f.load(p); }
+__device__ __forceinline__ void load8(const float* p, Frag<float>& f) { f.load(p); }
+__device__ __forceinline__ bf16_t felem(const Frag<bf16_t>& f, int e) {
+  return bf16_t{static_cast<uint16_t>((f.v[e >> 1] >> (16 * (e & 1))) & 0xffffu)};
 }
-__device__ __forceinline__ void load8(const float* p, float* out) {
-  *reinterpret_cast<f32x4*>(out) = *reinterpret_cast<const f32x4*>(p);
-  *reinterpret_cast<f32x4*>(out + 4) = *reinterpret_cast<const f32x4*>(p + 4);
-}
+__device__ __forceinline__ float felem(const Frag<float>& f, int e) { return f.v[e]; }
+__device__ __forceinline__ float tof(bf16_t x) { return bf16_to_f32(x.bits); }
+__device__ __forceinline__ float tof(float x) { return x; }
 __device__ __forceinline__ bf16_t zero_elem(const bf16_t*) { return bf16_t{0}; }
 __device__ __forceinline__ float zero_elem(const float*) { return 0.0f; }
 
+// position -> phase in units of 2^-32 turns (wraps), and its cosine / sine.  An
+// integer multiple n * phase wraps exactly, so harmonics cost one multiply.
+__device__ __forceinline__ uint32_t fixed_phase(int pos, double ph_scale) {
+  return static_cast<uint32_t>(static_cast<uint64_t>(static_cast<double>(pos) * ph_scale));
+}
 template <typename T>
-__global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
-  __shared__ __attribute__((aligned(16))) T phi_s[kRows * kLd];
-  __shared__ __attribute__((aligned(16))) T xc_s[kCols * kLd];
-  __shared__ int16_t cpos[FA_MAX_HEAD_DIM];
-  __shared__ uint8_t mask_s[FA_MAX_HEAD_DIM];
+__device__ __forceinline__ void fixed_phase_cs(uint32_t ph, float* c, float* s) {
+  const float x = static_cast<float>(static_cast<int32_t>(ph)) * 2.3283064365386963e-10f;  // turns in [-0.5, 0.5)
+  if constexpr (sizeof(T) == 4) {
+    sincospif(2.0f * x, s, c);
+  } else {
+    *s = __builtin_amdgcn_sinf(x);
+    *c = __builtin_amdgcn_cosf(x);
+  }
+}
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+template <typename T>
+__device__ __forceinline__ void set_elem(Frag<T>& f, int e, float x);
+template <>
+__device__ __forceinline__ void set_elem<bf16_t>(Frag<bf16_t>& f, int e, float x) { f.set(e, x); }
+template <>
+__device__ __forceinline__ void set_elem<float>(Frag<float>& f, int e, float x) { f.v[e] = x; }
+
+// DT: 16-column tiles of compressed dims per workgroup; kXR: 8-element vectors of
+// X per thread and block (4 covers head dims up to 128, 8 up to 256)
+// kFast: the row vectors divide the workgroup evenly (head dim 64 / 128 / 256) and
+// kept dims are staged, so every thread routes the same 8 dims in every block.
+template <typename T, int DT, int kXR, bool kFast>
+__global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_project(CompressParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int16_t cpos[FA_MAX_HEAD_DIM];
+  __shared__ float dcred[kCBlock];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q4 = lane >> 4, r16 = lane & 15;
   const int s = blockIdx.x, mc = blockIdx.y % p.MC, dc = blockIdx.y / p.MC;
   const int bh = blockIdx.z, b = bh / p.H, h = bh % p.H;
-  const int D = p.D, M = p.M;
+  const int D = p.D, M = p.M, Du = p.Du;
   const int j0 = s * p.chunk, jend = min(p.N, j0 + p.chunk);
-  const bool write_keep = (blockIdx.y == 0) && p.keep != nullptr && p.Du > 0;
+  const int nb = (jend - j0 + kTB - 1) / kTB;
+  const bool write_keep = (blockIdx.y == 0) && p.keep != nullptr && Du > 0;
+  const bool stage = write_keep && p.stage_keep;
   const bool project = p.Dc > 0;
+  const bool do_dc = project && mc == 0;
 
-  // cpos[d]: >= 0 index among kept dims, < 0: -(1 + index among compressed dims)
-  for (int d = tid; d < D; d += kCBlock) mask_s[d] = p.mask[static_cast<size_t>(bh) * D + d] ? 1 : 0;
-  __syncthreads();
-  for (int d = tid; d < D; d += kCBlock) {
-    int nc = 0;
-    for (int e = 0; e < d; ++e) nc += mask_s[e];
-    cpos[d] = mask_s[d] ? static_cast<int16_t>(-(1 + nc)) : static_cast<int16_t>(d - nc);
+  // two buffers of [compressed columns kCols x kLdX | keep staging ks_elems | 8 spare elements]
+  T* lds = reinterpret_cast<T*>(smem);
+  const uint32_t bufe = kCols * kLdX + p.ks_elems + 8;      // elements per buffer
+
+  // ---- first X block is requested before anything else --------------------------------
+  const T* xbase = static_cast<const T*>(p.x) + b * p.sx_b + h * p.sx_h;
+  const int nch = D / 8;
+  const int nx = (kTB * nch + kCBlock - 1) / kCBlock;      // vectors per thread and block (<= kXR)
+  Frag<T> xr[kXR];
+  auto load_x = [&](int blk) {
+    const int js = j0 + blk * kTB;
+#pragma unroll
+    for (int i = 0; i < kXR; ++i) {
+      if (i < nx) {
+        const int it = tid + i * kCBlock;
+        const int jt = it / nch, ch = it % nch;
+        const int j = min(js + min(jt, kTB - 1), p.N - 1);
+        load8(xbase + static_cast<int64_t>(j) * p.sx_n + ch * 8, xr[i]);
+      }
+    }
+  };
+  load_x(0);
+
+  // ---- dimension ranks: >= 0 index among kept dims, < 0: -(1 + index among compressed) ------
+  {
+    uint8_t mb[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) mb[j] = p.mask[static_cast<size_t>(bh) * D + min(lane + 64 * j, D - 1)];
+    uint64_t bal[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bal[j] = __ballot(mb[j] != 0 && lane + 64 * j < D);
+    if (tid < D) {
+      const int w = tid >> 6;
+      const uint64_t bit = 1ull << (tid & 63);
+      int nc = 0;
+      uint64_t hit = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint64_t below = (j < w) ? ~0ull : ((j == w) ? (bit - 1ull) : 0ull);
+        nc += __popcll(bal[j] & below);
+        hit |= bal[j] & ((j == w) ? bit : 0ull);
+      }
+      cpos[tid] = hit ? static_cast<int16_t>(-(1 + nc)) : static_cast<int16_t>(tid - nc);
+    }
   }
-  // unused columns of the X slab stay zero for the whole kernel
-  for (int it = tid; it < kCols * kLd; it += kCBlock) xc_s[it] = zero_elem(xc_s);
-  __syncthreads();
+  // unused columns / pad columns of the LDS tiles stay zero for the whole kernel
+  for (int it = tid; it < 2 * static_cast<int>(bufe); it += kCBlock) lds[it] = zero_elem(lds);
 
-  // ---- rotating basis state: thread owns pair pl of this row block, 16 tokens
-  const int pl = tid >> 1, half = tid & 1;
-  const int pg = mc * (kRows / 2) + pl;           // global pair index
-  const bool pair_live = project && pg <= p.P;
-  const int order = (pg == 0) ? (M / 2) : pg;     // pair 0 carries the unpaired cosine
-  float bc[16], bs[16], tc = 1.0f, ts = 0.0f;
-  if (pair_live) unit_phase(order, kKT, p.T, &tc, &ts);
-
-  const int rows_here = min(kRows, 2 * (p.P + 1) - mc * kRows);  // live internal rows
+  // ---- per-wave constants: E fragments (A operand) and frame twiddles -------------------
+  const int rows_here = 2 * min(kPairs, p.nmax - mc * kPairs);   // live basis rows of this row block
+  const bool wave_live = project && wave * 64 < rows_here;
   const int cols_here = min(kCols, p.Dc - dc * kCols);
-  const int DT = (cols_here + 15) / 16;
+  const int ndt = (cols_here + 15) / 16;
 
-  f32x4 acc[4][8];
+  Frag<T> ea[4][2];          // [m tile][32-token half]
+  float twc[4][2], tws[4][2];   // cos/sin(omega_n * 64) of the two pairs a lane owns in every m tile
+  const uint32_t ph_blk = fixed_phase(kTB, p.ph_scale);   // 64 positions, as a 2^-32-turn phase
+  if (wave_live) {
+    const float invT = 1.0f / static_cast<float>(p.T);
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+      const int rho = wave * 64 + mt * 16 + r16;              // A-operand row of this lane
+      const int n = mc * kPairs + (rho >> 1) + 1;
+      const bool live = n <= p.nmax;
+#pragma unroll
+      for (int ksx = 0; ksx < 2; ++ksx) {
+        const int u0 = 32 * ksx + 8 * q4;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float c, sn;
+          if constexpr (sizeof(T) == 4) {
+            unit_phase(n, u0 + e, p.T, &c, &sn);
+          } else {
+            // n * u < 2^24: the float quotient estimate is exact to +-1
+            const int prod = n * (u0 + e);
+            int ph = prod - static_cast<int>(static_cast<float>(prod) * invT) * p.T;
+            if (ph < 0) ph += p.T;
+            if (ph >= p.T) ph -= p.T;
+            const float x = static_cast<float>(ph) * invT;
+            sn = __builtin_amdgcn_sinf(x);
+            c = __builtin_amdgcn_cosf(x);
+          }
+          set_elem<T>(ea[mt][ksx], e, live ? ((rho & 1) ? sn : c) : 0.0f);
+        }
+      }
+#pragma unroll
+      for (int pr = 0; pr < 2; ++pr) {
+        const int n2 = mc * kPairs + ((wave * 64 + mt * 16 + 4 * q4) >> 1) + pr + 1;   // accumulator rows 4*q4 + 2*pr
+        fixed_phase_cs<T>(static_cast<uint32_t>(n2) * ph_blk, &twc[mt][pr], &tws[mt][pr]);
+      }
+    }
+  }
+
+  f32x4 acc[4][DT];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt) acc[mt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int dt = 0; dt < DT; ++dt) acc[mt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float dcs = 0.0f;   // column sum of this thread's (column, token half)
 
-  const T* xbase = static_cast<const T*>(p.x) + b * p.sx_b + h * p.sx_h;
   T* keep = static_cast<T*>(p.keep) + static_cast<int64_t>(bh) * p.keep_stride;
-  const int nch = D / 8;
-  const int q = lane >> 4, r16 = lane & 15;
+  const int kp = p.keep_pitch;
+  __syncthreads();   // cpos and the zero fills are visible
 
-  int step = 0;
-  for (int js = j0; js < jend; js += kKT, ++step) {
-    // -- basis slab for tokens js .. js+31 (in registers until the LDS is free)
-    if (pair_live) {
-      if (step % kReanchor == 0) {
+  // Where each of a thread's 8 dims goes inside a buffer is decided once (kFast).
+  const int tstride = kCBlock / nch;            // tokens between a thread's consecutive vectors
+  uint32_t sc_off[8], sc_step[8];               // byte offset inside a buffer, step per vector
+  if constexpr (kFast) {
+    const int ch = tid % nch, jt0 = tid / nch;
+    const uint32_t es = sizeof(T);
 #pragma unroll
-        for (int u = 0; u < 16; ++u) unit_phase(order, p.t0 + js + 16 * half + u, p.T, &bc[u], &bs[u]);
+    for (int e = 0; e < 8; ++e) {
+      const int cp = cpos[ch * 8 + e];
+      const int rank = -cp - 1 - dc * kCols;
+      if (cp < 0 && rank >= 0 && rank < kCols) {
+        sc_off[e] = (rank * kLdX + jt0) * es;
+        sc_step[e] = tstride * es;
+      } else if (cp >= 0 && stage) {
+        const bool rows = p.keep_layout == FA_KEEP_ROWS;
+        sc_off[e] = (kCols * kLdX + (rows ? jt0 * (kp + 8) + cp : cp * kLdX + jt0)) * es;
+        sc_step[e] = (rows ? tstride * (kp + 8) : tstride) * es;
       } else {
+        sc_off[e] = (kCols * kLdX + p.ks_elems) * es;   // spare slot: the value is not needed here
+        sc_step[e] = 0;
+      }
+    }
+  }
+
+  for (int blk = 0; blk < nb; ++blk) {
+    const int buf = blk & 1;
+    const int js = j0 + blk * kTB;
+    T* xcb = lds + buf * bufe;
+    T* ksb = xcb + kCols * kLdX;
+
+    // -- scatter the block held in registers: compressed columns transposed, kept ones staged
+    if constexpr (kFast) {
+      const bool ragged = js + kTB > jend;
+      unsigned char* bb = reinterpret_cast<unsigned char*>(xcb);
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-          const float c = bc[u] * tc - bs[u] * ts;
-          const float sn = bs[u] * tc + bc[u] * ts;
-          bc[u] = c;
-          bs[u] = sn;
+      for (int i = 0; i < kXR; ++i) {
+        if (i < nx) {
+          const bool valid = !ragged || js + tid / nch + i * tstride < jend;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const T val = valid ? felem(xr[i], e) : zero_elem(lds);
+            *reinterpret_cast<T*>(bb + sc_off[e] + i * sc_step[e]) = val;
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < kXR; ++i) {
+        if (i < nx) {
+          const int it = tid + i * kCBlock;
+          const int jt = it / nch, ch = it % nch;
+          const bool valid = jt < kTB && js + jt < jend;
+          if (jt < kTB) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const int cp = cpos[ch * 8 + e];
+              const T val = valid ? felem(xr[i], e) : zero_elem(lds);
+              if (cp < 0) {
+                const int rank = -cp - 1 - dc * kCols;
+                if (rank >= 0 && rank < kCols) xcb[rank * kLdX + jt] = val;
+              } else if (stage) {
+                if (p.keep_layout == FA_KEEP_ROWS) ksb[jt * (kp + 8) + cp] = val;
+                else ksb[cp * kLdX + jt] = val;
+              } else if (write_keep && valid) {
+                const int64_t tok = static_cast<int64_t>(p.keep_offset) + js + jt;
+                const int64_t off = (p.keep_layout == FA_KEEP_ROWS) ? tok * kp + cp
+                                                                    : ((tok >> 3) * Du + cp) * 8 + (tok & 7);
+                keep[off] = val;
+              }
+            }
+          }
         }
       }
     }
-    __syncthreads();  // previous step's MFMAs have consumed the LDS slabs
-
-    // -- X slab: 128-bit loads, compressed columns transposed into LDS, kept ones to x_keep
-    for (int it = tid; it < kKT * nch; it += kCBlock) {
-      const int jt = it / nch, ch = it % nch;
-      const int j = js + jt;
-      T v[8];
-      if (j < jend) {
-        load8(xbase + static_cast<int64_t>(j) * p.sx_n + ch * 8, v);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = zero_elem(v);
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int cp = cpos[ch * 8 + e];
-        if (cp < 0) {
-          const int rank = -cp - 1 - dc * kCols;
-          if (rank >= 0 && rank < kCols) xc_s[rank * kLd + jt] = v[e];
-        } else if (write_keep && j < jend) {
-          const int64_t tok = static_cast<int64_t>(p.keep_offset) + j;
-          const int64_t off = (p.keep_layout == FA_KEEP_ROWS)
-                                  ? tok * p.keep_pitch + cp
-                                  : ((tok >> 3) * p.Du + cp) * 8 + (tok & 7);
-          keep[off] = v[e];
-        }
-      }
-    }
-    if (write_keep && p.keep_layout == FA_KEEP_ROWS && p.keep_pitch > p.Du) {
-      const int npad = p.keep_pitch - p.Du;
-      for (int it = tid; it < kKT * npad; it += kCBlock) {
+    if (write_keep && !stage && p.keep_layout == FA_KEEP_ROWS && kp > Du) {
+      const int npad = kp - Du;   // zero pad columns of the rows layout
+      for (int it = tid; it < kTB * npad; it += kCBlock) {
         const int j = js + it / npad;
-        if (j < jend)
-          keep[(static_cast<int64_t>(p.keep_offset) + j) * p.keep_pitch + p.Du + it % npad] = zero_elem(keep);
+        if (j < jend) keep[(static_cast<int64_t>(p.keep_offset) + j) * kp + Du + it % npad] = zero_elem(keep);
       }
     }
-    if (project) {
-      float row0[16], row1[16];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        if (!pair_live) { row0[u] = 0.0f; row1[u] = 0.0f; }
-        else if (pg == 0) { row0[u] = 1.0f; row1[u] = (M % 2 == 0) ? bc[u] : 0.0f; }
-        else { row0[u] = bc[u]; row1[u] = bs[u]; }
-      }
-      Pack16<T>::store(&phi_s[(2 * pl) * kLd + 16 * half], row0);
-      Pack16<T>::store(&phi_s[(2 * pl + 1) * kLd + 16 * half], row1);
-    }
+    // -- the next block travels while this one is multiplied
+    if (blk + 1 < nb) load_x(blk + 1);
     __syncthreads();
 
-    // -- MFMA: wave owns rows [64*wave, 64*wave+64) of the block
-    if (project && wave * 64 < rows_here) {
-      Frag<T> a[4];
+    // -- kept dims: staging tile -> 128-bit stores
+    if (stage) {
+      const int64_t tok0 = static_cast<int64_t>(p.keep_offset) + js;
+      if (p.keep_layout == FA_KEEP_ROWS) {
+        const int c8n = kp / 8;
+        for (int it = tid; it < kTB * c8n; it += kCBlock) {
+          const int jt = it / c8n, c8 = it % c8n;
+          if (js + jt < jend) {
+            Frag<T> f;
+            f.load(ksb + jt * (kp + 8) + 8 * c8);
+            *reinterpret_cast<Frag<T>*>(keep + (tok0 + jt) * kp + 8 * c8) = f;
+          }
+        }
+      } else {
+        for (int it = tid; it < Du * (kTB / 8); it += kCBlock) {
+          const int dim = it / (kTB / 8), g = it % (kTB / 8);
+          if (js + 8 * g < jend) {
+            Frag<T> f;
+            f.load(ksb + dim * kLdX + 8 * g);
+            *reinterpret_cast<Frag<T>*>(keep + (((tok0 >> 3) + g) * Du + dim) * 8) = f;
+          }
+        }
+      }
+    }
+    // -- constant function: column sums
+    if (do_dc) {
+      const int col = tid & (kCols - 1), th = tid / kCols;   // two token halves per column
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) a[mt].load(&phi_s[(wave * 64 + mt * 16 + r16) * kLd + 8 * q]);
+      for (int g = 0; g < 4; ++g) {
+        Frag<T> f;
+        f.load(xcb + col * kLdX + 32 * th + 8 * g);
 #pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        if (dt < DT) {
-          Frag<T> bfr;
-          bfr.load(&xc_s[(dt * 16 + r16) * kLd + 8 * q]);
+        for (int e = 0; e < 8; ++e) dcs += tof(felem(f, e));
+      }
+    }
+    // -- harmonics: move the frame to this block, then accumulate E * X_blk
+    if (wave_live) {
+      if (blk > 0) {
 #pragma unroll
-          for (int mt = 0; mt < 4; ++mt) mma_k32(acc[mt][dt], a[mt], bfr);
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+          for (int pr = 0; pr < 2; ++pr) {
+            const float c = twc[mt][pr], sn = tws[mt][pr];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+              const float ac = acc[mt][dt][2 * pr], as = acc[mt][dt][2 * pr + 1];
+              acc[mt][dt][2 * pr] = c * ac + sn * as;
+              acc[mt][dt][2 * pr + 1] = c * as - sn * ac;
+            }
+          }
+      }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        if (dt < ndt) {
+#pragma unroll
+          for (int ksx = 0; ksx < 2; ++ksx) {
+            Frag<T> bx;
+            bx.load(xcb + (dt * 16 + r16) * kLdX + 32 * ksx + 8 * q4);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) mma_k32(acc[mt][dt], ea[mt][ksx], bx);
+          }
         }
       }
     }
   }
 
-  // ---- epilogue: accumulator rows back to the caller's basis order
+  // ---- epilogue -----------------------------------------------------------------------------
   if (!project) return;
-  const size_t BH = static_cast<size_t>(p.B) * p.H;
   float* dst = (p.Sc == 1) ? p.coeffs + static_cast<size_t>(bh) * M * p.Dc
-                           : p.part + (static_cast<size_t>(s) * BH + bh) * M * p.Dc;
+                           : p.part + static_cast<size_t>(s) * p.part_stride + static_cast<size_t>(bh) * M * p.Dc;
   const bool add = (p.Sc == 1) && p.accumulate;
-#pragma unroll
-  for (int mt = 0; mt < 4; ++mt) {
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int rho = mc * kRows + wave * 64 + mt * 16 + 4 * q + v;  // internal row
-      int m;
-      if (rho == 0) m = 0;
-      else if (rho == 1) m = (M % 2 == 0) ? M - 1 : -1;   // unpaired cosine of order M/2
-      else m = 2 * (rho >> 1) - 1 + (rho & 1);            // rows 2n, 2n+1 -> m = 2n-1, 2n
-      if (m < 0 || (rho >= 2 && (rho >> 1) > p.P)) continue;
-#pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        const int i = dc * kCols + dt * 16 + r16;
-        if (dt < DT && i < p.Dc) {
-          float* o = dst + static_cast<size_t>(m) * p.Dc + i;
-          const float val = acc[mt][dt][v];
-          *o = add ? (*o + val) : val;
-        }
+  if (do_dc) {   // uniform per workgroup
+    dcred[tid] = dcs;
+    __syncthreads();
+    if (tid < kCols) {
+      const int i = dc * kCols + tid;
+      if (tid < cols_here) {
+        const float v = dcred[tid] + dcred[tid + kCols];
+        dst[i] = add ? dst[i] + v : v;
       }
     }
+  }
+  if (wave_live) {
+    const uint32_t ph_last = fixed_phase(p.t0 + j0 + (nb - 1) * kTB, p.ph_scale);   // frame origin
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int pr = 0; pr < 2; ++pr) {
+        const int n = mc * kPairs + ((wave * 64 + mt * 16 + 4 * q4) >> 1) + pr + 1;
+        if (n > p.nmax) continue;
+        float c, sn;
+        fixed_phase_cs<T>(static_cast<uint32_t>(n) * ph_last, &c, &sn);
+        const int m_cos = 2 * n - 1, m_sin = 2 * n;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          const int i = dc * kCols + dt * 16 + r16;
+          if (dt < ndt && i < p.Dc) {
+            const float ac = acc[mt][dt][2 * pr], as = acc[mt][dt][2 * pr + 1];
+            const float vc = c * ac - sn * as, vs = sn * ac + c * as;
+            float* oc = dst + static_cast<size_t>(m_cos) * p.Dc + i;
+            *oc = add ? (*oc + vc) : vc;
+            if (m_sin < M) {
+              float* os = dst + static_cast<size_t>(m_sin) * p.Dc + i;
+              *os = add ? (*os + vs) : vs;
+            }
+          }
+        }
+      }
   }
 }
 
 // sum of the token-chunk partials (fixed order, so results are reproducible)
 __global__ __launch_bounds__(256) void compress_reduce(const float* part, float* coeffs, size_t total,
-                                                       int Sc, int accumulate) {
-  const size_t idx = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+                                                       size_t stride, int Sc, int accumulate) {
+  const size_t idx = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
   if (idx >= total) return;
-  float v = accumulate ? coeffs[idx] : 0.0f;
-  for (int s = 0; s < Sc; ++s) v += part[static_cast<size_t>(s) * total + idx];
-  coeffs[idx] = v;
+  if (idx + 4 <= total) {
+    f32x4 v = accumulate ? *reinterpret_cast<const f32x4*>(coeffs + idx) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int s = 0; s < Sc; ++s) v += *reinterpret_cast<const f32x4*>(part + static_cast<size_t>(s) * stride + idx);
+    *reinterpret_cast<f32x4*>(coeffs + idx) = v;
+  } else {
+    for (size_t k = idx; k < total; ++k) {
+      float v = accumulate ? coeffs[k] : 0.0f;
+      for (int s = 0; s < Sc; ++s) v += part[static_cast<size_t>(s) * stride + k];
+      coeffs[k] = v;
+    }
+  }
 }
 
 struct CompressPlan {
-  int Sc, chunk, MC, DCn, P;
+  int Sc, chunk, MC, DCn, nmax, stage;
+  unsigned ks_elems, lds;
   size_t total;  // workspace bytes
 };
 
-static CompressPlan make_compress_plan(int B, int H, int N, int Dc, int M) {
+static CompressPlan make_compress_plan(int dtype, int B, int H, int N, int D, int Dc, int M,
+                                       int keep_layout, int keep_offset) {
   CompressPlan pl{};
-  pl.P = (M - 1) / 2;
-  const int rows = 2 * (pl.P + 1);
-  pl.MC = Dc > 0 ? (rows + kRows - 1) / kRows : 1;
+  pl.nmax = M / 2;
+  pl.MC = (Dc > 0 && pl.nmax > 0) ? (pl.nmax + kPairs - 1) / kPairs : 1;
   pl.DCn = Dc > 0 ? (Dc + kCols - 1) / kCols : 1;
   const long groups = static_cast<long>(B) * H * pl.MC * pl.DCn;
-  long want = (512 + groups - 1) / groups;  // token chunks needed to fill the chip
-  const long steps = (N + kKT - 1) / kKT;
-  if (want > steps) want = steps;
+  const long nblocks = (N + kTB - 1) / kTB;
+  long want = (512 + groups - 1) / groups;       // token chunks that fill the chip twice over
+  const long cap = nblocks / 16 > 0 ? nblocks / 16 : 1;   // but at least 16 blocks per chunk: the
+  if (want > cap) want = cap;                             // chunk partials cost memory traffic
   if (want < 1) want = 1;
-  if (want > 1024) want = 1024;
-  const long per = N > 0 ? (steps + want - 1) / want : 1;
-  pl.chunk = static_cast<int>(per) * kKT;
+  const long per = N > 0 ? (nblocks + want - 1) / want : 1;
+  pl.chunk = static_cast<int>(per) * kTB;
   pl.Sc = N > 0 ? (N + pl.chunk - 1) / pl.chunk : 0;
   pl.total = (pl.Sc > 1 && Dc > 0)
-                 ? align_up(static_cast<size_t>(pl.Sc) * B * H * M * Dc * sizeof(float), 256)
+                 ? align_up(static_cast<size_t>(pl.Sc) * ((static_cast<size_t>(B) * H * M * Dc + 3) & ~size_t(3)) *
+                                sizeof(float), 256)
                  : 0;
+  const unsigned es = dtype == FA_F32 ? 4 : 2;
+  const int Du = D - Dc, kp = (Du + 7) & ~7;
+  const unsigned rows_elems = kTB * (kp + 8), tok8_elems = static_cast<unsigned>(Du) * kLdX;
+  pl.ks_elems = keep_layout == FA_KEEP_ROWS ? rows_elems : tok8_elems;
+  const unsigned base = 2u * (kCols * kLdX + 8u) * es;
+  pl.stage = Du > 0 && (keep_layout == FA_KEEP_ROWS || keep_offset % 8 == 0) &&
+             base + 2u * pl.ks_elems * es <= kMaxCLds;
+  if (!pl.stage) pl.ks_elems = 0;
+  pl.lds = base + 2u * pl.ks_elems * es;
   return pl;
 }
 
@@ -291,13 +477,29 @@ static int check_compress_shapes(int dtype, int B, int H, int N, int D, int Dc, 
   return FA_OK;
 }
 
+template <typename T, int DT, int kXR, bool kFast>
+static int launch_project(const CompressParams& p, const CompressPlan& pl, hipStream_t st) {
+  auto kern = compress_project<T, DT, kXR, kFast>;
+  static unsigned granted = 48 * 1024;
+  if (pl.lds > granted) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(kMaxCLds)) != hipSuccess)
+      return FA_ERR_HIP;
+    granted = kMaxCLds;
+  }
+  dim3 grid(pl.Sc, pl.MC * pl.DCn, p.B * p.H);
+  hipLaunchKernelGGL(kern, grid, dim3(kCBlock), pl.lds, st, p);
+  return FA_OK;
+}
+
 }  // namespace fa
 
 extern "C" {
 
 size_t fa_compress_workspace_bytes(int B, int H, int N, int D, int Dc, int M) {
   if (fa::check_compress_shapes(FA_BF16, B, H, N, D, Dc, M, M > N ? M : N, 0) != FA_OK) return 0;
-  const size_t t = fa::make_compress_plan(B, H, N, Dc, M).total;
+  const size_t t = fa::make_compress_plan(FA_BF16, B, H, N, D, Dc, M, FA_KEEP_ROWS, 0).total;
   return t ? t : 256;
 }
 
@@ -321,9 +523,12 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
   const int keep_pitch = (Du + 7) & ~7;
   const int64_t dense = (keep_layout == FA_KEEP_ROWS) ? tokens * keep_pitch : ((tokens + 7) / 8) * 8 * Du;
   if (keep_stride_bh == 0) keep_stride_bh = dense;
-  if (x_keep && keep_stride_bh < dense) return FA_ERR_SHAPE;
+  if (x_keep && (keep_stride_bh < dense || (keep_stride_bh % 8) ||
+                 (reinterpret_cast<uintptr_t>(x_keep) & 15u)))
+    return FA_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(coeffs) & 15u) return FA_ERR_SHAPE;
 
-  const CompressPlan pl = make_compress_plan(B, H, N, Dc, M);
+  const CompressPlan pl = make_compress_plan(dtype, B, H, N, D, Dc, M, keep_layout, keep_offset);
   if (pl.total > 0) {
     if (!workspace) return FA_ERR_NULL;
     if (workspace_bytes < pl.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
@@ -335,23 +540,45 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
   p.B = B; p.H = H; p.N = N; p.D = D; p.Dc = Dc; p.Du = Du; p.M = M; p.T = T; p.t0 = t0;
   p.accumulate = accumulate ? 1 : 0;
   p.mask = dim_mask; p.coeffs = coeffs;
-  p.keep = x_keep; p.keep_layout = keep_layout; p.keep_pitch = keep_pitch; p.keep_stride = keep_stride_bh; p.keep_offset = keep_offset;
-  p.Sc = pl.Sc; p.chunk = pl.chunk; p.MC = pl.MC; p.DCn = pl.DCn; p.P = pl.P;
+  p.keep = x_keep; p.keep_layout = keep_layout; p.keep_pitch = keep_pitch;
+  p.keep_stride = keep_stride_bh; p.keep_offset = keep_offset; p.stage_keep = pl.stage;
+  p.Sc = pl.Sc; p.chunk = pl.chunk; p.MC = pl.MC; p.DCn = pl.DCn; p.nmax = pl.nmax;
+  p.ks_elems = pl.ks_elems;
+  p.ph_scale = 4294967296.0 / static_cast<double>(T);
   p.part = static_cast<float*>(workspace);
+  p.part_stride = (static_cast<size_t>(B) * H * M * Dc + 3) & ~size_t(3);
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const size_t total = static_cast<size_t>(B) * H * M * Dc;
   if (ev) (void)hipEventRecord(ev[0], stream);
   if (pl.Sc > 0) {
-    dim3 grid(pl.Sc, pl.MC * pl.DCn, B * H);
-    if (dtype == FA_F32) hipLaunchKernelGGL(compress_project<float>, grid, dim3(kCBlock), 0, stream, p);
-    else hipLaunchKernelGGL(compress_project<bf16_t>, grid, dim3(kCBlock), 0, stream, p);
+    const int cols = Dc < kCols ? Dc : kCols;
+    int rc;
+    const bool narrow = cols <= 96, small_d = D <= 128;
+    // every thread routes fixed dims when the row vectors divide the workgroup and kept dims are staged
+    const bool fast = (kCBlock % (D / 8)) == 0 && (pl.stage || Du == 0 || x_keep == nullptr);
+#define FA_LAUNCH_PROJECT2(T_, F_)                                                                  \
+  rc = narrow ? (small_d ? launch_project<T_, 6, 4, F_>(p, pl, stream) : launch_project<T_, 6, 8, F_>(p, pl, stream)) \
+              : (small_d ? launch_project<T_, 8, 4, F_>(p, pl, stream) : launch_project<T_, 8, 8, F_>(p, pl, stream))
+#define FA_LAUNCH_PROJECT(T_)       \
+  do {                              \
+    if (fast) {                     \
+      FA_LAUNCH_PROJECT2(T_, true); \
+    } else {                        \
+      FA_LAUNCH_PROJECT2(T_, false);\
+    }                               \
+  } while (0)
+    if (dtype == FA_F32) FA_LAUNCH_PROJECT(float);
+    else FA_LAUNCH_PROJECT(bf16_t);
+#undef FA_LAUNCH_PROJECT2
+#undef FA_LAUNCH_PROJECT
+    if (rc != FA_OK) return rc;
   }
   if (ev) (void)hipEventRecord(ev[1], stream);
   if (total > 0 && (pl.Sc > 1 || (pl.Sc == 0 && !accumulate))) {
-    const unsigned blocks = static_cast<unsigned>((total + 255) / 256);
+    const unsigned blocks = static_cast<unsigned>((total / 4 + 1 + 255) / 256);
     hipLaunchKernelGGL(compress_reduce, dim3(blocks), dim3(256), 0, stream, p.part, coeffs, total,
-                       pl.Sc, p.accumulate);
+                       p.part_stride, pl.Sc, p.accumulate);
   }
   if (ev) (void)hipEventRecord(ev[2], stream);
   return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;

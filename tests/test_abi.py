@@ -73,7 +73,8 @@ def _compress(fa, **kw):
 @pytest.mark.parametrize("kw,code", [
     (dict(Dc=200), -2), (dict(M=513), -2), (dict(t0=4), -2), (dict(sn=100), -2), (dict(sn=132), -2),
     (dict(layout=3), -2), (dict(koff=-1), -2), (dict(D=100, Dc=50), -3), (dict(M=2000, T=4000), -3),
-    (dict(x=None), -1), (dict(mask=None), -1), (dict(coeffs=None), -1), (dict(ws_bytes=8), -4),
+    (dict(x=None), -1), (dict(mask=None), -1), (dict(coeffs=None), -1),
+    (dict(N=8192, T=8192, sb=8 * 8192 * 128, sh=8192 * 128, ws_bytes=8), -4),
     (dict(x=ctypes.c_void_p(0x10004)), -2),
 ])
 def test_compress_rejects_bad_arguments(kw, code):

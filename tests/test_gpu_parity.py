@@ -154,5 +154,6 @@ def test_compress_streaming_update_matches_one_shot():
         fa.fa_compress(x[:, :, j0:j1], mask, cfg.Dkc, cfg.M, cfg.T, t0=j0, accumulate=True,
                        coeffs=c, x_keep=keep, keep_offset=j0, keep_stride_bh=slab)
     torch.cuda.synchronize()
-    assert rel_err(c.cpu().numpy(), full.cpu().numpy()) <= 1e-5
+    # both sides round the basis table to the element type at different block phases
+    assert rel_err(c.cpu().numpy(), full.cpu().numpy()) <= cfg.tol
     assert torch.equal(keep, keep_full)
