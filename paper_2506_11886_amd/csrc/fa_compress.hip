@@ -27,12 +27,24 @@
 
 namespace fa {
 
-constexpr int kCBlock = 256;
+constexpr int kCBlock = 512;      // 8 waves: 4 row groups of 64 basis rows x 2 column halves
 constexpr int kTB = 64;          // tokens per block
 constexpr int kLdX = kTB + 8;    // LDS pitch (elements) of a transposed column: 16-byte aligned, bank-spread
 constexpr int kPairs = 128;      // harmonics per workgroup (256 basis rows)
 constexpr int kCols = 128;       // compressed columns per workgroup
 constexpr unsigned kMaxCLds = 160 * 1024 - 8192;
+
+// Developer aid (compiled out unless FA_TRACE is defined): per-wave cycle stamps.
+#ifdef FA_TRACE
+#define FA_CSTAMP(i)                                                                          \
+  do {                                                                                        \
+    if ((threadIdx.x & 63) == 0 && (i) < 32)                                                  \
+      p.trace[(((static_cast<size_t>(blockIdx.z) * gridDim.y + blockIdx.y) * gridDim.x +      \
+                blockIdx.x) * 8 + (threadIdx.x >> 6)) * 32 + (i)] = clock64();                \
+  } while (0)
+#else
+#define FA_CSTAMP(i) do {} while (0)
+#endif
 
 struct CompressParams {
   const void* x;
@@ -53,6 +65,9 @@ struct CompressParams {
   double ph_scale;  // 2^32 / T
   float* part;      // [Sc][part_stride] when Sc > 1, chunk s holds [B*H][M][Dc]
   size_t part_stride;   // B*H*M*Dc rounded up to 4 floats
+#ifdef FA_TRACE
+  long long* trace;
+#endif
 };
 
 __device__ __forceinline__ void load8(const bf16_t* p, Frag<bf16_t>& f) { f.load(p); }
@@ -89,12 +104,12 @@ __device__ __forceinline__ void set_elem<bf16_t>(Frag<bf16_t>& f, int e, float x
 template <>
 __device__ __forceinline__ void set_elem<float>(Frag<float>& f, int e, float x) { f.v[e] = x; }
 
-// DT: 16-column tiles of compressed dims per workgroup; kXR: 8-element vectors of
-// X per thread and block (4 covers head dims up to 128, 8 up to 256)
+// DT: 16-column tiles of compressed dims per wave (a workgroup covers 2 * DT); kXR:
+// 8-element vectors of X per thread and block (2 covers head dims up to 128, 4 up to 256)
 // kFast: the row vectors divide the workgroup evenly (head dim 64 / 128 / 256) and
 // kept dims are staged, so every thread routes the same 8 dims in every block.
 template <typename T, int DT, int kXR, bool kFast>
-__global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_project(CompressParams p) {
+__global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int16_t cpos[FA_MAX_HEAD_DIM];
   __shared__ float dcred[kCBlock];
@@ -133,6 +148,7 @@ __global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_proj
       }
     }
   };
+  FA_CSTAMP(0);
   load_x(0);
 
   // ---- dimension ranks: >= 0 index among kept dims, < 0: -(1 + index among compressed) ------
@@ -158,13 +174,15 @@ __global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_proj
     }
   }
   // unused columns / pad columns of the LDS tiles stay zero for the whole kernel
-  for (int it = tid; it < 2 * static_cast<int>(bufe); it += kCBlock) lds[it] = zero_elem(lds);
+  for (int it = tid; it < static_cast<int>(2 * bufe * sizeof(T) / 16); it += kCBlock)
+    reinterpret_cast<u32x4*>(smem)[it] = u32x4{0u, 0u, 0u, 0u};
 
   // ---- per-wave constants: E fragments (A operand) and frame twiddles -------------------
   const int rows_here = 2 * min(kPairs, p.nmax - mc * kPairs);   // live basis rows of this row block
-  const bool wave_live = project && wave * 64 < rows_here;
+  const int rgw = wave & 3, chw = wave >> 2;       // row group (64 basis rows), column half of this wave
   const int cols_here = min(kCols, p.Dc - dc * kCols);
-  const int ndt = (cols_here + 15) / 16;
+  const int ndt = (cols_here + 15) / 16 - chw * DT;   // live column tiles of this wave (may be <= 0)
+  const bool wave_live = project && rgw * 64 < rows_here && ndt > 0;
 
   Frag<T> ea[4][2];          // [m tile][32-token half]
   float twc[4][2], tws[4][2];   // cos/sin(omega_n * 64) of the two pairs a lane owns in every m tile
@@ -173,7 +191,7 @@ __global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_proj
     const float invT = 1.0f / static_cast<float>(p.T);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
-      const int rho = wave * 64 + mt * 16 + r16;              // A-operand row of this lane
+      const int rho = rgw * 64 + mt * 16 + r16;               // A-operand row of this lane
       const int n = mc * kPairs + (rho >> 1) + 1;
       const bool live = n <= p.nmax;
 #pragma unroll
@@ -199,7 +217,7 @@ __global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_proj
       }
 #pragma unroll
       for (int pr = 0; pr < 2; ++pr) {
-        const int n2 = mc * kPairs + ((wave * 64 + mt * 16 + 4 * q4) >> 1) + pr + 1;   // accumulator rows 4*q4 + 2*pr
+        const int n2 = mc * kPairs + ((rgw * 64 + mt * 16 + 4 * q4) >> 1) + pr + 1;   // accumulator rows 4*q4 + 2*pr
         fixed_phase_cs<T>(static_cast<uint32_t>(n2) * ph_blk, &twc[mt][pr], &tws[mt][pr]);
       }
     }
@@ -240,6 +258,7 @@ __global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_proj
     }
   }
 
+  FA_CSTAMP(1);
   for (int blk = 0; blk < nb; ++blk) {
     const int buf = blk & 1;
     const int js = j0 + blk * kTB;
@@ -297,9 +316,11 @@ __global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_proj
         if (j < jend) keep[(static_cast<int64_t>(p.keep_offset) + j) * kp + Du + it % npad] = zero_elem(keep);
       }
     }
+    FA_CSTAMP(2 + 4 * blk);
     // -- the next block travels while this one is multiplied
     if (blk + 1 < nb) load_x(blk + 1);
     __syncthreads();
+    FA_CSTAMP(3 + 4 * blk);
 
     // -- kept dims: staging tile -> 128-bit stores
     if (stage) {
@@ -327,15 +348,16 @@ __global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_proj
     }
     // -- constant function: column sums
     if (do_dc) {
-      const int col = tid & (kCols - 1), th = tid / kCols;   // two token halves per column
+      const int col = tid & (kCols - 1), th = tid / kCols;   // four token quarters per column
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
+      for (int g = 0; g < 2; ++g) {
         Frag<T> f;
-        f.load(xcb + col * kLdX + 32 * th + 8 * g);
+        f.load(xcb + col * kLdX + 16 * th + 8 * g);
 #pragma unroll
         for (int e = 0; e < 8; ++e) dcs += tof(felem(f, e));
       }
     }
+    FA_CSTAMP(4 + 4 * blk);
     // -- harmonics: move the frame to this block, then accumulate E * X_blk
     if (wave_live) {
       if (blk > 0) {
@@ -358,15 +380,17 @@ __global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_proj
 #pragma unroll
           for (int ksx = 0; ksx < 2; ++ksx) {
             Frag<T> bx;
-            bx.load(xcb + (dt * 16 + r16) * kLdX + 32 * ksx + 8 * q4);
+            bx.load(xcb + ((chw * DT + dt) * 16 + r16) * kLdX + 32 * ksx + 8 * q4);
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt) mma_k32(acc[mt][dt], ea[mt][ksx], bx);
           }
         }
       }
     }
+    FA_CSTAMP(5 + 4 * blk);
   }
 
+  FA_CSTAMP(30);
   // ---- epilogue -----------------------------------------------------------------------------
   if (!project) return;
   float* dst = (p.Sc == 1) ? p.coeffs + static_cast<size_t>(bh) * M * p.Dc
@@ -378,7 +402,7 @@ __global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_proj
     if (tid < kCols) {
       const int i = dc * kCols + tid;
       if (tid < cols_here) {
-        const float v = dcred[tid] + dcred[tid + kCols];
+        const float v = (dcred[tid] + dcred[tid + kCols]) + (dcred[tid + 2 * kCols] + dcred[tid + 3 * kCols]);
         dst[i] = add ? dst[i] + v : v;
       }
     }
@@ -389,14 +413,14 @@ __global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_proj
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
       for (int pr = 0; pr < 2; ++pr) {
-        const int n = mc * kPairs + ((wave * 64 + mt * 16 + 4 * q4) >> 1) + pr + 1;
+        const int n = mc * kPairs + ((rgw * 64 + mt * 16 + 4 * q4) >> 1) + pr + 1;
         if (n > p.nmax) continue;
         float c, sn;
         fixed_phase_cs<T>(static_cast<uint32_t>(n) * ph_last, &c, &sn);
         const int m_cos = 2 * n - 1, m_sin = 2 * n;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-          const int i = dc * kCols + dt * 16 + r16;
+          const int i = dc * kCols + (chw * DT + dt) * 16 + r16;
           if (dt < ndt && i < p.Dc) {
             const float ac = acc[mt][dt][2 * pr], as = acc[mt][dt][2 * pr + 1];
             const float vc = c * ac - sn * as, vs = sn * ac + c * as;
@@ -410,6 +434,7 @@ __global__ __launch_bounds__(kCBlock, sizeof(T) == 2 ? 2 : 1) void compress_proj
         }
       }
   }
+  FA_CSTAMP(31);
 }
 
 // sum of the token-chunk partials (fixed order, so results are reproducible)
@@ -456,6 +481,9 @@ static CompressPlan make_compress_plan(int dtype, int B, int H, int N, int D, in
                  ? align_up(static_cast<size_t>(pl.Sc) * ((static_cast<size_t>(B) * H * M * Dc + 3) & ~size_t(3)) *
                                 sizeof(float), 256)
                  : 0;
+#ifdef FA_TRACE
+  pl.total = align_up(pl.total, 256) + static_cast<size_t>(B) * H * pl.MC * pl.DCn * (pl.Sc > 0 ? pl.Sc : 1) * 8 * 32 * sizeof(long long);
+#endif
   const unsigned es = dtype == FA_F32 ? 4 : 2;
   const int Du = D - Dc, kp = (Du + 7) & ~7;
   const unsigned rows_elems = kTB * (kp + 8), tok8_elems = static_cast<unsigned>(Du) * kLdX;
@@ -547,6 +575,10 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
   p.ph_scale = 4294967296.0 / static_cast<double>(T);
   p.part = static_cast<float*>(workspace);
   p.part_stride = (static_cast<size_t>(B) * H * M * Dc + 3) & ~size_t(3);
+#ifdef FA_TRACE
+  p.trace = reinterpret_cast<long long*>(static_cast<char*>(workspace) + pl.total -
+                                         static_cast<size_t>(B) * H * pl.MC * pl.DCn * (pl.Sc > 0 ? pl.Sc : 1) * 8 * 32 * sizeof(long long));
+#endif
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const size_t total = static_cast<size_t>(B) * H * M * Dc;
@@ -558,8 +590,8 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
     // every thread routes fixed dims when the row vectors divide the workgroup and kept dims are staged
     const bool fast = (kCBlock % (D / 8)) == 0 && (pl.stage || Du == 0 || x_keep == nullptr);
 #define FA_LAUNCH_PROJECT2(T_, F_)                                                                  \
-  rc = narrow ? (small_d ? launch_project<T_, 6, 4, F_>(p, pl, stream) : launch_project<T_, 6, 8, F_>(p, pl, stream)) \
-              : (small_d ? launch_project<T_, 8, 4, F_>(p, pl, stream) : launch_project<T_, 8, 8, F_>(p, pl, stream))
+  rc = narrow ? (small_d ? launch_project<T_, 3, 2, F_>(p, pl, stream) : launch_project<T_, 3, 4, F_>(p, pl, stream)) \
+              : (small_d ? launch_project<T_, 4, 2, F_>(p, pl, stream) : launch_project<T_, 4, 4, F_>(p, pl, stream))
 #define FA_LAUNCH_PROJECT(T_)       \
   do {                              \
     if (fast) {                     \
