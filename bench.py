@@ -26,6 +26,10 @@ if ROOT not in sys.path:
 
 METRIC = "Fourier-KV decode context tokens/s/GPU + achieved HBM GB/s (% of peak)"
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch from hardware counters (FETCH_SIZE + WRITE_SIZE, each scaled by what the
+# same counter reads for the --copy-probe kernel), keyed by (kernel, config index).
+# Source: profiles/hbm_traffic_*.txt; null for anything not measured there.
+MEASURED_TRAFFIC = {}
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_MATRIX_PEAK_TFLOPS = 157.3
 LLC_BYTES = 256 << 20
@@ -39,6 +43,9 @@ def parse_args():
     ap.add_argument("--workload", default="2", help="config index (1-5) or name")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch a converting copy of known size (bf16 -> fp32, 64 MiB read, "
+                         "128 MiB written) three times: the yardstick that HBM counter runs are scaled by")
     return ap.parse_args()
 
 
@@ -134,7 +141,8 @@ def main():
     def roof_hbm(bytes_, t, kernel):
         a = bytes_ / t / 1e9
         return {"kernel": kernel, "bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(a / HBM_PEAK_GBS, 4), "traffic": None}
+                "unit": "GB/s", "frac": round(a / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC.get((kernel, cfg.index))}
 
     mm_peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else FP32_MATRIX_PEAK_TFLOPS
     roof_dec = roof_hbm(dec_bytes, t_partial, "decode_partial")
@@ -144,7 +152,9 @@ def main():
     else:
         a = cmp_flops / t_project / 1e12
         roof_cmp = {"kernel": "compress_project", "bound": "mfma", "achieved": round(a, 1),
-                    "peak": mm_peak, "unit": "TFLOP/s", "frac": round(a / mm_peak, 4), "traffic": None}
+                    "peak": mm_peak, "unit": "TFLOP/s", "frac": round(a / mm_peak, 4),
+                    "traffic": MEASURED_TRAFFIC.get(("compress_project", cfg.index))}
+    roof_cmp["launches_per_step"] = 2       # K and V; achieved = bytes (flop) of both / duration of both
     roof_cmp["mfma_tflops"] = round(cmp_flops / t_project / 1e12, 1)
     roof_cmp["mfma_frac"] = round(cmp_flops / t_project / 1e12 / mm_peak, 4)
     dominant = roof_cmp if t_project > t_partial else roof_dec
@@ -186,6 +196,14 @@ def main():
                          "roofline": roof_cmp},
         },
     }
+
+    if args.copy_probe:
+        src = torch.ones(32 << 20, dtype=torch.bfloat16, device="cuda")
+        dst = torch.empty(32 << 20, dtype=torch.float32, device="cuda")
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        result["copy_probe"] = {"read_bytes": src.numel() * 2, "written_bytes": dst.numel() * 4, "launches": 3}
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, ctx, args.cpu_seconds)
