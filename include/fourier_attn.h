@@ -172,8 +172,9 @@ int fa_decode_timed(const void* q, int dtype,
                     float* kernel_ms);
 
 /* Number of middle-row chunks fa_decode will use for these sizes when
- * num_splits = 0 (exposed so callers can size and report). */
-int fa_decode_default_splits(int B, int Hq, int Hkv, int N);
+ * num_splits = 0 (exposed so callers can size and report); 0 for sizes
+ * fa_decode rejects. */
+int fa_decode_default_splits(int B, int Hq, int Hkv, int M, int N, int W);
 
 /* Static description of a status code (never NULL). */
 const char* fa_status_string(int status);

@@ -49,7 +49,7 @@ def _load(path: str = _LIB_PATH):
     lib.fa_decode_workspace_bytes.restype = sz
     lib.fa_decode_workspace_bytes.argtypes = [i32] * 10
     lib.fa_decode_default_splits.restype = i32
-    lib.fa_decode_default_splits.argtypes = [i32] * 4
+    lib.fa_decode_default_splits.argtypes = [i32] * 6
     lib.fa_status_string.restype = c.c_char_p
     lib.fa_status_string.argtypes = [i32]
     return lib
@@ -88,8 +88,8 @@ def decode_workspace_bytes(B, Hq, Hkv, D, Dkc, Dvc, M, N, W, num_splits=0) -> in
     return int(lib.fa_decode_workspace_bytes(B, Hq, Hkv, D, Dkc, Dvc, M, N, W, num_splits))
 
 
-def decode_default_splits(B, Hq, Hkv, N) -> int:
-    return int(lib.fa_decode_default_splits(B, Hq, Hkv, N))
+def decode_default_splits(B, Hq, Hkv, M, N, W) -> int:
+    return int(lib.fa_decode_default_splits(B, Hq, Hkv, M, N, W))
 
 
 def keep_rows_pitch(Du: int) -> int:

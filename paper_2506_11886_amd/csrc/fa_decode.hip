@@ -15,17 +15,20 @@
 // omega_n tau.  One 16-column MFMA tile covers (up to 4 token tiles) x (query
 // heads of the group), so the table is shared by the heads and by both sides.
 // The V side is the mirror image: r' = P^T E per tile, rotated back once per
-// chunk.
+// chunk.  The table is split by harmonics over the four waves of a workgroup
+// and lives in registers.
 //
 // The kernels are latency-shaped: a decode step moves only tens of megabytes,
 // so every kernel requests all of its global-memory operands up front (one
 // dependent round trip) and hides them behind table construction and MFMAs.
 //
 // Launches on the caller's stream:
-//   1. decode_prepare : g (series order) for every query head, from C_k and q.
+//   1. decode_prepare : g (series order) for every query head, from C_k and q;
+//      q at the kept K dims, packed.
 //   2. decode_partial : one workgroup per (sequence, KV head, token chunk);
 //      chunks of middle rows and chunks of full-width sink/window rows; emits
-//      a flash-decoding partial (max, sum, acc[D], r[Mint]) per query head.
+//      a flash-decoding partial per query head: (max, sum, acc[kept dims],
+//      r[Mint]) for middle rows, (max, sum, acc[D]) for full-width rows.
 //   3. decode_finish  : one workgroup per query head merges the partials,
 //      applies diag(w) C_v to r and normalises.
 
@@ -43,7 +46,7 @@ constexpr int kXN = kTJ / 32;      // 32-token contraction steps per tile on the
 constexpr int kMaxKT = 4;          // tiles per wave step
 constexpr int kWChunk = 64;        // full-width rows per workgroup
 constexpr int kMaxDvTiles = 8;     // kept V dims handled per middle row: 8 * 16
-constexpr int kMaxPartials = 1024; // partial records per query head
+constexpr int kMaxPartials = 1024; // partial records per query head (= threads of decode_finish)
 constexpr unsigned kMaxDynLds = 160 * 1024 - 4096;   // dynamic LDS a workgroup may ask for
 constexpr int kFinBlock = 1024;    // threads of decode_finish
 
@@ -80,13 +83,15 @@ struct DecodeParams {
   int Mint;         // series length: 2 * (M/2) padded to a compiled size
   int Sw, Sm;       // chunks of full-width rows / of middle rows (middle chunks come first)
   int chunk_m;      // middle rows per chunk (multiple of the workgroup step)
-  int rec;          // floats per partial record: 2 + D + Mint
-  unsigned lds_tab; // bytes of the E-table region
+  int recm, recw;   // floats per partial record: 4 + 16 ceil(Dvu/16) + Mint (middle), 4 + D (full rows)
+  unsigned lds_tab; // bytes of the exchange / reduction region of a middle-row workgroup
   float scale;
   double ph_scale;  // 2^32 / T
   float* gs;        // [B,Hq,Mint] series coefficients, K-side order
   float* g0;        // [B,Hq]      constant-term coefficient
-  float* part;      // [B,Hq,Sm+Sw,rec]
+  void* qkeep;      // [B,Hq,Dkq]  q at the kept K dims, zero padded to Dkq = 32 ceil(Dku/32)
+  float* part_m;    // [B,Hq,Sm,recm]
+  float* part_w;    // [B,Hq,Sw,recw]
   float* out;       // [B,Hq,D]
 #ifdef FA_TRACE
   long long* trace;
@@ -179,6 +184,27 @@ __device__ __forceinline__ float quad_bcast(float v, int i) {
   return __int_as_float(r);
 }
 
+// rotation by N lanes within each row of 16 lanes (lane i receives lane (i + N) % 16 of its row)
+template <int N>
+__device__ __forceinline__ float row_ror(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xf, 0xf, false));
+}
+// sum / max over the lanes of a row whose indices differ by a multiple of `stride` (a power of two)
+__device__ __forceinline__ float row_stride_sum(float v, int stride) {
+  if (stride <= 8) v += row_ror<8>(v);
+  if (stride <= 4) v += row_ror<4>(v);
+  if (stride <= 2) v += row_ror<2>(v);
+  if (stride <= 1) v += row_ror<1>(v);
+  return v;
+}
+__device__ __forceinline__ float row_stride_max(float v, int stride) {
+  if (stride <= 8) v = fmaxf(v, row_ror<8>(v));
+  if (stride <= 4) v = fmaxf(v, row_ror<4>(v));
+  if (stride <= 2) v = fmaxf(v, row_ror<2>(v));
+  if (stride <= 1) v = fmaxf(v, row_ror<1>(v));
+  return v;
+}
+
 // every wave reads the whole mask row (D <= 256) and keeps it as 4 ballot words
 __device__ __forceinline__ void mask_ballots(const uint8_t* mask, int D, int lane, uint64_t* bal) {
   uint8_t b[4];
@@ -234,12 +260,13 @@ __global__ __launch_bounds__(kBlock) void decode_prepare(DecodeParams p) {
   }
   uint64_t kbal[4];
   mask_ballots(p.kmask + static_cast<size_t>(bh) * D, D, lane, kbal);
-  const T* q = static_cast<const T*>(p.q) + (static_cast<size_t>(b) * p.Hq + hkv * G) * D;
-  constexpr int kQLoads = kMaxG * FA_MAX_HEAD_DIM / 8 / kBlock;   // 8-element vectors per thread
-  Frag<T> qv[kQLoads];
-  const int nq8 = G * D / 8;
+  const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
+  const T* q = static_cast<const T*>(p.q) + hq0 * D;
+  constexpr int kQElems = kMaxG * FA_MAX_HEAD_DIM / kBlock;   // query elements per thread (worst case)
+  const int nqe = G * D;
+  T qe[kQElems];
 #pragma unroll
-  for (int i = 0; i < kQLoads; ++i) qv[i].load(q + 8 * min(tid + i * kBlock, nq8 - 1));
+  for (int i = 0; i < kQElems; ++i) qe[i] = q[min(tid + i * kBlock, nqe - 1)];
 
 #pragma unroll
   for (int i = 0; i < kPrepLoads; ++i) {
@@ -249,17 +276,24 @@ __global__ __launch_bounds__(kBlock) void decode_prepare(DecodeParams p) {
       crow[r * ld + col] = (m0 + r < p.M) ? cval[i] : 0.0f;
     }
   }
+  // q splits into its compressed dims (fp32, for the products below) and its kept dims (packed and
+  // zero padded for the K^mu products of decode_partial; written by the first workgroup of the row)
+  const int kpitch = (p.Dku + 7) & ~7;
+  const int Dkq = (kpitch + 31) / 32 * 32;
+  T* qkeep = static_cast<T*>(p.qkeep) + hq0 * Dkq;
 #pragma unroll
-  for (int i = 0; i < kQLoads; ++i) {
-    const int v8 = tid + i * kBlock;
-    if (v8 < nq8) {
-      const int h = (8 * v8) / D, d0 = (8 * v8) % D;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int r = dim_rank(kbal, d0 + e);
-        if (r < 0) qc[h * Dkc + (-r - 1)] = to_f32(frag_elem(qv[i], e));
-      }
+  for (int i = 0; i < kQElems; ++i) {
+    const int it = tid + i * kBlock;
+    if (it < nqe) {
+      const int h = it / D, d = it % D;
+      const int r = dim_rank(kbal, d);
+      if (r < 0) qc[h * Dkc + (-r - 1)] = to_f32(qe[i]);
+      else if (blockIdx.x == 0) qkeep[h * Dkq + r] = qe[i];
     }
+  }
+  if (blockIdx.x == 0) {
+    const int npad = Dkq - p.Dku;
+    for (int it = tid; it < G * npad; it += kBlock) qkeep[(it / npad) * Dkq + p.Dku + it % npad] = T{};
   }
   __syncthreads();
 
@@ -386,8 +420,9 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
   }
   __syncthreads();
 
-  float* part = p.part + (hq0 * (p.Sw + p.Sm) + blockIdx.x) * p.rec;
-  const size_t part_h = static_cast<size_t>(p.Sw + p.Sm) * p.rec;
+  // record of head h: [max, sum, -, -, acc[D]]
+  float* part = p.part_w + (hq0 * p.Sw + s) * p.recw;
+  const size_t part_h = static_cast<size_t>(p.Sw) * p.recw;
   if (tid < G) {
     part[tid * part_h + 0] = mx[tid];
     part[tid * part_h + 1] = lsum[tid];
@@ -431,7 +466,7 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
         float v = 0.0f;
 #pragma unroll 8
         for (int k = 0; k < nts; ++k) v += red[(k * 4 + hh) * D + d];
-        part[(hg + hh) * part_h + 2 + d] = v;
+        part[(hg + hh) * part_h + 4 + d] = v;
       }
     }
   }
@@ -441,322 +476,351 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
 // ---------------------------------------------------------------------------
 // 2b. middle rows: kept dims streamed, compressed dims through the series
 // ---------------------------------------------------------------------------
-template <typename T, int NCH, int DVTM>
+// The four waves of a workgroup walk the same steps (KT tiles of 64 rows x the
+// query heads of the group) and divide the work of every step:
+//   * the series by harmonics: wave w owns orders 16 CW w + 1 .. 16 CW (w + 1)
+//     on both sides; its slices of the E table (K side: A operands, V side: B
+//     operands) are built once and stay in registers;
+//   * the kept dims by rows: wave w multiplies a quarter of the step's K^mu row
+//     blocks and a quarter of its V^mu token blocks.
+// The partial scores are summed across the waves through LDS (the only barrier
+// of a step); every wave then runs the same online softmax on the full scores.
+constexpr int kVU = 2;                                        // V^mu token blocks per wave and step
+constexpr unsigned kXchgBytes = 2 * kWaves * kRB * 64 * 16;   // double-buffered score exchange
+
+// cos / sin of 2 pi n u / T for a table entry (n u < 2^24): exact integer phase
+template <typename T>
+__device__ __forceinline__ void table_cs(int n, int u, int period, float inv_period, float* c, float* s) {
+  const int prod = n * u;
+  int ph = prod - static_cast<int>(static_cast<float>(prod) * inv_period) * period;   // quotient exact to +-1
+  if (ph < 0) ph += period;
+  if (ph >= period) ph -= period;
+  if constexpr (sizeof(T) == 4) {
+    sincospif(2.0f * (static_cast<float>(ph) / static_cast<float>(period)), s, c);
+  } else {
+    const float x = static_cast<float>(ph) * inv_period;
+    *s = __builtin_amdgcn_sinf(x);
+    *c = __builtin_amdgcn_cosf(x);
+  }
+}
+
+template <typename T, int CW, int DVTM>
 __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsigned char* smem) {
   using ES = typename SeriesType<T>::type;
-  constexpr int Mint = NCH * 32;
-  constexpr int kPitchA = Mint * sizeof(ES) + 16;   // bytes per E_A row
-  constexpr int kPitchB = kTJ * sizeof(ES) + 16;    // bytes per E_B row
+  constexpr int Mint = kWaves * CW * 32;
   constexpr int kQLoads = kMaxG * FA_MAX_HEAD_DIM / 8 / kBlock;
-  constexpr int kGLoads = kMaxG * Mint / 4 / kBlock;   // >= 1 since Mint >= 64
-  // V^mu operands of a whole step are requested at once when they fit in registers (they reuse
-  // the registers of the K^mu operands, which are consumed by then)
+  // V^mu operands are requested a step ahead when they fit in registers
   constexpr bool kPrefetchV = DVTM <= 2;
+  constexpr int kVR = kPrefetchV ? DVTM : 1;
 
   const int sm_idx = blockIdx.x, bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
-  const int G = p.G, Gp = p.Gp, KT = p.KT, D = p.D;
+  const int G = p.G, Gp = p.Gp, KT = p.KT;
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps step offsets scalar
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps unit ids scalar
   const int q4 = lane >> 4, r16 = lane & 15;
   const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
   const int c0 = sm_idx * p.chunk_m, c1 = min(p.N, c0 + p.chunk_m);   // chunk of middle rows
-  const int wstep = KT * kTJ;                                          // rows per wave step
-  const int stride = kWaves * wstep;
-
-  // ---- LDS carve-up -------------------------------------------------------
-  unsigned char* eA = smem;                                   // [kRB*16][pitchA]
-  unsigned char* eB = smem + kTJ * kPitchA;                   // [Mint][pitchB]
-  float* red = reinterpret_cast<float*>(smem);                // aliases everything after the loop
-  unsigned char* aux = smem + p.lds_tab;
-  float* gs_s = reinterpret_cast<float*>(aux);                // [Gp][Mint]
-  T* qk_s = reinterpret_cast<T*>(aux + Gp * Mint * 4);        // [Gp][FA_MAX_HEAD_DIM]
-  __shared__ float g0_s[kMaxG];
-  __shared__ float stat_m[kWaves * 16], stat_l[kWaves * 16], mstar[kMaxG], lstar[kMaxG];
-
-  // ---- per-lane roles ---------------------------------------------------------
-  const int col_k = r16 / Gp, col_h = r16 % Gp;      // S column = (tile, head)
+  const int step = KT * kTJ;                                           // rows per step
+  const int col_k = r16 / Gp, col_h = r16 % Gp;                        // S column = (tile, head)
   const bool col_live = col_k < KT && col_h < G;
+  const int hsafe = min(col_h, G - 1);
   const int DVT = (p.Dvu + 15) / 16;
   const int kpitch = (p.Dku + 7) & ~7;               // K^mu rows are padded to 8 columns
   const int kchunks = (kpitch + 31) / 32;
-  const bool kragged = (kpitch & 31) != 0, vragged = (p.Dvu & 15) != 0;
+  const int Dkq = kchunks * 32;                      // pitch of the packed query rows (zero padded)
+  const bool vragged = (p.Dvu & 15) != 0;
   const T* kk = static_cast<const T*>(p.k_keep) + bh * p.kk_stride;
   const T* vk = static_cast<const T*>(p.v_keep) + bh * p.vk_stride;
   const int Nm1 = p.N - 1;
+  const int NV = KT >= 2 ? KT / 2 : 1;               // V^mu token blocks of this wave per step
 
-  // K^mu rows of one wave step, dims [32*cc, 32*cc+32): 4 tiles x 4 row blocks.
-  // A step that lies wholly inside the chunk addresses its operands as (uniform
-  // offset) + (one per-lane offset); the last, ragged step clamps every row into
-  // the slab instead (rows past the chunk are masked at the softmax).  Columns
-  // past the row pitch are zeroed in both cases.
-  const uint32_t lane_k = (8u * (r16 >> 2) + (r16 & 3)) * static_cast<uint32_t>(kpitch);
-  auto load_k = [&](Frag<T> (&kf)[kMaxKT][kRB], int base, int cc) {
-    const int d0 = cc * 32 + 8 * q4;
-    const uint32_t dcl = static_cast<uint32_t>(min(d0, kpitch - 8));
-    const bool dead = kragged && d0 >= kpitch;
-    if (base + wstep <= c1) {
-      const T* lp = kk + (lane_k + dcl);
-#pragma unroll
-      for (int k = 0; k < kMaxKT; ++k) {
-        if (k < KT) {
-#pragma unroll
-          for (int rb = 0; rb < kRB; ++rb) {
-            const uint32_t urow = static_cast<uint32_t>(base + k * kTJ + 32 * (rb >> 1) + 4 * (rb & 1));
-            kf[k][rb].load(lp + urow * static_cast<uint32_t>(kpitch));
-            if (dead) kf[k][rb].zero();
-          }
-        }
-      }
-    } else {
-#pragma unroll
-      for (int k = 0; k < kMaxKT; ++k) {
-        if (k < KT) {
-#pragma unroll
-          for (int rb = 0; rb < kRB; ++rb) {
-            const int u = 32 * (rb >> 1) + 8 * (r16 >> 2) + 4 * (rb & 1) + (r16 & 3);
-            const int j = min(base + k * kTJ + u, Nm1);
-            kf[k][rb].load(kk + (static_cast<uint32_t>(j) * static_cast<uint32_t>(kpitch) + dcl));
-            if (dead) kf[k][rb].zero();
-          }
-        }
-      }
-    }
+  // ---- LDS carve-up -------------------------------------------------------
+  f32x4* xs = reinterpret_cast<f32x4*>(smem);                   // [2][kWaves][kRB][64]
+  float* red_r = reinterpret_cast<float*>(smem);                // after the loop: [16][Mint + 4]
+  const int pr = Mint + 4, po = 16 * DVT + 4;
+  float* red_o = red_r + 16 * pr;                               // [kWaves][16][16 DVT + 4]
+  constexpr int kPitchG = Mint + 32;                            // floats per row of gs_s
+  float* gs_s = reinterpret_cast<float*>(smem + p.lds_tab);     // [G][kPitchG] series coefficients
+  T* qk_s = reinterpret_cast<T*>(gs_s + G * kPitchG);           // [G][Dkq]
+
+  // K^mu row block uid of the step at `base` (tile uid / 4, row block uid % 4), dims
+  // [32 cc, 32 cc + 32).  Rows are clamped into the slab (rows past the chunk are
+  // masked at the softmax); columns past the row pitch re-read the row's last 8
+  // columns, where the packed query is zero.
+  auto k_ptr = [&](int base, int uid, int cc) -> const T* {
+    const int k = uid >> 2, rb = uid & 3;
+    const int u = 32 * (rb >> 1) + 8 * (r16 >> 2) + 4 * (rb & 1) + (r16 & 3);
+    const int j = min(base + k * kTJ + u, Nm1);
+    const int dcl = min(cc * 32 + 8 * q4, kpitch - 8);
+    return kk + (static_cast<uint32_t>(j) * static_cast<uint32_t>(kpitch) + static_cast<uint32_t>(dcl));
   };
-  // V^mu operand of tile k, contraction step x, dim tile dt: 8 consecutive rows of one dim.
-  // Rows past the chunk are zeroed (their softmax weight is 0, but 0 * garbage must stay 0).
-  const uint32_t lane_v = (static_cast<uint32_t>(q4) * static_cast<uint32_t>(p.Dvu) + r16) * 8u;
-  auto load_v = [&](Frag<T>& bv, int base, bool tail, int k, int x, int dt) {
-    if (!tail && !vragged) {
-      const uint32_t ug = static_cast<uint32_t>((base + k * kTJ + 32 * x) >> 3);
-      bv.load(vk + lane_v + (ug * static_cast<uint32_t>(p.Dvu) + 16u * dt) * 8u);
-    } else {
-      const int tok0 = base + k * kTJ + 32 * x + 8 * q4;   // multiple of 8
-      const int dim = 16 * dt + r16;
-      const uint32_t g8 = static_cast<uint32_t>(min(tok0, Nm1) >> 3);
-      bv.load(vk + (g8 * static_cast<uint32_t>(p.Dvu) + static_cast<uint32_t>(min(dim, p.Dvu - 1))) * 8u);
-      if (vragged && dim >= p.Dvu) bv.zero();
-      if (tail && tok0 + 8 > c1) mask_tail(bv, c1 - tok0);
+  // V^mu token block vid (tile vid / 2, half vid % 2), dim tile dt: 8 consecutive rows of one dim
+  auto v_ptr = [&](int base, int vid, int dt) -> const T* {
+    const int tok0 = base + (vid >> 1) * kTJ + 32 * (vid & 1) + 8 * q4;   // multiple of 8
+    const int dim = min(16 * dt + r16, p.Dvu - 1);
+    const uint32_t g8 = static_cast<uint32_t>(min(tok0, Nm1)) >> 3;
+    return vk + (g8 * static_cast<uint32_t>(p.Dvu) + static_cast<uint32_t>(dim)) * 8u;
+  };
+  // applied when the operand is consumed, so that the loads stay asynchronous: rows past
+  // the chunk and dims past Dvu are zeroed (their weight is 0, but 0 * garbage must stay 0)
+  auto fix_v = [&](Frag<T>& bv, int base, int vid, int dt) {
+    const int tok0 = base + (vid >> 1) * kTJ + 32 * (vid & 1) + 8 * q4;
+    if (16 * dt + r16 >= p.Dvu) bv.zero();
+    if (tok0 + 8 > c1) mask_tail(bv, c1 - tok0);
+  };
+  auto load_step = [&](Frag<T> (&kf)[kMaxKT], Frag<T> (&vf)[kVU][kVR], int base) {
+    if (kchunks > 0) {
+#pragma unroll
+      for (int i = 0; i < kMaxKT; ++i)
+        if (i < KT) kf[i].load(k_ptr(base, wave * KT + i, 0));
+    }
+    if constexpr (kPrefetchV) {
+      if (DVT > 0) {
+#pragma unroll
+        for (int i = 0; i < kVU; ++i) {
+          const int vid = wave * NV + i;
+          if (i < NV && vid < 2 * KT) {
+#pragma unroll
+            for (int dt = 0; dt < DVTM; ++dt)
+              if (dt < DVT) vf[i][dt].load(v_ptr(base, vid, dt));
+          }
+        }
+      }
     }
   };
 
   FA_STAMP(0);
   // ---- (0) everything that comes from global memory is requested first ------------
-  const int base0 = c0 + wave * wstep;
-  uint8_t kmb[4], vmb[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    kmb[j] = p.kmask[static_cast<size_t>(bh) * D + min(lane + 64 * j, D - 1)];
-    vmb[j] = p.vmask[static_cast<size_t>(bh) * D + min(lane + 64 * j, D - 1)];
-  }
-  const T* q = static_cast<const T*>(p.q) + hq0 * D;
-  const int nq8 = G * D / 8;
-  Frag<T> qv[kQLoads];
-#pragma unroll
-  for (int i = 0; i < kQLoads; ++i) qv[i].load(q + 8 * min(tid + i * kBlock, nq8 - 1));
   // series coefficients of the group: G * Mint contiguous floats
+  constexpr int kGLoads = kMaxG * Mint / 4 / kBlock;
   const int ng4 = G * Mint / 4;
   f32x4 gv[kGLoads];
 #pragma unroll
   for (int i = 0; i < kGLoads; ++i)
     gv[i] = *reinterpret_cast<const f32x4*>(p.gs + hq0 * Mint + 4 * min(tid + i * kBlock, ng4 - 1));
-  const float g0v = p.g0[hq0 + min(tid, G - 1)];
-  Frag<T> kf[kMaxKT][kRB];
-  if (kchunks > 0 && base0 < c1) load_k(kf, base0, 0);
+  const float g0 = p.g0[hq0 + hsafe];
+  const int nq8 = G * Dkq / 8;
+  Frag<T> qv[kQLoads];
+  if (nq8 > 0) {
+    const T* qsrc = static_cast<const T*>(p.qkeep) + hq0 * Dkq;
+#pragma unroll
+    for (int i = 0; i < kQLoads; ++i) qv[i].load(qsrc + 8 * min(tid + i * kBlock, nq8 - 1));
+  }
+  Frag<T> kfA[kMaxKT], kfB[kMaxKT];
+  Frag<T> vfA[kVU][kVR], vfB[kVU][kVR];
+  load_step(kfA, vfA, c0);
 
   FA_STAMP(1);
-  // ---- zero fills that do not depend on anything loaded ---------------------------------
-  for (int it = tid; it < Gp * FA_MAX_HEAD_DIM; it += kBlock) qk_s[it] = T{};
-  for (int it = tid; it < (Gp - G) * Mint; it += kBlock) gs_s[G * Mint + it] = 0.0f;
-
-  // ---- E tables: E[u][slot] = cos/sin(2 pi n u / T), n = slot/2 + 1 ----------
-  // E_A rows are stored row-block-major (row 16*rb + i holds u(rb,i)); E_B rows
-  // are V-side series indices, columns are u.
+  // ---- this wave's slices of the E table ------------------------------------------------------
+  // K side, A operand of (own chunk i, row block rb): row u(rb, r16), slots 8 q4 .. 8 q4 + 7 of the
+  // chunk = (cos, sin) of 4 consecutive orders.  V side, B operand of (own chunk i, cos | sin,
+  // half x): order 16 c + r16 + 1 at the 8 consecutive rows 32 x + 8 q4 ...
+  Frag<ES> eA[CW][kRB], eB[CW][2][kXN];
   {
     const int n_max = p.M / 2;
     const float invT = 1.0f / static_cast<float>(p.T);
-    for (int it = tid; it < (Mint / 2) * (kTJ / 8); it += kBlock) {
-      const int o = it % (Mint / 2), ug = it / (Mint / 2);
-      const int n = o + 1;
-      float cs[8], sn[8];
-      if (n <= n_max) {
-        // phase numerator (n * u) mod T; n * u < 2^24, so one float quotient estimate is exact to +-1
-        const int prod = n * (8 * ug);
-        int ph = prod - static_cast<int>(static_cast<float>(prod) * invT) * p.T;
-        if (ph < 0) ph += p.T;
-        if (ph >= p.T) ph -= p.T;
+    if constexpr (sizeof(ES) == 4) {
+      // fp32 tables: every entry evaluated on its own
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          if constexpr (sizeof(T) == 4) {
-            sincospif(2.0f * (static_cast<float>(ph) / static_cast<float>(p.T)), &sn[e], &cs[e]);
-          } else {
-            const float x = static_cast<float>(ph) * invT;
-            sn[e] = __builtin_amdgcn_sinf(x);
-            cs[e] = __builtin_amdgcn_cosf(x);
+      for (int i = 0; i < CW; ++i) {
+        const int c = wave * CW + i;
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb) {
+          const int u = 32 * (rb >> 1) + 8 * (r16 >> 2) + 4 * (rb & 1) + (r16 & 3);
+          float vals[8];
+#pragma unroll
+          for (int hp = 0; hp < 4; ++hp) {
+            const int n = 16 * c + 4 * q4 + hp + 1;
+            vals[2 * hp] = vals[2 * hp + 1] = 0.0f;
+            if (n <= n_max) table_cs<T>(n, u, p.T, invT, &vals[2 * hp], &vals[2 * hp + 1]);
           }
-          ph += n;
-          if (ph >= p.T) ph -= p.T;
+          pack8(eA[i][rb], vals);
         }
-      } else {
+        const int n = 16 * c + r16 + 1;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) cs[e] = sn[e] = 0.0f;
-      }
-      // E_A: (cos, sin) of order n are slots 2o, 2o+1 of row u
-      const int x = ug >> 2, a = ug & 3;
+        for (int x = 0; x < kXN; ++x) {
+          float cs[8], sn[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int row = 16 * (2 * x + (e >> 2)) + 4 * a + (e & 3);
-        ES* dst = reinterpret_cast<ES*>(eA + row * kPitchA) + 2 * o;
-        if constexpr (sizeof(ES) == 4) {
-          dst[0] = cs[e];
-          dst[1] = sn[e];
-        } else {
-          *reinterpret_cast<uint32_t*>(dst) =
-              __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{cs[e], sn[e]}, f16x2));
+          for (int e = 0; e < 8; ++e) {
+            cs[e] = sn[e] = 0.0f;
+            if (n <= n_max) table_cs<T>(n, 32 * x + 8 * q4 + e, p.T, invT, &cs[e], &sn[e]);
+          }
+          pack8(eB[i][0][x], cs);
+          pack8(eB[i][1][x], sn);
         }
       }
-      // E_B: rows iota = 32*(o/16) + (o%16) [cos], +16 [sin]; 8 consecutive u
-      const int iota = 32 * (o >> 4) + (o & 15);
-      Frag<ES> fc, fs;
-      pack8(fc, cs);
-      pack8(fs, sn);
-      ES* bc = reinterpret_cast<ES*>(eB + iota * kPitchB) + 8 * ug;
-      ES* bs = reinterpret_cast<ES*>(eB + (iota + 16) * kPitchB) + 8 * ug;
-      if constexpr (sizeof(ES) == 4) {
+    } else {
+      // 16-bit tables.  K side: the first of a lane's 4 consecutive orders is evaluated, the others
+      // follow by the angle-addition step of its row.  V side: the same entries, transposed through a
+      // wave-private LDS tile [slot][row] one chunk at a time.
+      constexpr int kPitchT = 2 * kTJ + 16;   // bytes per slot row of the transpose tile
+      unsigned char* et = smem + wave * (32 * kPitchT);
+      int urow[kRB];
+      float cd[kRB], sd[kRB];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          bc[e] = fc.v[e];
-          bs[e] = fs.v[e];
+      for (int rb = 0; rb < kRB; ++rb) {
+        urow[rb] = 32 * (rb >> 1) + 8 * (r16 >> 2) + 4 * (rb & 1) + (r16 & 3);
+        table_cs<T>(1, urow[rb], p.T, invT, &cd[rb], &sd[rb]);
+      }
+#pragma unroll
+      for (int i = 0; i < CW; ++i) {
+        const int n0 = 16 * (wave * CW + i) + 4 * q4 + 1;
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb) {
+          float vals[8];
+          table_cs<T>(n0, urow[rb], p.T, invT, &vals[0], &vals[1]);
+#pragma unroll
+          for (int hp = 1; hp < 4; ++hp) {
+            vals[2 * hp] = vals[2 * hp - 2] * cd[rb] - vals[2 * hp - 1] * sd[rb];
+            vals[2 * hp + 1] = vals[2 * hp - 1] * cd[rb] + vals[2 * hp - 2] * sd[rb];
+          }
+#pragma unroll
+          for (int hp = 0; hp < 4; ++hp)
+            if (n0 + hp > n_max) vals[2 * hp] = vals[2 * hp + 1] = 0.0f;
+          pack8(eA[i][rb], vals);
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            *reinterpret_cast<uint16_t*>(et + (8 * q4 + e) * kPitchT + 2 * urow[rb]) =
+                static_cast<uint16_t>(eA[i][rb].v[e >> 1] >> (16 * (e & 1)));
         }
-      } else {
-        *reinterpret_cast<u32x4*>(bc) = fc.v;
-        *reinterpret_cast<u32x4*>(bs) = fs.v;
+        __syncthreads();
+#pragma unroll
+        for (int cs = 0; cs < 2; ++cs)
+#pragma unroll
+          for (int x = 0; x < kXN; ++x)
+            eB[i][cs][x].load(reinterpret_cast<const ES*>(et + (2 * r16 + cs) * kPitchT) + 32 * x + 8 * q4);
+        if (i + 1 < CW) __syncthreads();
       }
     }
+  }
+  // the accumulators of the V side live in a frame that moves with the steps: per step
+  // every (cos, sin) pair turns by -omega_n * step, a fixed twiddle per order
+  float tc[CW], ts[CW];
+  {
+    const uint32_t ph_step = phase_of(step, p.ph_scale);
+#pragma unroll
+    for (int i = 0; i < CW; ++i)
+      phase_cs<T>(static_cast<uint32_t>(16 * (wave * CW + i) + r16 + 1) * ph_step, &tc[i], &ts[i]);
   }
   FA_STAMP(2);
-  uint64_t kbal[4], vbal[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    kbal[j] = __ballot(kmb[j] != 0 && lane + 64 * j < D);
-    vbal[j] = __ballot(vmb[j] != 0 && lane + 64 * j < D);
-  }
-  __syncthreads();   // the qk_s zero fill is complete before the gather below
-  FA_STAMP(3);
 
-  // ---- loaded operands into LDS ---------------------------------------------------------
-#pragma unroll
-  for (int i = 0; i < kQLoads; ++i) {
-    const int v8 = tid + i * kBlock;
-    if (v8 < nq8) {
-      const int h = (8 * v8) / D, d0 = (8 * v8) % D;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int r = dim_rank(kbal, d0 + e);
-        if (r >= 0) qk_s[h * FA_MAX_HEAD_DIM + r] = frag_elem(qv[i], e);
-      }
-    }
-  }
+  // ---- series coefficients and packed query into LDS ---------------------------------------------
 #pragma unroll
   for (int i = 0; i < kGLoads; ++i) {
     const int v4 = tid + i * kBlock;
-    if (v4 < ng4) *reinterpret_cast<f32x4*>(gs_s + 4 * v4) = gv[i];
+    if (v4 < ng4) *reinterpret_cast<f32x4*>(gs_s + (4 * v4 / Mint) * kPitchG + (4 * v4) % Mint) = gv[i];
   }
-  if (tid < kMaxG) g0_s[tid] = (tid < G) ? g0v : 0.0f;
-  __syncthreads();
-  FA_STAMP(4);
-
-  f32x4 racc[2 * NCH];          // r' = P^T E, frame of the current step
-  f32x4 oacc[DVTM];             // sum_j p_j V^mu[j,:]
 #pragma unroll
-  for (int t = 0; t < 2 * NCH; ++t) racc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int i = 0; i < kQLoads; ++i) {
+    const int v8 = tid + i * kBlock;
+    if (v8 < nq8) *reinterpret_cast<Frag<T>*>(qk_s + 8 * v8) = qv[i];
+  }
+  __syncthreads();
+  // the second step's operands are requested only now: a wave that asks for more than the memory
+  // pipeline holds stalls at the request, and the table above is better built before that
+  if (c0 + step < c1) load_step(kfB, vfB, c0 + step);
+  FA_STAMP(3);
+
+  f32x4 racc[2 * CW];           // r' = P^T E (own orders), frame of the current step
+  f32x4 oacc[DVTM];             // sum_j p_j V^mu[j,:] over this wave's token blocks
+#pragma unroll
+  for (int t = 0; t < 2 * CW; ++t) racc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int t = 0; t < DVTM; ++t) oacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.0f;   // per S column (replicated over q4); l is a per-lane partial
-  int last_base = c0;                       // origin of this wave's latest step
+  float m_run = -INFINITY, l_run = 0.0f;   // per S column (replicated over q4 and waves); l is a per-lane partial
+  int last_base = c0;                       // origin of the latest step
   const bool quad_share = Gp >= 4;          // the 4 lanes of a quad then share (tile, q4)
-
   bool first = true;
-  for (int base = base0; base < c1; base += stride) {
-    const bool tail = base + wstep > c1;
-    const int next = base + stride;
+  int buf = 0;
+
+  auto do_step = [&](Frag<T> (&kf)[kMaxKT], Frag<T> (&vf)[kVU][kVR], int base) {
+    const bool tail = base + step > c1;
+    [[maybe_unused]] const bool traced = base == c0 + step || c0 + step >= c1;   // developer trace: second step
     f32x4 sacc[kRB];
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // -- (a) series on the K side: S += E g'(tile origin) --------------------------
+    // -- (a) series on the K side, own orders: S += E g'(tile origin) -----------------
     const uint32_t ph_k = phase_of(p.t0 + base + col_k * kTJ, p.ph_scale);
-#pragma unroll 2
-    for (int c = 0; c < NCH; ++c) {
-      float gp[8];
-      const float* gsrc = gs_s + col_h * Mint + 32 * c + 8 * q4;
-      const uint32_t n0 = 16 * c + 4 * q4 + 1;
+#pragma unroll
+    for (int i = 0; i < CW; ++i) {
+      const uint32_t n0 = 16 * (wave * CW + i) + 4 * q4 + 1;
       float csv[4], snv[4];
       if (quad_share) {
         float cs, sn;
         phase_cs<T>((n0 + (lane & 3)) * ph_k, &cs, &sn);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          csv[i] = quad_bcast(cs, i);
-          snv[i] = quad_bcast(sn, i);
+        for (int j = 0; j < 4; ++j) {
+          csv[j] = quad_bcast(cs, j);
+          snv[j] = quad_bcast(sn, j);
         }
       } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) phase_cs<T>((n0 + i) * ph_k, &csv[i], &snv[i]);
+        for (int j = 0; j < 4; ++j) phase_cs<T>((n0 + j) * ph_k, &csv[j], &snv[j]);
       }
+      const float* gl = gs_s + hsafe * kPitchG + 32 * (wave * CW + i) + 8 * q4;
+      const f32x4 ga = *reinterpret_cast<const f32x4*>(gl), gb = *reinterpret_cast<const f32x4*>(gl + 4);
+      float gp[8];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float gc = gsrc[2 * i], gsn = gsrc[2 * i + 1];
-        gp[2 * i] = gc * csv[i] + gsn * snv[i];
-        gp[2 * i + 1] = gsn * csv[i] - gc * snv[i];
+      for (int j = 0; j < 4; ++j) {
+        const float gc = (j < 2) ? ga[2 * (j & 1)] : gb[2 * (j & 1)];
+        const float gsn = (j < 2) ? ga[2 * (j & 1) + 1] : gb[2 * (j & 1) + 1];
+        gp[2 * j] = gc * csv[j] + gsn * snv[j];
+        gp[2 * j + 1] = gsn * csv[j] - gc * snv[j];
       }
       Frag<ES> bg;
       pack8(bg, gp);
       if (!col_live) bg.zero();
 #pragma unroll
-      for (int rb = 0; rb < kRB; ++rb) {
-        Frag<ES> a;
-        a.load(reinterpret_cast<const ES*>(eA + (16 * rb + r16) * kPitchA) + 32 * c + 8 * q4);
-        mma_k32(sacc[rb], a, bg);
-      }
+      for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], eA[i][rb], bg);
     }
 
-    FA_STAMP(5);
-    // -- (b) kept K dims: A = K^mu rows, B = q masked to the tile's columns ------
-    for (int cc = 0; cc < kchunks; ++cc) {
-      if (cc > 0) load_k(kf, base, cc);
-      Frag<T> bq;
-      bq.load(qk_s + col_h * FA_MAX_HEAD_DIM + cc * 32 + 8 * q4);
+    if (traced) FA_STAMP(4);
+    // -- (b) kept K dims, own row blocks: A = K^mu rows, B = q masked to the tile's columns --
+    if (kchunks > 0) {
 #pragma unroll
-      for (int k = 0; k < kMaxKT; ++k) {
-        if (k < KT) {
-          Frag<T> bk = bq;
-          if (col_k != k) bk.zero();
-#pragma unroll
-          for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], kf[k][rb], bk);
+      for (int i = 0; i < kMaxKT; ++i) {
+        if (i < KT) {
+          const int uid = wave * KT + i, k = uid >> 2, rbd = uid & 3;
+          f32x4 ka = {0.f, 0.f, 0.f, 0.f};
+          for (int cc = 0; cc < kchunks; ++cc) {
+            Frag<T> a = kf[i];
+            if (cc > 0) a.load(k_ptr(base, uid, cc));
+            Frag<T> bq;
+            bq.load(qk_s + hsafe * Dkq + cc * 32 + 8 * q4);
+            if (col_k != k || !col_live) bq.zero();
+            mma_k32(ka, a, bq);
+          }
+          if (rbd == 0) sacc[0] += ka;
+          else if (rbd == 1) sacc[1] += ka;
+          else if (rbd == 2) sacc[2] += ka;
+          else sacc[3] += ka;
         }
       }
     }
-    // V^mu operands travel while the softmax and the V-side series run
-    Frag<T> vf[kPrefetchV ? kMaxKT : 1][kXN][kPrefetchV ? DVTM : 1];
-    if constexpr (kPrefetchV) {
-      if (DVT > 0) {
+
+    if (traced) FA_STAMP(5);
+    // -- (c) sum the partial scores of the four waves (fixed order: every wave gets the same bits)
+    {
+      f32x4* xw = xs + ((buf * kWaves + wave) * kRB) * 64 + lane;
 #pragma unroll
-        for (int k = 0; k < kMaxKT; ++k)
-          if (k < KT)
+      for (int rb = 0; rb < kRB; ++rb) xw[rb * 64] = sacc[rb];
+      if (traced) FA_STAMP(6);
+      __syncthreads();
+      if (traced) FA_STAMP(7);
+      const f32x4* xr = xs + (buf * kWaves * kRB) * 64 + lane;
 #pragma unroll
-            for (int x = 0; x < kXN; ++x)
-#pragma unroll
-              for (int dt = 0; dt < DVTM; ++dt)
-                if (dt < DVT) load_v(vf[k][x][dt], base, tail, k, x, dt);
-      }
+      for (int rb = 0; rb < kRB; ++rb)
+        sacc[rb] = ((xr[(0 * kRB + rb) * 64] + xr[(1 * kRB + rb) * 64]) + xr[(2 * kRB + rb) * 64]) +
+                   xr[(3 * kRB + rb) * 64];
+      buf ^= 1;   // two buffers: a wave can be at most one barrier ahead of the slowest reader
     }
 
-    FA_STAMP(6);
-    // -- (c) online softmax per column -----------------------------------------------
+    if (traced) FA_STAMP(8);
+    // -- (d) online softmax per column -----------------------------------------------
     // lane (column, q4) holds rows u = 32x + 8*q4 + 4y + v  (rb = 2x + y)
     float pv[kRB][4];
     float m_tile = -INFINITY;
-    const float g0 = g0_s[col_h];
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
@@ -783,8 +847,8 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
     l_run = l_run * alpha + l_add;
     m_run = m_new;
 
-    FA_STAMP(7);
-    // -- (d) bring the accumulators into this step's frame --------------------------------
+    if (traced) FA_STAMP(9);
+    // -- (e) bring the accumulators into this step's frame --------------------------------
     if (!first) {
       // accumulator rows are S columns 4*q4 + v: fetch their rescale factors
       float al[4];
@@ -794,24 +858,20 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
       for (int t = 0; t < DVTM; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) oacc[t][v] *= al[v];
-      // r' moves to the new origin: rotate every (cos, sin) pair by -omega_n * stride
-      const uint32_t ph_d = phase_of(stride, p.ph_scale);
 #pragma unroll
-      for (int t = 0; t < NCH; ++t) {
-        float cs, sn;
-        phase_cs<T>(static_cast<uint32_t>(16 * t + r16 + 1) * ph_d, &cs, &sn);
+      for (int i = 0; i < CW; ++i)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          const float rc = racc[2 * t][v], rs = racc[2 * t + 1][v];
-          racc[2 * t][v] = al[v] * (cs * rc + sn * rs);
-          racc[2 * t + 1][v] = al[v] * (cs * rs - sn * rc);
+          const float rc = racc[2 * i][v], rs = racc[2 * i + 1][v];
+          racc[2 * i][v] = al[v] * (tc[i] * rc + ts[i] * rs);
+          racc[2 * i + 1][v] = al[v] * (tc[i] * rs - ts[i] * rc);
         }
-      }
     }
     first = false;
     last_base = base;
 
-    // -- (e) V side: r' += P^T E, O += P^T V^mu ---------------------------------------------
+    if (traced) FA_STAMP(10);
+    // -- (f) V side, own orders: r' += P^T E ------------------------------------------------------
     Frag<T> pt[kXN];
 #pragma unroll
     for (int x = 0; x < kXN; ++x) {
@@ -822,86 +882,73 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
       pack8(ps, pe);
       pack8(pt[x], pe);
 #pragma unroll
-      for (int t = 0; t < 2 * NCH; ++t) {
-        Frag<ES> eb;
-        eb.load(reinterpret_cast<const ES*>(eB + (16 * t + r16) * kPitchB) + 32 * x + 8 * q4);
-        mma_k32(racc[t], ps, eb);
-        // keep the table reads next to their MFMAs: hoisting all of them costs ~4 registers each
-        if ((t & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+      for (int i = 0; i < CW; ++i) {
+        mma_k32(racc[2 * i], ps, eB[i][0][x]);
+        mma_k32(racc[2 * i + 1], ps, eB[i][1][x]);
       }
     }
-    FA_STAMP(8);
+    if (traced) FA_STAMP(11);
+    // -- (g) kept V dims, own token blocks: O += P^T V^mu -----------------------------------------
     if (DVT > 0) {
 #pragma unroll
-      for (int k = 0; k < kMaxKT; ++k) {
-        if (k < KT) {
+      for (int i = 0; i < kVU; ++i) {
+        const int vid = wave * NV + i;
+        if (i < NV && vid < 2 * KT) {
+          Frag<T> ak = pt[0];   // select by value: an lvalue choice would put both fragments in memory
+          const Frag<T> p1 = pt[1];
+          if (vid & 1) ak = p1;
+          if (col_k != (vid >> 1)) ak.zero();
 #pragma unroll
-          for (int x = 0; x < kXN; ++x) {
-            Frag<T> ak = pt[x];
-            if (col_k != k) ak.zero();
-            if constexpr (kPrefetchV) {
-#pragma unroll
-              for (int dt = 0; dt < DVTM; ++dt)
-                if (dt < DVT) mma_k32(oacc[dt], ak, vf[k][x][dt]);
-            } else {
-              Frag<T> bv[DVTM];
-#pragma unroll
-              for (int dt = 0; dt < DVTM; ++dt)
-                if (dt < DVT) load_v(bv[dt], base, tail, k, x, dt);
-#pragma unroll
-              for (int dt = 0; dt < DVTM; ++dt)
-                if (dt < DVT) mma_k32(oacc[dt], ak, bv[dt]);
+          for (int dt = 0; dt < DVTM; ++dt) {
+            if (dt < DVT) {
+              Frag<T> bv;
+              if constexpr (kPrefetchV) bv = vf[i][dt];
+              else bv.load(v_ptr(base, vid, dt));
+              if (tail || vragged) fix_v(bv, base, vid, dt);
+              mma_k32(oacc[dt], ak, bv);
             }
           }
         }
       }
     }
-    // the K operands of this wave's next step travel during its series evaluation
-    if (kchunks > 0 && next < c1) load_k(kf, next, 0);
+    if (traced) FA_STAMP(12);
+  };
+
+  // two steps per trip: the operands of a step are requested while the step before it runs
+  for (int base = c0; base < c1; base += 2 * step) {
+    do_step(kfA, vfA, base);
+    if (base + 2 * step < c1) load_step(kfA, vfA, base + 2 * step);
+    if (base + step < c1) {
+      do_step(kfB, vfB, base + step);
+      if (base + 3 * step < c1) load_step(kfB, vfB, base + 3 * step);
+    }
   }
 
-  FA_STAMP(9);
-  // ---- merge tiles and waves --------------------------------------------------------------
+  FA_STAMP(13);
+  // ---- merge the tiles of a head --------------------------------------------------------------
   l_run += __shfl_xor(l_run, 16, kWave);
   l_run += __shfl_xor(l_run, 32, kWave);
-  if (q4 == 0) {
-    stat_m[wave * 16 + r16] = col_live ? m_run : -INFINITY;
-    stat_l[wave * 16 + r16] = col_live ? l_run : 0.0f;
-  }
-  __syncthreads();   // also: every wave is done with the E tables and the aux region
-  FA_STAMP(10);
-  if (tid < G) {
-    float m = -INFINITY;
-    for (int w = 0; w < kWaves; ++w)
-      for (int k = 0; k < KT; ++k) m = fmaxf(m, stat_m[w * 16 + k * Gp + tid]);
-    float l = 0.0f;
-    for (int w = 0; w < kWaves; ++w)
-      for (int k = 0; k < KT; ++k) {
-        const float mm = stat_m[w * 16 + k * Gp + tid];
-        if (mm != -INFINITY) l += stat_l[w * 16 + k * Gp + tid] * __expf(mm - m);
-      }
-    mstar[tid] = m;
-    lstar[tid] = l;
-  }
-  __syncthreads();
+  const float mc = col_live ? m_run : -INFINITY;
+  const float mstar = row_stride_max(mc, Gp);   // the columns of one head are Gp lanes apart
+  const float fc = (mc != -INFINITY) ? __expf(mc - mstar) : 0.0f;
+  const float lstar = row_stride_sum(col_live ? l_run * fc : 0.0f, Gp);
+  __syncthreads();   // every wave has read the last score exchange: the region is reused below
 
-  // every wave rotates its r' rows to the global frame, scales rows to the chunk
-  // maximum and parks them in LDS: red[wave][row][Mint + 16*DVT]
-  const int redw = Mint + 16 * DVT;
+  // every wave rotates its r' rows to the global frame, scales rows to the head's maximum and
+  // parks them in LDS: red_r[row][own orders], red_o[wave][row][kept dims]
   {
     float f[4];
     uint32_t phr[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      const int row = 4 * q4 + v, k = row / Gp, h = row % Gp;
-      const float mm = stat_m[wave * 16 + row];
-      f[v] = (k < KT && h < G && mm != -INFINITY) ? __expf(mm - mstar[h]) : 0.0f;
-      phr[v] = phase_of(p.t0 + last_base + k * kTJ, p.ph_scale);
+      const int row = 4 * q4 + v;
+      f[v] = __shfl(fc, row, kWave);
+      phr[v] = phase_of(p.t0 + last_base + (row / Gp) * kTJ, p.ph_scale);
     }
-    float* dst = red + static_cast<size_t>(wave) * 16 * redw;
 #pragma unroll
-    for (int t = 0; t < NCH; ++t) {
-      const uint32_t n = 16 * t + r16 + 1;
+    for (int i = 0; i < CW; ++i) {
+      const int c = wave * CW + i;
+      const uint32_t n = 16 * c + r16 + 1;
       float cs[4], sn[4];
       phase_cs<T>(n * phr[0], &cs[0], &sn[0]);
       if (quad_share) {   // rows 4*q4 .. 4*q4+3 belong to one tile
@@ -916,55 +963,56 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
       }
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const float rc = racc[2 * t][v], rs = racc[2 * t + 1][v];
-        const int row = 4 * q4 + v;
-        dst[row * redw + 32 * t + r16] = f[v] * (cs[v] * rc - sn[v] * rs);
-        dst[row * redw + 32 * t + 16 + r16] = f[v] * (sn[v] * rc + cs[v] * rs);
+        const float rc = racc[2 * i][v], rs = racc[2 * i + 1][v];
+        float* dst = red_r + (4 * q4 + v) * pr + 32 * c + r16;
+        dst[0] = f[v] * (cs[v] * rc - sn[v] * rs);
+        dst[16] = f[v] * (sn[v] * rc + cs[v] * rs);
       }
     }
+    float* ro = red_o + wave * 16 * po;
 #pragma unroll
     for (int dt = 0; dt < DVTM; ++dt)
       if (dt < DVT)
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-          dst[(4 * q4 + v) * redw + Mint + 16 * dt + r16] = f[v] * oacc[dt][v];
+        for (int v = 0; v < 4; ++v) ro[(4 * q4 + v) * po + 16 * dt + r16] = f[v] * oacc[dt][v];
   }
   __syncthreads();
-  FA_STAMP(11);
+  FA_STAMP(14);
 
-  float* part = p.part + (hq0 * (p.Sw + p.Sm) + blockIdx.x) * p.rec;
-  const size_t part_h = static_cast<size_t>(p.Sw + p.Sm) * p.rec;
-  if (tid < G) {
-    part[tid * part_h + 0] = mstar[tid];
-    part[tid * part_h + 1] = lstar[tid];
+  // record of head h: [max, sum, -, -, acc over the kept dims (16 DVT), r (Mint, V-side order)]
+  const size_t rec_h = static_cast<size_t>(p.Sm) * p.recm;
+  float* rec0 = p.part_m + (hq0 * p.Sm + sm_idx) * p.recm;
+  if (wave == 0 && lane < G) {   // lane = column (tile 0, head lane): holds the head's merged statistics
+    rec0[lane * rec_h + 0] = mstar;
+    rec0[lane * rec_h + 1] = lstar;
   }
-  // r[h][iota] and acc[h][dim] = sum over waves and tiles
-  for (int it = tid; it < G * (D + Mint); it += kBlock) {
-    const int h = it / (D + Mint), x = it % (D + Mint);
-    int src;   // column of the reduction rows, or -1 for a dim that middle rows do not carry
-    if (x < D) {
-      const int r = dim_rank(vbal, x);
-      src = (r >= 0) ? Mint + r : -1;
-    } else {
-      src = x - D;
-    }
-    float v = 0.0f;
-    if (src >= 0) {
+  const int no4 = 4 * DVT, nr4 = Mint / 4, per = no4 + nr4;
+  for (int it = tid; it < G * per; it += kBlock) {
+    {
+      const int h = it / per, x4 = it - h * per;
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (x4 < no4) {
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w)
+        for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+          for (int k = 0; k < kMaxKT; ++k)
+            if (k < KT) v += *reinterpret_cast<const f32x4*>(red_o + ((w * 16 + k * Gp + h) * po + 4 * x4));
+      } else {
+        const int y = x4 - no4;
 #pragma unroll
         for (int k = 0; k < kMaxKT; ++k)
-          if (k < KT) v += red[(w * 16 + k * Gp + h) * redw + src];
+          if (k < KT) v += *reinterpret_cast<const f32x4*>(red_r + ((k * Gp + h) * pr + 4 * y));
+      }
+      *reinterpret_cast<f32x4*>(rec0 + h * rec_h + 4 + 4 * x4) = v;
     }
-    part[h * part_h + 2 + x] = v;
   }
-  FA_STAMP(12);
+  FA_STAMP(15);
 }
 
-template <typename T, int NCH, int DVTM>
-__global__ __launch_bounds__(kBlock) void decode_partial(DecodeParams p) {
+template <typename T, int CW, int DVTM>
+__global__ __launch_bounds__(kBlock, (CW <= 2 && sizeof(T) == 2) ? 2 : 1) void decode_partial(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  if (static_cast<int>(blockIdx.x) < p.Sm) partial_middle_rows<T, NCH, DVTM>(p, smem);
+  if (static_cast<int>(blockIdx.x) < p.Sm) partial_middle_rows<T, CW, DVTM>(p, smem);
   else partial_full_rows<T>(p, smem);
 }
 
@@ -973,45 +1021,51 @@ __global__ __launch_bounds__(kBlock) void decode_partial(DecodeParams p) {
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
-  __shared__ float rr[FA_MAX_DECODE_STATES];   // r in basis order, weighted
-  __shared__ float accs[FA_MAX_HEAD_DIM];
-  __shared__ float es[kMaxPartials];
-  __shared__ float red[kFinBlock];
-  __shared__ float wred[kFinBlock / 64];
-  __shared__ float stat[2];
+  constexpr int kNW = kFinBlock / 64;
+  __shared__ float es[kMaxPartials];                                 // e^{m_s - m} per record
+  __shared__ f32x4 redm[kFinBlock], redw[kFinBlock];                 // per-thread partial sums
+  __shared__ float colm[16 * kMaxDvTiles + FA_MAX_DECODE_STATES];    // middle records merged: acc (kept order), r
+  __shared__ float colw[FA_MAX_HEAD_DIM];                            // full-row records merged
+  __shared__ float rr[FA_MAX_DECODE_STATES];                         // r in basis order, weighted
+  __shared__ float wmax[kNW], wsum[kNW], wsum_m[kNW];
 
   const int hq = blockIdx.x, b = hq / p.Hq, hkv = (hq % p.Hq) / p.G;
   const int bh = b * p.Hkv + hkv;
-  const int D = p.D, M = p.M, S = p.Sw + p.Sm, Dvc = p.Dvc;
+  const int D = p.D, M = p.M, Sm = p.Sm, Sw = p.Sw, S = Sm + Sw, Dvc = p.Dvc;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  constexpr int kNW = kFinBlock / 64;
-  const float* part = p.part + static_cast<size_t>(hq) * S * p.rec;
-  const size_t rec = p.rec;
+  const int Dva = 16 * ((p.Dvu + 15) / 16);
+  const int recm = p.recm, recw = p.recw;
+  const float* pm = p.part_m + static_cast<size_t>(hq) * Sm * recm;
+  const float* pw = p.part_w + static_cast<size_t>(hq) * Sw * recw;
 
   // ---- every global operand is requested before anything is consumed -------------------
-  // (1) chunk maxima and sums
+  // (1) chunk maxima and sums (S <= kMaxPartials = kFinBlock: one record per thread)
   const int s_me = min(tid, S - 1);
-  const float ms_me = part[s_me * rec], ls_me = part[s_me * rec + 1];
-  // (2) acc[d] over chunks: thread (d, group ga) takes chunks ga, ga+nga, ...
-  constexpr int kU = 8;
-  const int nga = kFinBlock / D;
-  const int d_a = tid % D, ga = tid / D;
-  float av[kU];
+  const float* r_me = (s_me < Sm) ? pm + static_cast<size_t>(s_me) * recm
+                                  : pw + static_cast<size_t>(s_me - Sm) * recw;
+  const float ms_me = r_me[0], ls_me = r_me[1];
+  // (2) columns of the middle records: thread (4 columns c4m, group gm) takes records gm, gm + ngm, ...
+  const int cm4 = (Dva + p.Mint) / 4;
+  const int ngm = kFinBlock / cm4;
+  const int c4m = tid % cm4, gm = tid / cm4;
+  constexpr int kU = 5;
+  f32x4 mv[kU];
+  if (Sm > 0) {
 #pragma unroll
-  for (int u = 0; u < kU; ++u) av[u] = part[min(ga + u * nga, S - 1) * rec + 2 + d_a];
-  // (3) r[m] over middle chunks: thread (m, group gr)
-  const int ngr = kFinBlock / M;   // M <= 512
-  const int m_r = tid % M, gr = tid / M;
-  int col_r;   // record column of basis function m_r
-  if (m_r == 0) {
-    col_r = 1;   // constant function: r_0 = sum of p over the middle rows = the chunk sums
-  } else {
-    const int n = (m_r + 1) / 2, cs = (m_r & 1) ? 0 : 1;   // odd m: cosine
-    col_r = 2 + D + 32 * ((n - 1) >> 4) + 16 * cs + ((n - 1) & 15);
+    for (int u = 0; u < kU; ++u)
+      mv[u] = *reinterpret_cast<const f32x4*>(pm + static_cast<size_t>(min(gm + u * ngm, Sm - 1)) * recm + 4 + 4 * c4m);
   }
-  float rv[kU];
+  // (3) columns of the full-row records
+  const int cw4 = D / 4;
+  const int ngw = kFinBlock / cw4;
+  const int c4w = tid % cw4, gw = tid / cw4;
+  constexpr int kUw = 2;
+  f32x4 wv[kUw];
+  if (Sw > 0) {
 #pragma unroll
-  for (int u = 0; u < kU; ++u) rv[u] = part[min(gr + u * ngr, max(p.Sm - 1, 0)) * rec + col_r];
+    for (int u = 0; u < kUw; ++u)
+      wv[u] = *reinterpret_cast<const f32x4*>(pw + static_cast<size_t>(min(gw + u * ngw, Sw - 1)) * recw + 4 + 4 * c4w);
+  }
   // (4) C_v rows: thread (4 columns c4, row group) takes rows rg, rg+nrg, ...
   const bool vec4 = (Dvc % 4) == 0 && Dvc > 0;
   const int ncol = vec4 ? Dvc / 4 : max(Dvc, 1);
@@ -1020,7 +1074,7 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
   const float* cv = p.cv + static_cast<size_t>(bh) * M * Dvc;
   constexpr int kCU = 16;
   f32x4 cvv[kCU];
-  const bool do_cv = p.Sm > 0 && Dvc > 0;
+  const bool do_cv = Sm > 0 && Dvc > 0;
   if (do_cv) {
 #pragma unroll
     for (int u = 0; u < kCU; ++u) {
@@ -1032,69 +1086,83 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
   uint64_t vbal[4];
   mask_ballots(p.vmask + static_cast<size_t>(bh) * D, D, lane, vbal);
 
-  // ---- global max and per-chunk factors ---------------------------------------------------
+  // ---- global max, per-record factors, normaliser ---------------------------------------------
   float m = (tid < S) ? ms_me : -INFINITY;
-  for (int s = tid + kFinBlock; s < S; s += kFinBlock) m = fmaxf(m, part[s * rec]);
   m = wave_max(m);
-  if (lane == 0) wred[wave] = m;
+  if (lane == 0) wmax[wave] = m;
   __syncthreads();
-  m = wred[0];
+  m = wmax[0];
 #pragma unroll
-  for (int w = 1; w < kNW; ++w) m = fmaxf(m, wred[w]);
+  for (int w = 1; w < kNW; ++w) m = fmaxf(m, wmax[w]);
   float l = 0.0f;
   if (tid < S) {
     const float e = (ms_me == -INFINITY) ? 0.0f : __expf(ms_me - m);
     es[tid] = e;
     l = e * ls_me;
   }
+  float lm = (tid < Sm) ? l : 0.0f;   // the middle rows' share: r of the constant basis function
   l = wave_sum(l);
-  __syncthreads();   // wred reads above are finished
-  if (lane == 0) wred[wave] = l;
+  lm = wave_sum(lm);
+  if (lane == 0) {
+    wsum[wave] = l;
+    wsum_m[wave] = lm;
+  }
   __syncthreads();
-  if (tid == 0) {
-    float t = 0.0f;
-    for (int w = 0; w < kNW; ++w) t += wred[w];
-    stat[0] = t;
+  float L = 0.0f, Lm = 0.0f;
+#pragma unroll
+  for (int w = 0; w < kNW; ++w) {
+    L += wsum[w];
+    Lm += wsum_m[w];
   }
 
-  // ---- acc[d] ---------------------------------------------------------------------------------
+  // ---- weighted sums over the records ---------------------------------------------------------
   {
-    float a = 0.0f;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    if (Sm > 0 && gm < ngm) {
 #pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      const int s = ga + u * nga;
-      if (s < S) a += es[s] * av[u];
+      for (int u = 0; u < kU; ++u) {
+        const int s = gm + u * ngm;
+        if (s < Sm) a += es[s] * mv[u];
+      }
+      for (int s = gm + kU * ngm; s < Sm; s += ngm)
+        a += es[s] * *reinterpret_cast<const f32x4*>(pm + static_cast<size_t>(s) * recm + 4 + 4 * c4m);
     }
-    for (int s = ga + kU * nga; s < S; s += nga) a += es[s] * part[s * rec + 2 + d_a];
-    red[tid] = (ga < nga) ? a : 0.0f;
-  }
-  __syncthreads();
-  if (tid < D) {
-    float a = 0.0f;
-    for (int g = 0; g < nga; ++g) a += red[g * D + tid];
-    accs[tid] = a;
-  }
-  __syncthreads();
-  // ---- r[m] -----------------------------------------------------------------------------------
-  {
-    float a = 0.0f;
+    redm[tid] = a;
+    f32x4 c = {0.f, 0.f, 0.f, 0.f};
+    if (Sw > 0 && gw < ngw) {
 #pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      const int s = gr + u * ngr;
-      if (s < p.Sm) a += es[s] * rv[u];
+      for (int u = 0; u < kUw; ++u) {
+        const int s = gw + u * ngw;
+        if (s < Sw) c += es[Sm + s] * wv[u];
+      }
+      for (int s = gw + kUw * ngw; s < Sw; s += ngw)
+        c += es[Sm + s] * *reinterpret_cast<const f32x4*>(pw + static_cast<size_t>(s) * recw + 4 + 4 * c4w);
     }
-    for (int s = gr + kU * ngr; s < p.Sm; s += ngr) a += es[s] * part[s * rec + col_r];
-    red[tid] = (gr < ngr) ? a : 0.0f;
+    redw[tid] = c;
   }
   __syncthreads();
-  if (tid < M) {
-    float a = 0.0f;
-    for (int g = 0; g < ngr; ++g) a += red[g * M + tid];
-    rr[tid] = a * basis_weight((tid + 1) / 2, p.T);
+  if (tid < cm4) {
+    f32x4 a = redm[tid];
+    for (int g = 1; g < ngm; ++g) a += redm[g * cm4 + tid];
+    *reinterpret_cast<f32x4*>(colm + 4 * tid) = a;
+  } else if (tid >= kFinBlock / 2 && tid < kFinBlock / 2 + cw4) {
+    const int t = tid - kFinBlock / 2;
+    f32x4 a = redw[t];
+    for (int g = 1; g < ngw; ++g) a += redw[g * cw4 + t];
+    *reinterpret_cast<f32x4*>(colw + 4 * t) = a;
+  }
+  __syncthreads();
+  // ---- r into basis order, weighted by the inverse squared norms -------------------------------
+  if (tid < p.Mint) {   // record order: 32 * chunk + 16 * (cos | sin) + order within the chunk
+    const int n = 16 * (tid >> 5) + (tid & 15) + 1, cs = (tid >> 4) & 1;
+    const int mm = 2 * n - 1 + cs;
+    if (mm < M) rr[mm] = colm[Dva + tid] * basis_weight(n, p.T);
+  } else if (tid == kFinBlock - 1) {
+    rr[0] = Lm * basis_weight(0, p.T);   // constant function: r_0 = sum of p over the middle rows
   }
   __syncthreads();
 
-  // ---- o[idx_vc[i]] += sum_m rr[m] C_v[m,i] ---------------------------------------------------
+  // ---- o[idx_vc[i]] = sum_m rr[m] C_v[m,i] ----------------------------------------------------
   if (do_cv) {
     f32x4 a = {0.f, 0.f, 0.f, 0.f};
     if (rg < nrg) {
@@ -1108,98 +1176,99 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
         else a[0] += rr[mm] * cv[static_cast<size_t>(mm) * Dvc + c4];
       }
     }
-    // reduce over row groups, one component at a time
-    const int ncomp = vec4 ? 4 : 1;
-    for (int comp = 0; comp < ncomp; ++comp) {
-      __syncthreads();
-      red[tid] = (rg < nrg) ? a[comp] : 0.0f;
-      __syncthreads();
-      if (tid < D) {
-        const int r = dim_rank(vbal, tid);
-        if (r < 0) {
-          const int ci = -r - 1;
-          const bool mine = vec4 ? ((ci & 3) == comp) : true;
-          if (mine) {
-            const int col = vec4 ? (ci >> 2) : ci;
-            float v = 0.0f;
-            for (int g = 0; g < nrg; ++g) v += red[g * ncol + col];
-            accs[tid] += v;
-          }
-        }
-      }
-    }
+    redm[tid] = a;   // every reader of the previous contents passed two barriers ago
   }
   __syncthreads();
-  if (tid < D) p.out[static_cast<size_t>(hq) * D + tid] = accs[tid] / stat[0];
+  if (tid < D) {
+    const int r = dim_rank(vbal, tid);
+    float v = colw[tid];
+    if (r >= 0) {
+      v += colm[r];
+    } else if (do_cv) {
+      const int ci = -r - 1;
+      const float* src = reinterpret_cast<const float*>(redm) + (vec4 ? 4 * (ci >> 2) + (ci & 3) : 4 * ci);
+      float a = 0.0f;
+      for (int g = 0; g < nrg; ++g) a += src[g * ncol * 4];
+      v += a;
+    }
+    p.out[static_cast<size_t>(hq) * D + tid] = v / L;
+  }
 }
 
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 struct DecodePlan {
-  int Gp, KT, Mint, nch, Sw, Sm, chunk_m, rec;
+  int Gp, KT, Mint, cw, Sw, Sm, chunk_m, recm, recw;
   unsigned lds_tab, lds_total;
-  size_t off_gs, off_g0, off_part, total;
+  size_t off_gs, off_g0, off_qk, off_pm, off_pw, total;
 };
 
 static int round_up(int x, int a) { return (x + a - 1) / a * a; }
 
-static int series_chunks(int M) {   // compiled series lengths: 64, 128, 256, 512
+static int series_chunks_per_wave(int M) {   // compiled series lengths: 128, 256, 512 slots
   const int slots = 2 * (M / 2);
-  const int need = slots > 0 ? (slots + 31) / 32 : 1;
-  for (int n : {2, 4, 8, 16})
-    if (need <= n) return n;
+  for (int cw : {1, 2, 4})
+    if (slots <= kWaves * cw * 32) return cw;
   return 0;
 }
 
-static int default_steps_per_chunk(int B, int Hkv, int N, int wg_step) {
-  const long total_steps = static_cast<long>(B) * Hkv * ((N + wg_step - 1) / wg_step);
-  long spc = (total_steps + 128) / 256;   // about one workgroup per compute unit
+// steps per chunk when the caller leaves the split to the library: all workgroups of the launch
+// (middle chunks and full-row chunks) should be resident at once, two per compute unit when two
+// fit (short series), else one
+static int default_steps_per_chunk(int B, int Hkv, int N, int step, int cw, int Sw) {
+  const long total_steps = static_cast<long>(B) * Hkv * ((N + step - 1) / step);
+  long target = (cw <= 2 ? 512 : 256) - static_cast<long>(B) * Hkv * Sw;
+  if (target < 64) target = 64;
+  long spc = (total_steps + target - 1) / target;
   if (spc < 1) spc = 1;
-  if (spc > 16) spc = 16;
+  if (spc > 32) spc = 32;
   return static_cast<int>(spc);
 }
 
-static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, int Dvc, int M,
+static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, int Dkc, int Dvc, int M,
                       int N, int W, int num_splits) {
   const int G = Hq / Hkv;
   pl.Gp = 1;
   while (pl.Gp < G) pl.Gp *= 2;
   pl.KT = 16 / pl.Gp < kMaxKT ? 16 / pl.Gp : kMaxKT;
-  pl.nch = series_chunks(M);
-  if (pl.nch == 0) return false;
-  pl.Mint = pl.nch * 32;
-  const int wg_step = kWaves * pl.KT * kTJ;
+  pl.cw = series_chunks_per_wave(M);
+  if (pl.cw == 0 || (dtype == FA_F32 && pl.cw > 2)) return false;
+  pl.Mint = kWaves * pl.cw * 32;
+  const int step = pl.KT * kTJ;
   pl.Sw = (W + kWChunk - 1) / kWChunk;
   if (N > 0) {
     int chunk;
-    if (num_splits > 0) chunk = round_up((N + num_splits - 1) / num_splits, wg_step);
-    else chunk = default_steps_per_chunk(B, Hkv, N, wg_step) * wg_step;
+    if (num_splits > 0) chunk = round_up((N + num_splits - 1) / num_splits, step);
+    else chunk = default_steps_per_chunk(B, Hkv, N, step, pl.cw, pl.Sw) * step;
     pl.chunk_m = chunk;
     pl.Sm = (N + chunk - 1) / chunk;
   } else {
-    pl.chunk_m = wg_step;
+    pl.chunk_m = step;
     pl.Sm = 0;
   }
   if (pl.Sw + pl.Sm > kMaxPartials) return false;
-  pl.rec = 2 + D + pl.Mint;
-  const unsigned es = (dtype == FA_F32) ? 4 : 2;   // bytes of a table entry
-  const unsigned ts = (dtype == FA_F32) ? 4 : 2;   // bytes of a K/V element
-  const unsigned tab = kTJ * (pl.Mint * es + 16) + pl.Mint * (kTJ * es + 16);
+  const unsigned ts = (dtype == FA_F32) ? 4 : 2;   // bytes of a q/K/V element
+  const int Dvu = D - Dvc, Dku = D - Dkc;
+  const unsigned DVT = (Dvu + 15) / 16;
+  const unsigned Dkq = (((Dku + 7) & ~7) + 31) / 32 * 32;
+  pl.recm = 4 + 16 * DVT + pl.Mint;
+  pl.recw = 4 + D;
+  const unsigned redb = (16 * (pl.Mint + 4) + kWaves * 16 * (16 * DVT + 4)) * 4;
+  const unsigned tab = redb > kXchgBytes ? redb : kXchgBytes;
   pl.lds_tab = (tab + 255u) & ~255u;
-  const unsigned mid = pl.lds_tab + pl.Gp * pl.Mint * 4 + pl.Gp * FA_MAX_HEAD_DIM * ts;
-  const unsigned DVT = (D - Dvc + 15) / 16;
-  const unsigned redb = kWaves * 16 * (pl.Mint + 16 * DVT) * 4;
+  const unsigned mid = pl.lds_tab + G * (pl.Mint + 32) * 4 + G * Dkq * ts;
   const unsigned wpath = 16 * FA_MAX_HEAD_DIM * ts + kWChunk * kMaxG * 4 + kBlock * 8 * 4 * 4;
-  unsigned t = mid > redb ? mid : redb;
-  if (wpath > t) t = wpath;
+  const unsigned t = mid > wpath ? mid : wpath;
   pl.lds_total = (t + 255u) & ~255u;
   if (pl.lds_total > kMaxDynLds) return false;
+  const size_t BHq = static_cast<size_t>(B) * Hq;
   pl.off_gs = 0;
-  pl.off_g0 = align_up(static_cast<size_t>(B) * Hq * pl.Mint * sizeof(float), 256);
-  pl.off_part = pl.off_g0 + align_up(static_cast<size_t>(B) * Hq * sizeof(float), 256);
-  pl.total = pl.off_part +
-             align_up(static_cast<size_t>(B) * Hq * (pl.Sw + pl.Sm) * pl.rec * sizeof(float), 256);
+  pl.off_g0 = align_up(BHq * pl.Mint * sizeof(float), 256);
+  pl.off_qk = pl.off_g0 + align_up(BHq * sizeof(float), 256);
+  pl.off_pm = pl.off_qk + align_up(BHq * Dkq * 4 + 16, 256);   // sized for fp32: the size query has no dtype
+  pl.off_pw = pl.off_pm + align_up(BHq * pl.Sm * pl.recm * sizeof(float) + 16, 256);
+  pl.total = pl.off_pw + align_up(BHq * pl.Sw * pl.recw * sizeof(float) + 16, 256);
 #ifdef FA_TRACE
   pl.total += static_cast<size_t>(B) * Hkv * (pl.Sw + pl.Sm) * 4 * 16 * sizeof(long long);
 #endif
@@ -1223,9 +1292,9 @@ static int check_decode_shapes(int dtype, int B, int Hq, int Hkv, int D, int Dkc
   return FA_OK;
 }
 
-template <typename T, int NCH, int DVTM>
+template <typename T, int CW, int DVTM>
 static int launch_partial(const DecodeParams& p, unsigned lds, hipStream_t st) {
-  auto kern = decode_partial<T, NCH, DVTM>;
+  auto kern = decode_partial<T, CW, DVTM>;
   // raising the dynamic-LDS ceiling is a property of the loaded kernel: do it once
   static unsigned granted = 48 * 1024;
   if (lds > granted) {
@@ -1252,16 +1321,15 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
   if (ev) (void)hipEventRecord(ev[1], st);
   int rc;
   const bool narrow = p.Dvu <= 32;   // kept V dims fit two MFMA column tiles
-#define FA_LAUNCH_PARTIAL(NCH_)                                                     \
-  rc = narrow ? launch_partial<T, NCH_, 2>(p, pl.lds_total, st)                     \
-              : launch_partial<T, NCH_, kMaxDvTiles>(p, pl.lds_total, st)
-  switch (pl.nch) {
+#define FA_LAUNCH_PARTIAL(CW_)                                                     \
+  rc = narrow ? launch_partial<T, CW_, 2>(p, pl.lds_total, st)                     \
+              : launch_partial<T, CW_, kMaxDvTiles>(p, pl.lds_total, st)
+  switch (pl.cw) {
+    case 1: FA_LAUNCH_PARTIAL(1); break;
     case 2: FA_LAUNCH_PARTIAL(2); break;
-    case 4: FA_LAUNCH_PARTIAL(4); break;
-    case 8: FA_LAUNCH_PARTIAL(8); break;
     default:
       if constexpr (sizeof(T) == 2) {
-        FA_LAUNCH_PARTIAL(16);
+        FA_LAUNCH_PARTIAL(4);
       } else {
         rc = FA_ERR_UNSUPPORTED;
       }
@@ -1279,10 +1347,12 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
 
 extern "C" {
 
-int fa_decode_default_splits(int B, int Hq, int Hkv, int N) {
-  if (B <= 0 || Hq <= 0 || Hkv <= 0 || N <= 0 || Hq % Hkv != 0 || Hq / Hkv > FA_MAX_GROUP) return 0;
+int fa_decode_default_splits(int B, int Hq, int Hkv, int M, int N, int W) {
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || N <= 0 || W < 0 || M < 1 || Hq % Hkv != 0 ||
+      Hq / Hkv > FA_MAX_GROUP)
+    return 0;
   fa::DecodePlan pl{};
-  if (!fa::make_plan(pl, FA_BF16, B, Hq, Hkv, 128, 0, 2, N, 0, 0)) return 0;
+  if (!fa::make_plan(pl, FA_BF16, B, Hq, Hkv, 128, 0, 0, M, N, W, 0)) return 0;
   return pl.Sm;
 }
 
@@ -1292,7 +1362,7 @@ size_t fa_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int Dkc, int Dvc
                               num_splits) != FA_OK)
     return 0;
   fa::DecodePlan pl{};
-  if (!fa::make_plan(pl, FA_BF16, B, Hq, Hkv, D, Dvc, M, N, W, num_splits)) return 0;
+  if (!fa::make_plan(pl, FA_BF16, B, Hq, Hkv, D, Dkc, Dvc, M, N, W, num_splits)) return 0;
   return pl.total;
 }
 
@@ -1332,7 +1402,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
     return FA_ERR_UNSUPPORTED;
 
   DecodePlan pl{};
-  if (!make_plan(pl, dtype, B, Hq, Hkv, D, Dvc, M, N, W, num_splits)) return FA_ERR_UNSUPPORTED;
+  if (!make_plan(pl, dtype, B, Hq, Hkv, D, Dkc, Dvc, M, N, W, num_splits)) return FA_ERR_UNSUPPORTED;
   if (workspace_bytes < pl.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
     return FA_ERR_WORKSPACE;
 
@@ -1344,18 +1414,20 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   p.Dkc = Dkc; p.Dvc = Dvc; p.Dku = Dku; p.Dvu = Dvu;
   p.M = M; p.T = T; p.t0 = t0; p.N = N; p.W = W;
   p.Gp = pl.Gp; p.KT = pl.KT; p.Mint = pl.Mint;
-  p.Sw = pl.Sw; p.Sm = pl.Sm; p.chunk_m = pl.chunk_m; p.rec = pl.rec;
+  p.Sw = pl.Sw; p.Sm = pl.Sm; p.chunk_m = pl.chunk_m; p.recm = pl.recm; p.recw = pl.recw;
   p.lds_tab = pl.lds_tab;
   p.scale = scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(D));
   p.ph_scale = 4294967296.0 / static_cast<double>(T);
   char* ws = static_cast<char*>(workspace);
   p.gs = reinterpret_cast<float*>(ws + pl.off_gs);
   p.g0 = reinterpret_cast<float*>(ws + pl.off_g0);
-  p.part = reinterpret_cast<float*>(ws + pl.off_part);
+  p.qkeep = ws + pl.off_qk;
+  p.part_m = reinterpret_cast<float*>(ws + pl.off_pm);
+  p.part_w = reinterpret_cast<float*>(ws + pl.off_pw);
   p.out = out;
 #ifdef FA_TRACE
   p.trace = reinterpret_cast<long long*>(
-      ws + pl.off_part + align_up(static_cast<size_t>(B) * Hq * (pl.Sw + pl.Sm) * pl.rec * sizeof(float), 256));
+      ws + pl.off_pw + align_up(static_cast<size_t>(B) * Hq * pl.Sw * pl.recw * sizeof(float) + 16, 256));
 #endif
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   return dtype == FA_F32 ? launch_decode<float>(p, pl, stream, ev)

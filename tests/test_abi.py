@@ -86,4 +86,4 @@ def test_workspace_queries():
     assert fa.decode_workspace_bytes(1, 32, 8, 128, 96, 96, 256, 31740, 1028, 0) > 0
     assert fa.decode_workspace_bytes(1, 7, 2, 128, 96, 96, 256, 100, 10, 0) == 0
     assert fa.compress_workspace_bytes(8, 32, 4096, 128, 96, 256) >= 256
-    assert fa.decode_default_splits(1, 32, 8, 31740) >= 1
+    assert fa.decode_default_splits(1, 32, 8, 256, 31740, 1028) >= 1
