@@ -46,9 +46,9 @@ constexpr int kXN = kTJ / 32;      // 32-token contraction steps per tile on the
 constexpr int kMaxKT = 4;          // tiles per wave step
 constexpr int kWChunk = 64;        // full-width rows per workgroup
 constexpr int kMaxDvTiles = 8;     // kept V dims handled per middle row: 8 * 16
-constexpr int kMaxPartials = 1024; // partial records per query head (= threads of decode_finish)
+constexpr int kMaxPartials = 1024; // partial records per query head
 constexpr unsigned kMaxDynLds = 160 * 1024 - 4096;   // dynamic LDS a workgroup may ask for
-constexpr int kFinBlock = 1024;    // threads of decode_finish
+constexpr int kFinBlock = 256;     // threads of decode_finish
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
@@ -63,8 +63,16 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
       p.trace[((static_cast<size_t>(blockIdx.y) * gridDim.x + blockIdx.x) * 4 +              \
                (threadIdx.x >> 6)) * 16 + (i)] = clock64();                                  \
   } while (0)
+// stamps of decode_finish live behind those of decode_partial
+#define FA_FSTAMP(i)                                                                         \
+  do {                                                                                       \
+    if ((threadIdx.x & 63) == 0)                                                             \
+      p.trace[(static_cast<size_t>(p.B) * p.Hkv * (p.Sw + p.Sm) * 4 +                        \
+               (static_cast<size_t>(blockIdx.y) * gridDim.x + blockIdx.x) * 4 + (threadIdx.x >> 6)) * 16 + (i)] = clock64(); \
+  } while (0)
 #else
 #define FA_STAMP(i) do {} while (0)
+#define FA_FSTAMP(i) do {} while (0)
 #endif
 
 struct DecodeParams {
@@ -203,6 +211,21 @@ __device__ __forceinline__ float row_stride_max(float v, int stride) {
   if (stride <= 2) v = fmaxf(v, row_ror<2>(v));
   if (stride <= 1) v = fmaxf(v, row_ror<1>(v));
   return v;
+}
+
+// value of lane `src` (compile-time) broadcast to the wave
+template <int SRC>
+__device__ __forceinline__ float lane_value(float v) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), SRC));
+}
+// wave-wide sum / max, result in every lane: rotations inside the rows, then the four row totals
+__device__ __forceinline__ float wave_sum_fast(float v) {
+  v = row_stride_sum(v, 1);
+  return (lane_value<0>(v) + lane_value<16>(v)) + (lane_value<32>(v) + lane_value<48>(v));
+}
+__device__ __forceinline__ float wave_max_fast(float v) {
+  v = row_stride_max(v, 1);
+  return fmaxf(fmaxf(lane_value<0>(v), lane_value<16>(v)), fmaxf(lane_value<32>(v), lane_value<48>(v)));
 }
 
 // every wave reads the whole mask row (D <= 256) and keeps it as 4 ballot words
@@ -1017,92 +1040,130 @@ __global__ __launch_bounds__(kBlock, (CW <= 2 && sizeof(T) == 2) ? 2 : 1) void d
 }
 
 // ---------------------------------------------------------------------------
-// 3. merge partials, apply diag(w) C_v, normalise: one workgroup per query head
+// 3. merge partials, apply diag(w) C_v, normalise
 // ---------------------------------------------------------------------------
+// A query head is shared by ceil(D / 32) workgroups, one per slice of 32 output
+// dims.  Every slice merges the statistics and the series sums r of the head's
+// records (replicated work, a few tens of KB), then finishes its own dims: kept
+// dims from the accumulators, compressed dims from r and its columns of C_v.
+// Nothing is exchanged between workgroups.
+constexpr int kFinDims = 32;   // output dims per workgroup
+
 template <typename T>
 __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
   constexpr int kNW = kFinBlock / 64;
-  __shared__ float es[kMaxPartials];                                 // e^{m_s - m} per record
-  __shared__ f32x4 redm[kFinBlock], redw[kFinBlock];                 // per-thread partial sums
-  __shared__ float colm[16 * kMaxDvTiles + FA_MAX_DECODE_STATES];    // middle records merged: acc (kept order), r
-  __shared__ float colw[FA_MAX_HEAD_DIM];                            // full-row records merged
-  __shared__ float rr[FA_MAX_DECODE_STATES];                         // r in basis order, weighted
+  constexpr int kSP = kMaxPartials / kFinBlock;   // records per thread when reading statistics
+  constexpr int kCG = kFinBlock / kFinDims;       // row / record groups of the per-dim passes
+  __shared__ float es[kMaxPartials];              // e^{m_s - m} per record
+  __shared__ f32x4 red4[kFinBlock];
+  __shared__ float rr[FA_MAX_DECODE_STATES];      // r in basis order, weighted
+  __shared__ f32x4 redw4[kFinBlock];
+  __shared__ float redc[kFinBlock];
+  __shared__ float outw[kFinDims];
   __shared__ float wmax[kNW], wsum[kNW], wsum_m[kNW];
 
-  const int hq = blockIdx.x, b = hq / p.Hq, hkv = (hq % p.Hq) / p.G;
-  const int bh = b * p.Hkv + hkv;
+  const int sl = blockIdx.x, hq = blockIdx.y;
+  const int b = hq / p.Hq, hkv = (hq % p.Hq) / p.G, bh = b * p.Hkv + hkv;
   const int D = p.D, M = p.M, Sm = p.Sm, Sw = p.Sw, S = Sm + Sw, Dvc = p.Dvc;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int Dva = 16 * ((p.Dvu + 15) / 16);
   const int recm = p.recm, recw = p.recw;
   const float* pm = p.part_m + static_cast<size_t>(hq) * Sm * recm;
   const float* pw = p.part_w + static_cast<size_t>(hq) * Sw * recw;
+  const bool do_cv = Sm > 0 && Dvc > 0;
+  const int d0 = kFinDims * sl;
 
-  // ---- every global operand is requested before anything is consumed -------------------
-  // (1) chunk maxima and sums (S <= kMaxPartials = kFinBlock: one record per thread)
-  const int s_me = min(tid, S - 1);
-  const float* r_me = (s_me < Sm) ? pm + static_cast<size_t>(s_me) * recm
-                                  : pw + static_cast<size_t>(s_me - Sm) * recw;
-  const float ms_me = r_me[0], ls_me = r_me[1];
-  // (2) columns of the middle records: thread (4 columns c4m, group gm) takes records gm, gm + ngm, ...
-  const int cm4 = (Dva + p.Mint) / 4;
-  const int ngm = kFinBlock / cm4;
-  const int c4m = tid % cm4, gm = tid / cm4;
-  constexpr int kU = 5;
-  f32x4 mv[kU];
-  if (Sm > 0) {
+  FA_FSTAMP(0);
+  // ---- global operands, in the order they are needed -----------------------------------------
+  // (0) the mask row: it decides which columns of C_v and of the accumulators this slice reads
+  uint8_t vmb[4];
 #pragma unroll
-    for (int u = 0; u < kU; ++u)
-      mv[u] = *reinterpret_cast<const f32x4*>(pm + static_cast<size_t>(min(gm + u * ngm, Sm - 1)) * recm + 4 + 4 * c4m);
+  for (int i = 0; i < 4; ++i) vmb[i] = p.vmask[static_cast<size_t>(bh) * D + min(lane + 64 * i, D - 1)];
+  // (1) chunk maxima and sums
+  float ms[kSP], ls[kSP];
+#pragma unroll
+  for (int i = 0; i < kSP; ++i) {
+    const int s = min(tid + i * kFinBlock, S - 1);
+    const float* r = (s < Sm) ? pm + static_cast<size_t>(s) * recm : pw + static_cast<size_t>(s - Sm) * recw;
+    ms[i] = r[0];
+    ls[i] = r[1];
   }
-  // (3) columns of the full-row records
-  const int cw4 = D / 4;
-  const int ngw = kFinBlock / cw4;
-  const int c4w = tid % cw4, gw = tid / cw4;
+  FA_FSTAMP(10);
+  // (2) series sums of the middle records: thread (4 columns, group of records)
+  const int cr4 = p.Mint / 4, ngr = kFinBlock / cr4;
+  const int c4r = tid % cr4, gr = tid / cr4;
+  const float* pr = pm + 4 + Dva + 4 * c4r;
+  constexpr int kUr = 12;
+  f32x4 rv[kUr];
+  if (do_cv) {
+#pragma unroll
+    for (int u = 0; u < kUr; ++u)   // clamped, not predicated: a predicated load is waited for at once
+      rv[u] = *reinterpret_cast<const f32x4*>(pr + static_cast<size_t>(min(gr + u * ngr, Sm - 1)) * recm);
+  }
+  FA_FSTAMP(11);
+  // (3) this slice's columns of the full-row records: thread (4 columns, group of records)
+  constexpr int kW4 = kFinDims / 4, kWG = kFinBlock / kW4;
+  const int c4w = tid % kW4, gw = tid / kW4;
+  const bool w_ok = d0 + 4 * c4w < D;
+  const int dw = min(d0 + 4 * c4w, D - 4);
   constexpr int kUw = 2;
   f32x4 wv[kUw];
   if (Sw > 0) {
 #pragma unroll
     for (int u = 0; u < kUw; ++u)
-      wv[u] = *reinterpret_cast<const f32x4*>(pw + static_cast<size_t>(min(gw + u * ngw, Sw - 1)) * recw + 4 + 4 * c4w);
+      wv[u] = *reinterpret_cast<const f32x4*>(pw + static_cast<size_t>(min(gw + u * kWG, Sw - 1)) * recw + 4 + dw);
   }
-  // (4) C_v rows: thread (4 columns c4, row group) takes rows rg, rg+nrg, ...
-  const bool vec4 = (Dvc % 4) == 0 && Dvc > 0;
-  const int ncol = vec4 ? Dvc / 4 : max(Dvc, 1);
-  const int nrg = kFinBlock / ncol;
-  const int c4 = tid % ncol, rg = tid / ncol;
-  const float* cv = p.cv + static_cast<size_t>(bh) * M * Dvc;
-  constexpr int kCU = 16;
-  f32x4 cvv[kCU];
-  const bool do_cv = Sm > 0 && Dvc > 0;
+  FA_FSTAMP(12);
+  // ranks of this slice's dims (needs only the mask)
+  uint64_t vbal[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) vbal[i] = __ballot(vmb[i] != 0 && lane + 64 * i < D);
+  const int col = tid % kFinDims, cg = tid / kFinDims;
+  const int dme = d0 + col;
+  const int rk = (dme < D) ? dim_rank(vbal, dme) : 0;
+  const bool is_c = dme < D && rk < 0, is_k = dme < D && rk >= 0;
+  FA_FSTAMP(13);
+  // (4) compressed dim: its column of C_v, rows cg, cg + kCG, ...; kept dim: its accumulator column
+  constexpr int kUc = 32, kUk = 6;
+  const float* cvc = p.cv + static_cast<size_t>(bh) * M * Dvc + (is_c ? -rk - 1 : 0);
+  float cvv[kUc];
   if (do_cv) {
 #pragma unroll
-    for (int u = 0; u < kCU; ++u) {
-      const int mm = min(rg + u * nrg, M - 1);
-      if (vec4) cvv[u] = *reinterpret_cast<const f32x4*>(cv + static_cast<size_t>(mm) * Dvc + 4 * c4);
-      else cvv[u] = f32x4{cv[static_cast<size_t>(mm) * Dvc + c4], 0.f, 0.f, 0.f};
-    }
+    for (int u = 0; u < kUc; ++u) cvv[u] = cvc[static_cast<size_t>(min(cg + u * kCG, M - 1)) * Dvc];
   }
-  uint64_t vbal[4];
-  mask_ballots(p.vmask + static_cast<size_t>(bh) * D, D, lane, vbal);
+  FA_FSTAMP(14);
+  const float* pk = pm + 4 + (is_k ? rk : 0);
+  float kv[kUk];
+  if (Sm > 0) {
+#pragma unroll
+    for (int u = 0; u < kUk; ++u) kv[u] = pk[static_cast<size_t>(min(cg + u * kCG, Sm - 1)) * recm];
+  }
 
+  FA_FSTAMP(1);
   // ---- global max, per-record factors, normaliser ---------------------------------------------
-  float m = (tid < S) ? ms_me : -INFINITY;
-  m = wave_max(m);
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < kSP; ++i)
+    if (tid + i * kFinBlock < S) m = fmaxf(m, ms[i]);
+  m = wave_max_fast(m);
   if (lane == 0) wmax[wave] = m;
   __syncthreads();
   m = wmax[0];
 #pragma unroll
   for (int w = 1; w < kNW; ++w) m = fmaxf(m, wmax[w]);
-  float l = 0.0f;
-  if (tid < S) {
-    const float e = (ms_me == -INFINITY) ? 0.0f : __expf(ms_me - m);
-    es[tid] = e;
-    l = e * ls_me;
+  float l = 0.0f, lm = 0.0f;
+#pragma unroll
+  for (int i = 0; i < kSP; ++i) {
+    const int s = tid + i * kFinBlock;
+    if (s < S) {
+      const float e = (ms[i] == -INFINITY) ? 0.0f : __expf(ms[i] - m);
+      es[s] = e;
+      l += e * ls[i];
+      if (s < Sm) lm += e * ls[i];   // the middle rows' share: r of the constant basis function
+    }
   }
-  float lm = (tid < Sm) ? l : 0.0f;   // the middle rows' share: r of the constant basis function
-  l = wave_sum(l);
-  lm = wave_sum(lm);
+  l = wave_sum_fast(l);
+  lm = wave_sum_fast(lm);
   if (lane == 0) {
     wsum[wave] = l;
     wsum_m[wave] = lm;
@@ -1114,85 +1175,86 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
     L += wsum[w];
     Lm += wsum_m[w];
   }
+  FA_FSTAMP(2);
 
-  // ---- weighted sums over the records ---------------------------------------------------------
-  {
-    f32x4 a = {0.f, 0.f, 0.f, 0.f};
-    if (Sm > 0 && gm < ngm) {
-#pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        const int s = gm + u * ngm;
-        if (s < Sm) a += es[s] * mv[u];
-      }
-      for (int s = gm + kU * ngm; s < Sm; s += ngm)
-        a += es[s] * *reinterpret_cast<const f32x4*>(pm + static_cast<size_t>(s) * recm + 4 + 4 * c4m);
-    }
-    redm[tid] = a;
-    f32x4 c = {0.f, 0.f, 0.f, 0.f};
-    if (Sw > 0 && gw < ngw) {
-#pragma unroll
-      for (int u = 0; u < kUw; ++u) {
-        const int s = gw + u * ngw;
-        if (s < Sw) c += es[Sm + s] * wv[u];
-      }
-      for (int s = gw + kUw * ngw; s < Sw; s += ngw)
-        c += es[Sm + s] * *reinterpret_cast<const f32x4*>(pw + static_cast<size_t>(s) * recw + 4 + 4 * c4w);
-    }
-    redw[tid] = c;
-  }
-  __syncthreads();
-  if (tid < cm4) {
-    f32x4 a = redm[tid];
-    for (int g = 1; g < ngm; ++g) a += redm[g * cm4 + tid];
-    *reinterpret_cast<f32x4*>(colm + 4 * tid) = a;
-  } else if (tid >= kFinBlock / 2 && tid < kFinBlock / 2 + cw4) {
-    const int t = tid - kFinBlock / 2;
-    f32x4 a = redw[t];
-    for (int g = 1; g < ngw; ++g) a += redw[g * cw4 + t];
-    *reinterpret_cast<f32x4*>(colw + 4 * t) = a;
-  }
-  __syncthreads();
-  // ---- r into basis order, weighted by the inverse squared norms -------------------------------
-  if (tid < p.Mint) {   // record order: 32 * chunk + 16 * (cos | sin) + order within the chunk
-    const int n = 16 * (tid >> 5) + (tid & 15) + 1, cs = (tid >> 4) & 1;
-    const int mm = 2 * n - 1 + cs;
-    if (mm < M) rr[mm] = colm[Dva + tid] * basis_weight(n, p.T);
-  } else if (tid == kFinBlock - 1) {
-    rr[0] = Lm * basis_weight(0, p.T);   // constant function: r_0 = sum of p over the middle rows
-  }
-  __syncthreads();
-
-  // ---- o[idx_vc[i]] = sum_m rr[m] C_v[m,i] ----------------------------------------------------
+  // ---- r in basis order, weighted by the inverse squared norms ---------------------------------
   if (do_cv) {
     f32x4 a = {0.f, 0.f, 0.f, 0.f};
-    if (rg < nrg) {
+    if (gr < ngr) {
 #pragma unroll
-      for (int u = 0; u < kCU; ++u) {
-        const int mm = rg + u * nrg;
-        if (mm < M) a += rr[mm] * cvv[u];
+      for (int u = 0; u < kUr; ++u) {
+        const int s = gr + u * ngr;
+        if (s < Sm) a += es[s] * rv[u];
       }
-      for (int mm = rg + kCU * nrg; mm < M; mm += nrg) {
-        if (vec4) a += rr[mm] * *reinterpret_cast<const f32x4*>(cv + static_cast<size_t>(mm) * Dvc + 4 * c4);
-        else a[0] += rr[mm] * cv[static_cast<size_t>(mm) * Dvc + c4];
-      }
+      for (int s = gr + kUr * ngr; s < Sm; s += ngr)
+        a += es[s] * *reinterpret_cast<const f32x4*>(pr + static_cast<size_t>(s) * recm);
     }
-    redm[tid] = a;   // every reader of the previous contents passed two barriers ago
+    red4[tid] = a;
+  }
+  // this slice's full-row columns
+  {
+    f32x4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < kUw; ++u) {
+      const int s = gw + u * kWG;
+      if (s < Sw && w_ok) c += es[Sm + s] * wv[u];
+    }
+    if (w_ok)
+      for (int s = gw + kUw * kWG; s < Sw; s += kWG)
+        c += es[Sm + s] * *reinterpret_cast<const f32x4*>(pw + static_cast<size_t>(s) * recw + 4 + dw);
+    redw4[tid] = c;   // [record group][column quad]
   }
   __syncthreads();
-  if (tid < D) {
-    const int r = dim_rank(vbal, tid);
-    float v = colw[tid];
-    if (r >= 0) {
-      v += colm[r];
-    } else if (do_cv) {
-      const int ci = -r - 1;
-      const float* src = reinterpret_cast<const float*>(redm) + (vec4 ? 4 * (ci >> 2) + (ci & 3) : 4 * ci);
-      float a = 0.0f;
-      for (int g = 0; g < nrg; ++g) a += src[g * ncol * 4];
-      v += a;
-    }
-    p.out[static_cast<size_t>(hq) * D + tid] = v / L;
+  if (tid < kFinDims) {
+    const float* src = reinterpret_cast<const float*>(redw4) + tid;
+    float v = 0.0f;
+#pragma unroll
+    for (int g = 0; g < kWG; ++g) v += src[g * kFinDims];
+    outw[tid] = v;
   }
+  if (do_cv) {
+    for (int ig = tid; ig < p.Mint; ig += kFinBlock) {   // record order: 32 * chunk + 16 * (cos | sin) + order
+      const float* src = reinterpret_cast<const float*>(red4) + ig;
+      float v = 0.0f;
+      for (int g = 0; g < ngr; ++g) v += src[g * p.Mint];
+      const int n = 16 * (ig >> 5) + (ig & 15) + 1, cs = (ig >> 4) & 1;
+      const int mm = 2 * n - 1 + cs;
+      if (mm < M) rr[mm] = v * basis_weight(n, p.T);
+    }
+    if (tid == kFinBlock - 1) rr[0] = Lm * basis_weight(0, p.T);   // constant function: sum of p over the middle rows
+  }
+  __syncthreads();
+  FA_FSTAMP(3);
+
+  // ---- per dim: sum_m rr[m] C_v[m, i] (compressed) or the merged accumulator (kept) ------------
+  {
+    float o = 0.0f;
+    if (do_cv && is_c) {
+#pragma unroll
+      for (int u = 0; u < kUc; ++u) {
+        const int mm = cg + u * kCG;
+        if (mm < M) o += rr[mm] * cvv[u];
+      }
+      for (int mm = cg + kUc * kCG; mm < M; mm += kCG) o += rr[mm] * cvc[static_cast<size_t>(mm) * Dvc];
+    }
+    if (is_k && Sm > 0) {
+#pragma unroll
+      for (int u = 0; u < kUk; ++u) {
+        const int s = cg + u * kCG;
+        if (s < Sm) o += es[s] * kv[u];
+      }
+      for (int s = cg + kUk * kCG; s < Sm; s += kCG) o += es[s] * pk[static_cast<size_t>(s) * recm];
+    }
+    redc[tid] = o;
+  }
+  __syncthreads();
+  if (tid < kFinDims && d0 + tid < D) {
+    float v = outw[tid];
+#pragma unroll
+    for (int g = 0; g < kCG; ++g) v += redc[g * kFinDims + tid];
+    p.out[static_cast<size_t>(hq) * D + d0 + tid] = v / L;
+  }
+  FA_FSTAMP(4);
 }
 
 // ---------------------------------------------------------------------------
@@ -1201,7 +1263,7 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
 struct DecodePlan {
   int Gp, KT, Mint, cw, Sw, Sm, chunk_m, recm, recw;
   unsigned lds_tab, lds_total;
-  size_t off_gs, off_g0, off_qk, off_pm, off_pw, total;
+  size_t off_gs, off_g0, off_qk, off_pm, off_pw, off_trace, total;
 };
 
 static int round_up(int x, int a) { return (x + a - 1) / a * a; }
@@ -1268,9 +1330,10 @@ static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, 
   pl.off_qk = pl.off_g0 + align_up(BHq * sizeof(float), 256);
   pl.off_pm = pl.off_qk + align_up(BHq * Dkq * 4 + 16, 256);   // sized for fp32: the size query has no dtype
   pl.off_pw = pl.off_pm + align_up(BHq * pl.Sm * pl.recm * sizeof(float) + 16, 256);
-  pl.total = pl.off_pw + align_up(BHq * pl.Sw * pl.recw * sizeof(float) + 16, 256);
+  pl.off_trace = pl.off_pw + align_up(BHq * pl.Sw * pl.recw * sizeof(float) + 16, 256);
+  pl.total = pl.off_trace;
 #ifdef FA_TRACE
-  pl.total += static_cast<size_t>(B) * Hkv * (pl.Sw + pl.Sm) * 4 * 16 * sizeof(long long);
+  pl.total += (static_cast<size_t>(B) * Hkv * (pl.Sw + pl.Sm) * 4 + BHq * 16) * 16 * sizeof(long long);
 #endif
   return true;
 }
@@ -1338,7 +1401,7 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
 #undef FA_LAUNCH_PARTIAL
   if (rc != FA_OK) return rc;
   if (ev) (void)hipEventRecord(ev[2], st);
-  hipLaunchKernelGGL(decode_finish<T>, dim3(p.B * p.Hq), dim3(kFinBlock), 0, st, p);
+  hipLaunchKernelGGL(decode_finish<T>, dim3((p.D + kFinDims - 1) / kFinDims, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
   if (ev) (void)hipEventRecord(ev[3], st);
   return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
 }
@@ -1426,8 +1489,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   p.part_w = reinterpret_cast<float*>(ws + pl.off_pw);
   p.out = out;
 #ifdef FA_TRACE
-  p.trace = reinterpret_cast<long long*>(
-      ws + pl.off_pw + align_up(static_cast<size_t>(B) * Hq * pl.Sw * pl.recw * sizeof(float) + 16, 256));
+  p.trace = reinterpret_cast<long long*>(ws + pl.off_trace);
 #endif
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   return dtype == FA_F32 ? launch_decode<float>(p, pl, stream, ev)
