@@ -46,6 +46,10 @@ constexpr unsigned kMaxCLds = 160 * 1024 - 8192;
 #define FA_CSTAMP(i) do {} while (0)
 #endif
 
+typedef float f32x2c __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2c __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2c __attribute__((ext_vector_type(2)));
+
 struct CompressParams {
   const void* x;
   int64_t sx_b, sx_h, sx_n;
@@ -437,6 +441,335 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
   FA_CSTAMP(31);
 }
 
+// ---------------------------------------------------------------------------
+// bf16, head dim 128: blocks of 128 tokens
+// ---------------------------------------------------------------------------
+// Same decomposition as compress_project, specialised for the common shape.  A thread
+// loads 8 dims of 4 consecutive tokens, so that every dim leaves as ONE 64-bit LDS
+// write into the transposed tiles (compressed dims: MFMA B operands; kept dims: a
+// staging tile in the same [dim][token] layout that serves both output layouts).  The
+// frame moves once per 128 tokens, the constant function rides on the matrix cores as
+// a row of ones, and all addressing is decided before the loop.
+constexpr int kFB = 128;            // tokens per block
+constexpr int kFP = kFB + 8;        // LDS pitch (elements) of a transposed column
+constexpr int kFK = kFB / 32;       // 32-token contraction steps per block
+
+__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) {   // (a.lo, b.lo)
+  return __builtin_amdgcn_perm(b, a, 0x05040100u);
+}
+__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) {   // (a.hi, b.hi)
+  return __builtin_amdgcn_perm(b, a, 0x07060302u);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams p) {
+  using T = bf16_t;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int16_t cpos[FA_MAX_HEAD_DIM];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q4 = lane >> 4, r16 = lane & 15;
+  const int s = blockIdx.x, mc = blockIdx.y;
+  const int bh = blockIdx.z, b = bh / p.H, h = bh % p.H;
+  constexpr int D = 128;
+  const int M = p.M, Du = p.Du, kp = p.keep_pitch;
+  const int j0 = s * p.chunk, jend = min(p.N, j0 + p.chunk);
+  const int nb = (jend - j0 + kFB - 1) / kFB;
+  const bool write_keep = (blockIdx.y == 0) && p.keep != nullptr && Du > 0;
+  const bool project = p.Dc > 0;
+  const bool do_dc = project && mc == 0;
+  const bool rows_layout = p.keep_layout == FA_KEEP_ROWS;
+
+  // two buffers of [compressed columns kCols x kFP | kept dims kp x kFP | 8 spare elements]
+  const uint32_t bufb = (kCols * kFP + static_cast<uint32_t>(kp) * kFP + 8) * 2;   // bytes per buffer
+  const uint32_t ks_off = kCols * kFP * 2;
+
+  // ---- first X block is requested before anything else --------------------------------
+  const int ch = tid & 15, quad = tid >> 4;        // 8 dims, 4 consecutive tokens
+  const T* xthr = static_cast<const T*>(p.x) + b * p.sx_b + h * p.sx_h + ch * 8;
+  Frag<T> xra[4], xrb[4];   // even / odd blocks: two blocks are in flight
+  // Loads are never predicated: a load under a condition is merged with the old register contents
+  // right after it, i.e. waited for at once.  Blocks past the chunk re-read its last block and rows
+  // past the segment its last row; both are ignored downstream.
+  auto load_x = [&](Frag<T> (&xr)[4], int blk) {
+    const int js = j0 + min(blk, nb - 1) * kFB + 4 * quad;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xr[i].load(xthr + static_cast<int64_t>(min(js + i, p.N - 1)) * p.sx_n);
+  };
+  FA_CSTAMP(0);
+  // the mask row first (it is waited for first), then the first two X blocks
+  uint8_t mb[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) mb[j] = p.mask[static_cast<size_t>(bh) * D + lane + 64 * j];
+  load_x(xra, 0);
+  load_x(xrb, 1);
+
+  // ---- per-wave constants: E fragments (A operand) and frame twiddles -------------------
+  const int rows_here = 2 * min(kPairs, p.nmax - mc * kPairs);   // live basis rows of this row block
+  const int rgw = wave & 3, chw = wave >> 2;       // row group (64 basis rows), column half of this wave
+  const int ndt = (p.Dc + 15) / 16 - chw * DT;     // live column tiles of this wave (may be <= 0)
+  const bool wave_live = project && rgw * 64 < rows_here && ndt > 0;
+  const bool wave_dc = do_dc && rgw < ndt && rgw < DT;   // this wave sums column tile rgw of its half
+
+  Frag<T> ea[4][kFK];            // [m tile][32-token step]
+  float twc[4][2], tws[4][2];    // cos/sin(omega_n * 128) of the two pairs a lane owns in every m tile
+  const uint32_t ph_blk = fixed_phase(kFB, p.ph_scale);
+  if (wave_live) {
+    // phase of token u as a 2^-32-turn fixed-point number; times n it wraps exactly, and the
+    // rounding of the unit (< 2^-32 turn) grows to at most n * 2^-32 turn: far below a bf16 ulp
+    const uint32_t ph_1 = fixed_phase(1, p.ph_scale);
+    uint32_t ph_u[kFK];
+#pragma unroll
+    for (int ksx = 0; ksx < kFK; ++ksx) ph_u[ksx] = fixed_phase(32 * ksx + 8 * q4, p.ph_scale);
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+      const int rho = rgw * 64 + mt * 16 + r16;               // A-operand row of this lane
+      const int n = mc * kPairs + (rho >> 1) + 1;
+      const bool live = n <= p.nmax;
+      // one exact evaluation per 32-token step; the 8 tokens of a lane follow by angle addition
+      float c1, s1;
+      fixed_phase_cs<T>(static_cast<uint32_t>(n) * ph_1, &c1, &s1);
+#pragma unroll
+      for (int ksx = 0; ksx < kFK; ++ksx) {
+        float c, sn;
+        fixed_phase_cs<T>(static_cast<uint32_t>(n) * ph_u[ksx], &c, &sn);
+        float vals[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          vals[e] = live ? ((rho & 1) ? sn : c) : 0.0f;
+          const float cn = c * c1 - sn * s1;
+          sn = sn * c1 + c * s1;
+          c = cn;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          ea[mt][ksx].v[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2c{vals[2 * e], vals[2 * e + 1]}, bf16x2c));
+      }
+#pragma unroll
+      for (int pr = 0; pr < 2; ++pr) {
+        const int n2 = mc * kPairs + ((rgw * 64 + mt * 16 + 4 * q4) >> 1) + pr + 1;   // accumulator rows 4*q4 + 2*pr
+        fixed_phase_cs<T>(static_cast<uint32_t>(n2) * ph_blk, &twc[mt][pr], &tws[mt][pr]);
+      }
+    }
+  }
+  // ---- dimension ranks: >= 0 index among kept dims, < 0: -(1 + index among compressed) ------
+  {
+    uint64_t bal[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) bal[j] = __ballot(mb[j] != 0);
+    if (tid < D) {
+      const int w = tid >> 6;
+      const uint64_t bit = 1ull << (tid & 63);
+      const int nc = __popcll(bal[0] & (w ? ~0ull : bit - 1ull)) + (w ? __popcll(bal[1] & (bit - 1ull)) : 0);
+      const bool hit = (bal[w ? 1 : 0] & bit) != 0;
+      cpos[tid] = hit ? static_cast<int16_t>(-(1 + nc)) : static_cast<int16_t>(tid - nc);
+    }
+  }
+  // unused columns / pad rows of the LDS tiles stay zero for the whole kernel
+  for (uint32_t it = tid; it < 2 * bufb / 16; it += kCBlock)
+    reinterpret_cast<u32x4*>(smem)[it] = u32x4{0u, 0u, 0u, 0u};
+
+  Frag<T> ones;
+  ones.v = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+
+  f32x4 acc[4][DT];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) acc[mt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  f32x4 acc_dc = {0.f, 0.f, 0.f, 0.f};   // rows are identical: the column sums of tile rgw
+
+  T* keep = static_cast<T*>(p.keep) + static_cast<int64_t>(bh) * p.keep_stride;
+  __syncthreads();   // cpos and the zero fills are visible
+
+  // ---- where each of the thread's 8 dims goes inside a buffer (bytes) -----------------------
+  uint32_t sc_off[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int cp = cpos[ch * 8 + e];
+    if (cp < 0) sc_off[e] = (static_cast<uint32_t>(-cp - 1) * kFP + 4 * quad) * 2;
+    else if (write_keep) sc_off[e] = ks_off + (static_cast<uint32_t>(cp) * kFP + 4 * quad) * 2;
+    else sc_off[e] = ks_off + static_cast<uint32_t>(kp) * kFP * 2;   // spare slot: the value is not needed
+  }
+  // ---- kept dims leave the staging tile as 128-bit stores: one or more vectors per thread ------
+  // rows layout: vector (token jt, 8 dims 8 c8..): gathered from 8 tile rows; tok8 layout: vector
+  // (dim, 8 tokens 8 g..): contiguous in the tile
+  const int nvec = rows_layout ? kFB * (kp / 8) : Du * (kFB / 8);
+  const int c8n = max(kp / 8, 1), dun = max(Du, 1);
+  const int kv_0 = tid;                                          // first vector of this thread
+  const int kv_a = rows_layout ? kv_0 / c8n : kv_0 / dun;        // token (rows) or 8-token group (tok8)
+  const int kv_b = rows_layout ? kv_0 - kv_a * c8n : kv_0 - kv_a * dun;   // 8-dim group (rows) or dim (tok8)
+
+  FA_CSTAMP(1);
+  // The two column halves of the workgroup (waves 0-3 and 4-7; wave w and w + 4 share a SIMD) run
+  // half a block out of phase: while one half multiplies block b on the matrix cores, the other
+  // scatters its tokens of block b + 1 and writes out kept dims of block b, then they swap.
+  const int grp = chw;
+  auto scatter_block = [&](Frag<T> (&xr)[4], int blk) {   // this thread's 4 tokens x 8 dims of block blk -> LDS
+    const int js = j0 + blk * kFB;
+    unsigned char* bb = smem + (blk & 1) * bufb;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int w = e >> 1;
+      uint32_t lo, hi;
+      if (e & 1) {
+        lo = pack_hi(xr[0].v[w], xr[1].v[w]);
+        hi = pack_hi(xr[2].v[w], xr[3].v[w]);
+      } else {
+        lo = pack_lo(xr[0].v[w], xr[1].v[w]);
+        hi = pack_lo(xr[2].v[w], xr[3].v[w]);
+      }
+      *reinterpret_cast<u32x2c*>(bb + sc_off[e]) = u32x2c{lo, hi};
+    }
+    if (js + kFB > jend) {   // ragged last block: tokens past the end count as zeros (written over)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (js + 4 * quad + i >= jend) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) *reinterpret_cast<uint16_t*>(bb + sc_off[e] + 2 * i) = 0;
+        }
+    }
+  };
+  auto keep_out = [&](int blk) {   // this half's share of the kept dims of block blk: tile -> 128-bit stores
+    const int js = j0 + blk * kFB;
+    const T* ks = reinterpret_cast<const T*>(smem + (blk & 1) * bufb + ks_off);
+    const int64_t tok0 = static_cast<int64_t>(p.keep_offset) + js;
+    const int it0 = tid;
+    if (rows_layout) {
+      for (int it = it0; it < nvec; it += kCBlock) {
+        const int jt = (it == it0) ? kv_a : it / c8n, c8 = (it == it0) ? kv_b : it - (it / c8n) * c8n;
+        if (js + jt < jend) {
+          const uint16_t* src = reinterpret_cast<const uint16_t*>(ks) + (8 * c8) * kFP + jt;
+          u32x4 v;
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            v[k] = static_cast<uint32_t>(src[(2 * k) * kFP]) | (static_cast<uint32_t>(src[(2 * k + 1) * kFP]) << 16);
+          *reinterpret_cast<u32x4*>(keep + (tok0 + jt) * kp + 8 * c8) = v;
+        }
+      }
+    } else {
+      for (int it = it0; it < nvec; it += kCBlock) {
+        const int g = (it == it0) ? kv_a : it / dun, dim = (it == it0) ? kv_b : it - (it / dun) * dun;
+        if (js + 8 * g < jend) {
+          Frag<T> f;
+          f.load(ks + dim * kFP + 8 * g);
+          *reinterpret_cast<Frag<T>*>(keep + (((tok0 >> 3) + g) * Du + dim) * 8) = f;
+        }
+      }
+    }
+  };
+  auto multiply_block = [&](int blk) {
+    if (!wave_live && !wave_dc) return;
+    const T* xcb = reinterpret_cast<const T*>(smem + (blk & 1) * bufb);
+    const T* bcol = xcb + (chw * DT * 16 + r16) * kFP + 8 * q4;   // this lane's column in tile 0
+    // The B operands of column tile dt + 1 are requested before the products of tile dt are
+    // issued, and the turn of the frame runs while the first tile's operands travel.
+    Frag<T> bxa[kFK], bxb[kFK];
+#pragma unroll
+    for (int ksx = 0; ksx < kFK; ++ksx) bxa[ksx].load(bcol + 32 * ksx);
+    if (wave_live) {
+      // (also for the first block: the accumulators are zero then, and an unconditional turn keeps
+      // them in place in their registers)
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+          const float c = twc[mt][pr], sn = tws[mt][pr];
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) {
+            const float ac = acc[mt][dt][2 * pr], as = acc[mt][dt][2 * pr + 1];
+            acc[mt][dt][2 * pr] = c * ac + sn * as;
+            acc[mt][dt][2 * pr + 1] = c * as - sn * ac;
+          }
+        }
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      Frag<T> (&cur)[kFK] = (dt & 1) ? bxb : bxa;
+      Frag<T> (&nxt)[kFK] = (dt & 1) ? bxa : bxb;
+      if (dt + 1 < DT) {   // (tiles past the last compressed column are zero-filled, never written)
+#pragma unroll
+        for (int ksx = 0; ksx < kFK; ++ksx) nxt[ksx].load(bcol + (dt + 1) * 16 * kFP + 32 * ksx);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (wave_live && dt < ndt) {
+#pragma unroll
+        for (int ksx = 0; ksx < kFK; ++ksx)
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt) mma_k32(acc[mt][dt], ea[mt][ksx], cur[ksx]);
+      }
+      // constant function: a row of ones against column tile rgw of this wave's half
+      if (wave_dc && dt == rgw) {
+#pragma unroll
+        for (int ksx = 0; ksx < kFK; ++ksx) mma_k32(acc_dc, ones, cur[ksx]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto two_slots = [&](Frag<T> (&xnext)[4], int blk) {   // block blk; xnext holds block blk + 1
+    if (blk + 1 < nb) scatter_block(xnext, blk + 1);
+    if (write_keep) keep_out(blk);
+    FA_CSTAMP(3 + 4 * blk);
+    multiply_block(blk);
+    FA_CSTAMP(4 + 4 * blk);
+    __syncthreads();
+    FA_CSTAMP(5 + 4 * blk);
+  };
+  // Loads are issued where every wave passes (never inside the half-specific branches, where the
+  // result would have to be merged with the other path, i.e. waited for): once both halves have
+  // scattered a register set, the block two ahead is requested into it.
+  scatter_block(xra, 0);
+  load_x(xra, 2);
+  __syncthreads();
+  FA_CSTAMP(2);
+  for (int blk = 0; blk < nb; blk += 2) {
+    two_slots(xrb, blk);
+    load_x(xrb, blk + 3);
+    if (blk + 1 < nb) two_slots(xra, blk + 1);
+    load_x(xra, blk + 4);
+  }
+
+  FA_CSTAMP(30);
+  // ---- epilogue -----------------------------------------------------------------------------
+  if (!project) return;
+  float* dst = (p.Sc == 1) ? p.coeffs + static_cast<size_t>(bh) * M * p.Dc
+                           : p.part + static_cast<size_t>(s) * p.part_stride + static_cast<size_t>(bh) * M * p.Dc;
+  const bool add = (p.Sc == 1) && p.accumulate;
+  if (wave_dc && q4 == 0) {
+    const int i = (chw * DT + rgw) * 16 + r16;
+    if (i < p.Dc) dst[i] = add ? dst[i] + acc_dc[0] : acc_dc[0];
+  }
+  if (wave_live) {
+    const uint32_t ph_last = fixed_phase(p.t0 + j0 + (nb - 1) * kFB, p.ph_scale);   // frame origin
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int pr = 0; pr < 2; ++pr) {
+        const int n = mc * kPairs + ((rgw * 64 + mt * 16 + 4 * q4) >> 1) + pr + 1;
+        if (n > p.nmax) continue;
+        float c, sn;
+        fixed_phase_cs<T>(static_cast<uint32_t>(n) * ph_last, &c, &sn);
+        const int m_cos = 2 * n - 1, m_sin = 2 * n;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          const int i = (chw * DT + dt) * 16 + r16;
+          if (dt < ndt && i < p.Dc) {
+            const float ac = acc[mt][dt][2 * pr], as = acc[mt][dt][2 * pr + 1];
+            const float vc = c * ac - sn * as, vs = sn * ac + c * as;
+            float* oc = dst + static_cast<size_t>(m_cos) * p.Dc + i;
+            *oc = add ? (*oc + vc) : vc;
+            if (m_sin < M) {
+              float* os = dst + static_cast<size_t>(m_sin) * p.Dc + i;
+              *os = add ? (*os + vs) : vs;
+            }
+          }
+        }
+      }
+  }
+  FA_CSTAMP(31);
+}
+
 // sum of the token-chunk partials (fixed order, so results are reproducible)
 __global__ __launch_bounds__(256) void compress_reduce(const float* part, float* coeffs, size_t total,
                                                        size_t stride, int Sc, int accumulate) {
@@ -469,13 +802,13 @@ static CompressPlan make_compress_plan(int dtype, int B, int H, int N, int D, in
   pl.MC = (Dc > 0 && pl.nmax > 0) ? (pl.nmax + kPairs - 1) / kPairs : 1;
   pl.DCn = Dc > 0 ? (Dc + kCols - 1) / kCols : 1;
   const long groups = static_cast<long>(B) * H * pl.MC * pl.DCn;
-  const long nblocks = (N + kTB - 1) / kTB;
+  const long nblocks = (N + kFB - 1) / kFB;       // 128-token blocks (two blocks of the generic kernel)
   long want = (512 + groups - 1) / groups;       // token chunks that fill the chip twice over
-  const long cap = nblocks / 16 > 0 ? nblocks / 16 : 1;   // but at least 16 blocks per chunk: the
+  const long cap = nblocks / 8 > 0 ? nblocks / 8 : 1;     // but at least 1024 tokens per chunk: the
   if (want > cap) want = cap;                             // chunk partials cost memory traffic
   if (want < 1) want = 1;
   const long per = N > 0 ? (nblocks + want - 1) / want : 1;
-  pl.chunk = static_cast<int>(per) * kTB;
+  pl.chunk = static_cast<int>(per) * kFB;
   pl.Sc = N > 0 ? (N + pl.chunk - 1) / pl.chunk : 0;
   pl.total = (pl.Sc > 1 && Dc > 0)
                  ? align_up(static_cast<size_t>(pl.Sc) * ((static_cast<size_t>(B) * H * M * Dc + 3) & ~size_t(3)) *
@@ -502,6 +835,22 @@ static int check_compress_shapes(int dtype, int B, int H, int N, int D, int Dc, 
   if (M < 1 || T < 1 || M > T || t0 < 0 || static_cast<long>(t0) + N > T) return FA_ERR_SHAPE;
   if (D % 8 != 0 || D > FA_MAX_HEAD_DIM || M > FA_MAX_STATES) return FA_ERR_UNSUPPORTED;
   if (static_cast<long>(B) * H > 65535) return FA_ERR_UNSUPPORTED;
+  return FA_OK;
+}
+
+template <int DT>
+static int launch_project_fast(const CompressParams& p, const CompressPlan& pl, unsigned lds, hipStream_t st) {
+  auto kern = compress_project_fast<DT>;
+  static unsigned granted = 48 * 1024;
+  if (lds > granted) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(kMaxCLds)) != hipSuccess)
+      return FA_ERR_HIP;
+    granted = kMaxCLds;
+  }
+  dim3 grid(pl.Sc, pl.MC, p.B * p.H);
+  hipLaunchKernelGGL(kern, grid, dim3(kCBlock), lds, st, p);
   return FA_OK;
 }
 
@@ -600,8 +949,16 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
       FA_LAUNCH_PROJECT2(T_, false);\
     }                               \
   } while (0)
-    if (dtype == FA_F32) FA_LAUNCH_PROJECT(float);
-    else FA_LAUNCH_PROJECT(bf16_t);
+    // bf16 with head dim 128 and staged (or no) kept dims: the specialised kernel
+    const unsigned fast_lds = 2u * (kCols * kFP + static_cast<unsigned>(keep_pitch) * kFP + 8u) * 2u;
+    const bool staged_ok = x_keep == nullptr || Du == 0 || keep_layout == FA_KEEP_ROWS || keep_offset % 8 == 0;
+    if (dtype == FA_BF16 && D == 128 && staged_ok && fast_lds <= kMaxCLds) {
+      rc = narrow ? launch_project_fast<3>(p, pl, fast_lds, stream) : launch_project_fast<4>(p, pl, fast_lds, stream);
+    } else if (dtype == FA_F32) {
+      FA_LAUNCH_PROJECT(float);
+    } else {
+      FA_LAUNCH_PROJECT(bf16_t);
+    }
 #undef FA_LAUNCH_PROJECT2
 #undef FA_LAUNCH_PROJECT
     if (rc != FA_OK) return rc;
