@@ -28,8 +28,11 @@ METRIC = "Fourier-KV decode context tokens/s/GPU + achieved HBM GB/s (% of peak)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from hardware counters (FETCH_SIZE + WRITE_SIZE, each scaled by what the
 # same counter reads for the --copy-probe kernel), keyed by (kernel, config index).
-# Source: profiles/hbm_traffic_*.txt; null for anything not measured there.
-MEASURED_TRAFFIC = {}
+# Source: profiles/bench_cfg*_hbm_traffic.txt; null for anything not measured there.
+MEASURED_TRAFFIC = {
+    ("compress_project", 2): 105986288,   # 65.35 MB read + 40.63 MB written (24.4 MB of it chunk partials)
+    ("decode_partial", 2): 39425501,      # 37.54 MB read + 1.89 MB written (split-K partial records)
+}
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_MATRIX_PEAK_TFLOPS = 157.3
 LLC_BYTES = 256 << 20

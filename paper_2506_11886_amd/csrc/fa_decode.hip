@@ -527,7 +527,9 @@ __device__ __forceinline__ void table_cs(int n, int u, int period, float inv_per
   }
 }
 
-template <typename T, int CW, int DVTM>
+// KC1: the kept K dims fit one 32-dim MFMA step (the usual case), so that all K^mu operands of
+// a step are requested ahead and none on demand.
+template <typename T, int CW, int DVTM, bool KC1>
 __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsigned char* smem) {
   using ES = typename SeriesType<T>::type;
   constexpr int Mint = kWaves * CW * 32;
@@ -806,13 +808,20 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
         if (i < KT) {
           const int uid = wave * KT + i, k = uid >> 2, rbd = uid & 3;
           f32x4 ka = {0.f, 0.f, 0.f, 0.f};
-          for (int cc = 0; cc < kchunks; ++cc) {
-            Frag<T> a = kf[i];
-            if (cc > 0) a.load(k_ptr(base, uid, cc));
+          {
             Frag<T> bq;
-            bq.load(qk_s + hsafe * Dkq + cc * 32 + 8 * q4);
+            bq.load(qk_s + hsafe * Dkq + 8 * q4);
             if (col_k != k || !col_live) bq.zero();
-            mma_k32(ka, a, bq);
+            mma_k32(ka, kf[i], bq);
+          }
+          if constexpr (!KC1) {
+            for (int cc = 1; cc < kchunks; ++cc) {
+              Frag<T> a, bq;
+              a.load(k_ptr(base, uid, cc));
+              bq.load(qk_s + hsafe * Dkq + cc * 32 + 8 * q4);
+              if (col_k != k || !col_live) bq.zero();
+              mma_k32(ka, a, bq);
+            }
           }
           if (rbd == 0) sacc[0] += ka;
           else if (rbd == 1) sacc[1] += ka;
@@ -1032,10 +1041,10 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
   FA_STAMP(15);
 }
 
-template <typename T, int CW, int DVTM>
+template <typename T, int CW, int DVTM, bool KC1>
 __global__ __launch_bounds__(kBlock, (CW <= 2 && sizeof(T) == 2) ? 2 : 1) void decode_partial(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  if (static_cast<int>(blockIdx.x) < p.Sm) partial_middle_rows<T, CW, DVTM>(p, smem);
+  if (static_cast<int>(blockIdx.x) < p.Sm) partial_middle_rows<T, CW, DVTM, KC1>(p, smem);
   else partial_full_rows<T>(p, smem);
 }
 
@@ -1355,9 +1364,9 @@ static int check_decode_shapes(int dtype, int B, int Hq, int Hkv, int D, int Dkc
   return FA_OK;
 }
 
-template <typename T, int CW, int DVTM>
+template <typename T, int CW, int DVTM, bool KC1>
 static int launch_partial(const DecodeParams& p, unsigned lds, hipStream_t st) {
-  auto kern = decode_partial<T, CW, DVTM>;
+  auto kern = decode_partial<T, CW, DVTM, KC1>;
   // raising the dynamic-LDS ceiling is a property of the loaded kernel: do it once
   static unsigned granted = 48 * 1024;
   if (lds > granted) {
@@ -1384,9 +1393,11 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
   if (ev) (void)hipEventRecord(ev[1], st);
   int rc;
   const bool narrow = p.Dvu <= 32;   // kept V dims fit two MFMA column tiles
-#define FA_LAUNCH_PARTIAL(CW_)                                                     \
-  rc = narrow ? launch_partial<T, CW_, 2>(p, pl.lds_total, st)                     \
-              : launch_partial<T, CW_, kMaxDvTiles>(p, pl.lds_total, st)
+  const bool kc1 = p.Dku <= 32;      // kept K dims fit one MFMA step
+#define FA_LAUNCH_PARTIAL(CW_)                                                                      \
+  rc = (narrow && kc1) ? launch_partial<T, CW_, 2, true>(p, pl.lds_total, st)                       \
+       : narrow        ? launch_partial<T, CW_, 2, false>(p, pl.lds_total, st)                      \
+                       : launch_partial<T, CW_, kMaxDvTiles, false>(p, pl.lds_total, st)
   switch (pl.cw) {
     case 1: FA_LAUNCH_PARTIAL(1); break;
     case 2: FA_LAUNCH_PARTIAL(2); break;
