@@ -46,6 +46,7 @@ __all__ = [
     "decode_head_group",
     "compress_batched",
     "decode_batched",
+    "append_token",
 ]
 
 
@@ -181,3 +182,31 @@ def decode_batched(q, Ck, kmask, Cv, vmask, T, t0, N,
                 q[b, h * G:(h + 1) * G], Ck[b, h], kmask[b, h], Cv[b, h], vmask[b, h],
                 T, t0, N, k_keep[b, h], v_keep[b, h], k_full[b, h], v_full[b, h], scale)
     return out
+
+
+def append_token(Ck, Cv, kmask, vmask, k_keep, v_keep, k_full, v_full, slot: int, k_new, v_new,
+                 T: int, n_mid: int, evict: bool):
+    """One decode step of cache maintenance for one KV head (Eq. 5 and the window of Eq. 1).
+
+    The recent window lives in rows of k_full / v_full (their order never matters to Eq. 6);
+    `slot` is the row that holds the oldest window token.  With `evict`, that token leaves the
+    window and becomes middle token number n_mid: its compressed dims are folded into the
+    coefficient states by the rank-one update of Eq. 5 (the basis column taken at the token's own
+    position n_mid), its kept dims are appended to K^mu / V^mu.  The new token then takes the row.
+
+    Returns new (Ck, Cv, k_keep, v_keep, k_full, v_full); nothing is modified in place.
+    """
+    Ck = np.asarray(Ck, dtype=np.float64)
+    Cv = np.asarray(Cv, dtype=np.float64)
+    k_keep = np.asarray(k_keep, dtype=np.float64)
+    v_keep = np.asarray(v_keep, dtype=np.float64)
+    k_full = np.array(k_full, dtype=np.float64, copy=True)
+    v_full = np.array(v_full, dtype=np.float64, copy=True)
+    if evict:
+        Ck, ku = compress_segment(k_full[slot][None, :], kmask, Ck.shape[0], T, n_mid, C_prev=Ck)
+        Cv, vu = compress_segment(v_full[slot][None, :], vmask, Cv.shape[0], T, n_mid, C_prev=Cv)
+        k_keep = np.concatenate([k_keep.reshape(-1, ku.shape[1]), ku], axis=0)
+        v_keep = np.concatenate([v_keep.reshape(-1, vu.shape[1]), vu], axis=0)
+    k_full[slot] = np.asarray(k_new, dtype=np.float64)
+    v_full[slot] = np.asarray(v_new, dtype=np.float64)
+    return Ck, Cv, k_keep, v_keep, k_full, v_full

@@ -381,3 +381,58 @@ def test_planted_mistakes_in_attention_are_caught(monkeypatch):
         return C, keep[:, ::-1]
     monkeypatch.setattr(fk, "compress_segment", compress_rev)
     assert _some_pin_fails()
+
+
+# ---------------------------------------------------------------------------
+# streaming maintenance (Eq. 5 + the window of Eq. 1)
+# ---------------------------------------------------------------------------
+def test_append_token_equals_recompression_of_the_longer_segment():
+    """Feeding tokens one at a time through the window must leave exactly the state that
+    compressing the longer middle segment in one shot gives, and attention over that state
+    must equal attention over the one-shot state (Eq. 5 is Eq. 3 restricted to one row)."""
+    rng = np.random.default_rng(77)
+    d, Li, Lw, N0, steps, M = 16, 2, 5, 20, 9, 7
+    T = N0 + steps
+    kmask = np.zeros(d, np.uint8); kmask[rng.choice(d, 11, replace=False)] = 1
+    vmask = np.zeros(d, np.uint8); vmask[rng.choice(d, 9, replace=False)] = 1
+    total = Li + N0 + Lw + steps
+    K = rng.standard_normal((total, d)); V = rng.standard_normal((total, d))
+    # state after prefill: sink rows, N0 middle rows compressed, a full window
+    Ck, kk = fk.compress_segment(K[Li:Li + N0], kmask, M, T, 0)
+    Cv, vk = fk.compress_segment(V[Li:Li + N0], vmask, M, T, 0)
+    k_full = np.concatenate([K[:Li], K[Li + N0:Li + N0 + Lw]]); v_full = np.concatenate([V[:Li], V[Li + N0:Li + N0 + Lw]])
+    for s in range(steps):
+        slot = Li + s % Lw            # ring: the oldest window row
+        t_new = Li + N0 + Lw + s
+        Ck, Cv, kk, vk, k_full, v_full = fk.append_token(Ck, Cv, kmask, vmask, kk, vk, k_full, v_full, slot,
+                                                         K[t_new], V[t_new], T, N0 + s, True)
+    # one-shot reference over the longer segment
+    Ck1, kk1 = fk.compress_segment(K[Li:Li + N0 + steps], kmask, M, T, 0)
+    Cv1, vk1 = fk.compress_segment(V[Li:Li + N0 + steps], vmask, M, T, 0)
+    assert np.allclose(Ck, Ck1, atol=1e-12) and np.allclose(Cv, Cv1, atol=1e-12)
+    assert np.array_equal(kk, kk1) and np.array_equal(vk, vk1)
+    # the window holds the last Lw tokens (as a set of rows), the sink rows are untouched
+    want = K[total - Lw:]
+    got = k_full[Li:]
+    assert np.array_equal(np.sort(got, axis=0), np.sort(want, axis=0))
+    assert np.array_equal(k_full[:Li], K[:Li])
+    q = rng.standard_normal((2, d))
+    o_stream = fk.decode_head_group(q, Ck, kmask, Cv, vmask, T, 0, N0 + steps, kk, vk, k_full, v_full)
+    o_shot = fk.decode_head_group(q, Ck1, kmask, Cv1, vmask, T, 0, N0 + steps, kk1, vk1,
+                                  np.concatenate([K[:Li], K[total - Lw:]]), np.concatenate([V[:Li], V[total - Lw:]]))
+    assert np.allclose(o_stream, o_shot, atol=1e-12)
+
+
+def test_append_token_without_eviction_only_fills_the_window():
+    rng = np.random.default_rng(5)
+    d, M, T = 8, 5, 40
+    kmask = np.array([1, 0, 1, 1, 0, 0, 1, 0], np.uint8); vmask = kmask[::-1].copy()
+    Ck = rng.standard_normal((M, 4)); Cv = rng.standard_normal((M, 4))
+    kk = rng.standard_normal((3, 4)); vk = rng.standard_normal((3, 4))
+    k_full = rng.standard_normal((6, d)); v_full = rng.standard_normal((6, d))
+    kn, vn = rng.standard_normal(d), rng.standard_normal(d)
+    out = fk.append_token(Ck, Cv, kmask, vmask, kk, vk, k_full, v_full, 4, kn, vn, T, 3, False)
+    assert np.array_equal(out[0], Ck) and np.array_equal(out[1], Cv)
+    assert np.array_equal(out[2], kk) and np.array_equal(out[3], vk)
+    assert np.array_equal(out[4][4], kn) and np.array_equal(out[5][4], vn)
+    assert np.array_equal(np.delete(out[4], 4, axis=0), np.delete(k_full, 4, axis=0))
