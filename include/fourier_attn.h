@@ -1,7 +1,7 @@
 /*
  * fourier_attn.h -- C ABI of the MI355X (gfx950) FourierAttention hot path.
  *
- * Two operations of the paper's Section 3.3 ("Online Compression via
+ * Three operations of the paper's Section 3.3 ("Online Compression via
  * HiPPO-FourierT"):
  *
  *   fa_compress  Eq. 1-4 (and Eq. 5 when `accumulate` is set): split the head
@@ -13,6 +13,8 @@
  *                reconstructed middle rows) where the compressed dimensions
  *                of the middle rows are evaluated from their coefficients on
  *                the fly and never written to memory.
+ *   fa_append    Eq. 5: the per-token update between two decode steps (the
+ *                token leaving the recent window is folded into the state).
  *
  * Conventions shared by every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
@@ -138,6 +140,34 @@ int fa_decode(const void* q, int dtype,
 
 size_t fa_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int Dkc, int Dvc,
                                  int M, int N, int W, int num_splits);
+
+/*
+ * fa_append -- one decode step of cache maintenance (Eq. 5 and the recent window of Eq. 1).
+ *
+ * The recent window is a ring inside k_full / v_full (fa_decode does not care about the order of
+ * their rows).  `slot` is the row that receives the new token.  With evict = 1 the window is full
+ * and that row still holds its oldest token, which first becomes middle token number n_mid:
+ *   ck[b,h,m,:] += phi_m(n_mid) * row[D^kc]        (the rank-one update of Eq. 5; same for cv)
+ *   token n_mid of k_keep (FA_KEEP_ROWS) and of v_keep (FA_KEEP_TOK8) = row at the kept dims
+ * With evict = 0 (window still filling) only the row is written and the arguments from kmask on
+ * are ignored.  Afterwards fa_decode is called with N = n_mid + 1.
+ *
+ *   k_new,v_new [B,Hkv,D] `dtype`: the new token's key and value.
+ *   k_full,v_full [B,Hkv,W,D] as for fa_decode, updated in place.
+ *   n_mid       tokens folded so far = position of the evicted token; n_mid < T.
+ *   ck, cv, k_keep, v_keep  as for fa_compress / fa_decode, updated in place; the slabs must
+ *               have room for n_mid + 1 tokens (strides 0 = dense for exactly that many).
+ *
+ * Enqueues two small kernels on `hip_stream`; needs no workspace.
+ */
+int fa_append(const void* k_new, const void* v_new, int dtype,
+              int B, int Hkv, int D,
+              void* k_full, void* v_full, int W, int64_t full_stride_bh, int slot, int evict,
+              const uint8_t* kmask, int Dkc, const uint8_t* vmask, int Dvc,
+              int M, int T, int n_mid,
+              float* ck, float* cv,
+              void* k_keep, int64_t kk_stride_bh, void* v_keep, int64_t vk_stride_bh,
+              void* hip_stream);
 
 /*
  * Measurement aids.  Same arguments and effect as fa_compress / fa_decode, but

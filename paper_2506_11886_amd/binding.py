@@ -50,6 +50,9 @@ def _load(path: str = _LIB_PATH):
     lib.fa_decode_workspace_bytes.argtypes = [i32] * 10
     lib.fa_decode_default_splits.restype = i32
     lib.fa_decode_default_splits.argtypes = [i32] * 6
+    lib.fa_append.restype = i32
+    lib.fa_append.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i64, i32, i32,
+                              vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, i64, vp, i64, vp]
     lib.fa_status_string.restype = c.c_char_p
     lib.fa_status_string.argtypes = [i32]
     return lib
@@ -182,3 +185,22 @@ def fa_decode(q, ck, kmask, cv, vmask, M, T, t0, N, k_keep, v_keep, k_full, v_fu
     if st != FA_OK:
         raise FourierAttnError(st, "fa_decode")
     return out
+
+
+def fa_append(k_new, v_new, k_full, v_full, slot, evict, kmask=None, vmask=None, M=0, T=0, n_mid=0,
+              ck=None, cv=None, k_keep=None, v_keep=None, stream=None,
+              kk_stride_bh=0, vk_stride_bh=0, full_stride_bh=0):
+    """Enqueue fa_append on `stream`: the new token takes row `slot` of k_full / v_full; with
+    `evict` the row's old token is first folded into ck / cv / k_keep / v_keep as middle token
+    number n_mid.  Everything is updated in place."""
+    B, Hkv, D = k_new.shape
+    W = k_full.shape[2]
+    Dkc = ck.shape[-1] if ck is not None else 0
+    Dvc = cv.shape[-1] if cv is not None else 0
+    st = lib.fa_append(_ptr(k_new), _ptr(v_new), _dtype_code(k_new), B, Hkv, D,
+                       _ptr(k_full), _ptr(v_full), W, full_stride_bh, int(slot), 1 if evict else 0,
+                       _ptr(kmask), Dkc, _ptr(vmask), Dvc, M, T, n_mid,
+                       _ptr(ck), _ptr(cv), _ptr(k_keep), kk_stride_bh, _ptr(v_keep), vk_stride_bh,
+                       _stream_ptr(stream))
+    if st != FA_OK:
+        raise FourierAttnError(st, "fa_append")

@@ -21,7 +21,8 @@ def test_library_exports_every_declared_symbol():
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(fa_[a-z_0-9]+)\s*\(", hdr))
     assert {"fa_compress", "fa_decode", "fa_compress_workspace_bytes",
-            "fa_decode_workspace_bytes", "fa_decode_default_splits", "fa_status_string"} <= names
+            "fa_decode_workspace_bytes", "fa_decode_default_splits", "fa_status_string",
+            "fa_append"} <= names
     for n in names:
         assert hasattr(fa.lib, n), n
 
@@ -87,3 +88,24 @@ def test_workspace_queries():
     assert fa.decode_workspace_bytes(1, 7, 2, 128, 96, 96, 256, 100, 10, 0) == 0
     assert fa.compress_workspace_bytes(8, 32, 4096, 128, 96, 256) >= 256
     assert fa.decode_default_splits(1, 32, 8, 256, 31740, 1028) >= 1
+
+
+def test_append_rejects_bad_arguments_on_the_host():
+    fa = _fa()
+    a = dict(k_new=FAKE, v_new=FAKE, dtype=1, B=1, Hkv=2, D=64, k_full=FAKE, v_full=FAKE, W=8, fs=0, slot=3,
+             evict=1, kmask=FAKE, Dkc=48, vmask=FAKE, Dvc=48, M=16, T=100, n_mid=5, ck=FAKE, cv=FAKE,
+             k_keep=FAKE, kks=0, v_keep=FAKE, vks=0, stream=None)
+
+    def call(**kw):
+        d = dict(a, **kw)
+        return fa.lib.fa_append(d["k_new"], d["v_new"], d["dtype"], d["B"], d["Hkv"], d["D"], d["k_full"],
+                                d["v_full"], d["W"], d["fs"], d["slot"], d["evict"], d["kmask"], d["Dkc"],
+                                d["vmask"], d["Dvc"], d["M"], d["T"], d["n_mid"], d["ck"], d["cv"], d["k_keep"],
+                                d["kks"], d["v_keep"], d["vks"], d["stream"])
+    assert call(slot=8) == -2            # slot outside the rows
+    assert call(k_new=None) == -1
+    assert call(D=60) == -3              # head dim not a multiple of 8
+    assert call(n_mid=100) == -2         # position outside the period
+    assert call(ck=None) == -1
+    assert call(dtype=7) == -3
+    assert call(kks=5) == -2             # slab too small for n_mid + 1 rows

@@ -157,3 +157,86 @@ def test_compress_streaming_update_matches_one_shot():
     # both sides round the basis table to the element type at different block phases
     assert rel_err(c.cpu().numpy(), full.cpu().numpy()) <= cfg.tol
     assert torch.equal(keep, keep_full)
+
+
+@pytest.mark.parametrize("name", ["tiny", "gqa8_oddM", "odd_dims"])
+def test_append_steps_match_oracle(name):
+    """fa_append (Eq. 5 + window ring), several steps in a row, against oracle.append_token; then
+    one decode over the streamed state against the oracle's decode over its streamed state."""
+    import oracle.fourier_kv as fk
+    fa = _fa()
+    cfg = next(c for c in SMALL if c.name == name)
+    ctx = cached_context(cfg)
+    B, H, D, M, G = cfg.B, cfg.Hkv, cfg.D, cfg.M, cfg.G
+    Dku, Dvu = D - cfg.Dkc, D - cfg.Dvc
+    steps, W = 11, cfg.W
+    N0 = cfg.N - steps                 # prefill compresses N0 rows; the others are still "window" rows
+    T = cfg.N                          # room for every token that will be folded
+    Li = cfg.Li
+    ring = W - Li
+    assert ring >= 1 and N0 > 0
+    rng = np.random.default_rng(4242)
+    dt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    new_k = torch.from_numpy(rng.standard_normal((steps, B, H, D)).astype(np.float32)).to(dt)
+    new_v = torch.from_numpy(rng.standard_normal((steps, B, H, D)).astype(np.float32)).to(dt)
+
+    # --- GPU: prefill with room for the appended tokens, then the steps ---
+    kmask, vmask = to_dev(ctx["kmask"]), to_dev(ctx["vmask"])
+    k_mid, v_mid = to_dev(ctx["k_mid"][:, :, :N0], cfg), to_dev(ctx["v_mid"][:, :, :N0], cfg)
+    kk = torch.zeros((B, H, cfg.N, fa.keep_rows_pitch(Dku)), dtype=dt, device="cuda")
+    vk = torch.zeros((B, H, fa.tok8_numel(cfg.N, Dvu)), dtype=dt, device="cuda")
+    ck, _ = fa.fa_compress(k_mid, kmask, cfg.Dkc, M, T, x_keep=kk, keep_layout=fa.FA_KEEP_ROWS,
+                           keep_stride_bh=kk.stride(1))
+    cv, _ = fa.fa_compress(v_mid, vmask, cfg.Dvc, M, T, x_keep=vk, keep_layout=fa.FA_KEEP_TOK8,
+                           keep_stride_bh=vk.stride(1))
+    k_full, v_full = to_dev(ctx["k_full"], cfg), to_dev(ctx["v_full"], cfg)
+    for s in range(steps):
+        slot = Li + s % ring
+        fa.fa_append(new_k[s].cuda(), new_v[s].cuda(), k_full, v_full, slot, True, kmask, vmask, M, T, N0 + s,
+                     ck, cv, kk, vk, kk_stride_bh=kk.stride(1), vk_stride_bh=vk.stride(1))
+    out = fa.fa_decode(to_dev(ctx["q"], cfg), ck, kmask, cv, vmask, M, T, 0, N0 + steps, kk, vk, k_full, v_full,
+                       kk_stride_bh=kk.stride(1), vk_stride_bh=vk.stride(1))
+    torch.cuda.synchronize()
+
+    # --- oracle, head by head ---
+    ck_g, cv_g = ck.cpu().numpy(), cv.cpu().numpy()
+    kk_g = kk.float().cpu().numpy()[..., :Dku]
+    vk_g = fa.keep_rows_from_tok8(vk, cfg.N, Dvu).float().cpu().numpy()
+    kf_g, vf_g = k_full.float().cpu().numpy(), v_full.float().cpu().numpy()
+    nk, nv = new_k.float().numpy().astype(np.float64), new_v.float().numpy().astype(np.float64)
+    out = out.cpu().numpy()
+    for b in range(B):
+        for h in range(H):
+            km, vm = ctx["kmask"][b, h], ctx["vmask"][b, h]
+            Ck, kko = fk.compress_segment(ctx["k_mid"][b, h][:N0], km, M, T, 0)
+            Cv, vko = fk.compress_segment(ctx["v_mid"][b, h][:N0], vm, M, T, 0)
+            kf, vf = ctx["k_full"][b, h].astype(np.float64), ctx["v_full"][b, h].astype(np.float64)
+            for s in range(steps):
+                Ck, Cv, kko, vko, kf, vf = fk.append_token(Ck, Cv, km, vm, kko, vko, kf, vf, Li + s % ring,
+                                                           nk[s, b, h], nv[s, b, h], T, N0 + s, True)
+            if cfg.Dkc:
+                fl = np.sqrt((N0 + steps) * np.mean(ctx["k_mid"][b, h][:, km == 1].astype(np.float64) ** 2))
+                assert rel_err(ck_g[b, h], Ck, fl) <= cfg.tol, ("ck", b, h)
+            if cfg.Dvc:
+                fl = np.sqrt((N0 + steps) * np.mean(ctx["v_mid"][b, h][:, vm == 1].astype(np.float64) ** 2))
+                assert rel_err(cv_g[b, h], Cv, fl) <= cfg.tol, ("cv", b, h)
+            assert np.array_equal(kk_g[b, h][:N0 + steps], kko), ("k_keep", b, h)
+            assert np.array_equal(vk_g[b, h][:N0 + steps], vko), ("v_keep", b, h)
+            assert np.array_equal(kf_g[b, h], kf) and np.array_equal(vf_g[b, h], vf), ("ring", b, h)
+            want = fk.decode_head_group(ctx["q"][b, h * G:(h + 1) * G], Ck, km, Cv, vm, T, 0, N0 + steps,
+                                        kko, vko, kf, vf)
+            got = out[b, h * G:(h + 1) * G]
+            assert rel_err(got, want) <= cfg.tol, ("out", b, h, rel_err(got, want))
+
+
+def test_append_without_eviction_only_writes_the_row():
+    fa = _fa()
+    k_full = torch.zeros((2, 3, 9, 64), dtype=torch.bfloat16, device="cuda")
+    v_full = torch.ones_like(k_full)
+    kn = torch.randn((2, 3, 64), device="cuda").to(torch.bfloat16)
+    vn = torch.randn((2, 3, 64), device="cuda").to(torch.bfloat16)
+    fa.fa_append(kn, vn, k_full, v_full, 5, False)
+    torch.cuda.synchronize()
+    assert torch.equal(k_full[:, :, 5], kn) and torch.equal(v_full[:, :, 5], vn)
+    assert not k_full[:, :, :5].any() and not k_full[:, :, 6:].any()
+    assert (v_full[:, :, :5] == 1).all() and (v_full[:, :, 6:] == 1).all()
