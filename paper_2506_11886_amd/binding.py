@@ -28,7 +28,7 @@ def library_path() -> str:
 def _load(path: str = _LIB_PATH):
     if not os.path.exists(path):
         raise ImportError(
-            f"{path} is missing: build it with `python -m paper_2506_11886_amd.build` "
+            f"{path} is missing: build it with `python paper_2506_11886_amd/build.py` "
             "(there is no fallback implementation)")
     lib = ctypes.CDLL(path)
     c = ctypes
