@@ -44,7 +44,7 @@ constexpr int kTJ = 64;            // tokens per tile (rows of the E table)
 constexpr int kRB = kTJ / 16;      // 16-row blocks per tile
 constexpr int kXN = kTJ / 32;      // 32-token contraction steps per tile on the V side
 constexpr int kMaxKT = 4;          // tiles per wave step
-constexpr int kWChunk = 64;        // full-width rows per workgroup
+constexpr int kWChunk = 256;       // full-width rows per workgroup
 constexpr int kMaxDvTiles = 8;     // kept V dims handled per middle row: 8 * 16
 constexpr int kMaxPartials = 1024; // partial records per query head
 constexpr unsigned kMaxDynLds = 160 * 1024 - 4096;   // dynamic LDS a workgroup may ask for
@@ -340,58 +340,57 @@ __global__ __launch_bounds__(kBlock) void decode_prepare(DecodeParams p) {
 // ---------------------------------------------------------------------------
 // 2a. full-width sink/window rows: plain single-query attention partial
 // ---------------------------------------------------------------------------
+// A workgroup takes 256 rows, 64 per wave.  A wave multiplies its rows with q on the matrix
+// cores (A = K rows, B = q, one column per head), normalises its 64 scores per head in registers
+// and accumulates sum_j p_j V[j,:] on the vector unit, each lane owning 8 dims of every nrg-th
+// row; the per-lane partial sums of all waves meet once in LDS.
+constexpr int kWRows = 64;      // rows per wave
+constexpr int kWBatch = 8;      // V rows a lane has in flight
+
 template <typename T>
 __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigned char* smem) {
   const int s = blockIdx.x - p.Sm, bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
   const int G = p.G, D = p.D;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int q4 = lane >> 4, r16 = lane & 15;
   const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
-  const int j0 = s * kWChunk, n = min(kWChunk, p.W - j0);
+  const int jw = s * kWChunk + wave * kWRows;          // first row of this wave
+  const int nw = max(0, min(kWRows, p.W - jw));        // its valid rows (0: the wave only joins the barriers)
+  const int jlast = p.W - 1;
 
-  // LDS carve-up
-  T* qf = reinterpret_cast<T*>(smem);                                             // [16][D]
-  float* sc = reinterpret_cast<float*>(smem + 16 * FA_MAX_HEAD_DIM * sizeof(T));  // [64][16]
-  float* red = sc + kWChunk * kMaxG;                                              // [slices*4][D]
-  __shared__ float mx[kMaxG], lsum[kMaxG];
+  // LDS carve-up: q [16][D] | p tiles [4][64][16] | partial sums [parts][4][D]
+  T* qf = reinterpret_cast<T*>(smem);
+  float* pw = reinterpret_cast<float*>(smem + 16 * FA_MAX_HEAD_DIM * sizeof(T)) + wave * kWRows * kMaxG;
+  float* red = reinterpret_cast<float*>(smem + 16 * FA_MAX_HEAD_DIM * sizeof(T)) + kWaves * kWRows * kMaxG;
+  __shared__ float wm[kWaves][kMaxG], wl[kWaves][kMaxG];
 
   FA_STAMP(0);
-  // ---- all global operands first ---------------------------------------------------
+  // ---- global operands: q of the group, this wave's K rows (rows past the end re-read the last) --
   constexpr int kQLoads = kMaxG * FA_MAX_HEAD_DIM / 8 / kBlock;
   const T* q = static_cast<const T*>(p.q) + hq0 * D;
   const int nq8 = G * D / 8;
   Frag<T> qv[kQLoads];
 #pragma unroll
   for (int i = 0; i < kQLoads; ++i) qv[i].load(q + 8 * min(tid + i * kBlock, nq8 - 1));
-  // K rows of this wave (16 rows), 32 dims per fragment
-  constexpr int kKF = FA_MAX_HEAD_DIM / 32;
-  const int tok = wave * 16 + r16;
-  const T* krow = static_cast<const T*>(p.k_full) + bh * p.full_stride +
-                  static_cast<int64_t>(j0 + min(tok, n - 1)) * D;
-  Frag<T> ka[kKF];
+  const int kcn = (D + 31) / 32;                        // 32-dim steps (the last may be partial)
+  const T* kbase = static_cast<const T*>(p.k_full) + bh * p.full_stride;
+  const T* vbase = static_cast<const T*>(p.v_full) + bh * p.full_stride;
+  const T* krow[kRB];
 #pragma unroll
-  for (int cc = 0; cc < kKF; ++cc)
-    if (cc * 32 < D) ka[cc].load(krow + min(cc * 32 + 8 * q4, D - 8));
-  // V rows: thread owns 8 dims of every nts-th row
-  const int nch = D / 8;
-  const int nts = kBlock / nch;
-  const int dc = tid % nch, ts = tid / nch;
-  const bool active = ts < nts;
-  constexpr int kMaxRows = 8;   // ceil(64 / nts) <= 8 for D <= 256
-  Frag<T> vf[kMaxRows];
-  {
-    const T* vb = static_cast<const T*>(p.v_full) + bh * p.full_stride +
-                  static_cast<int64_t>(j0) * D + dc * 8;
+  for (int rb = 0; rb < kRB; ++rb) krow[rb] = kbase + static_cast<int64_t>(min(jw + 16 * rb + r16, jlast)) * D;
+  Frag<T> ka[4][kRB];                                   // dims [0, 128)
 #pragma unroll
-    for (int r = 0; r < kMaxRows; ++r) {
-      const int j = ts + r * nts;
-      if (r * nts < kWChunk) vf[r].load(vb + static_cast<int64_t>(min(j, n - 1)) * D);
-    }
-  }
+  for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) ka[cc][rb].load(krow[rb] + min(cc * 32 + 8 * q4, D - 8));
 
   FA_STAMP(1);
   // ---- q into LDS (rows >= G zero) ---------------------------------------------------
-  for (int it = tid; it < (16 - G) * D; it += kBlock) qf[G * D + it] = T{};
+  {
+    const int nz = (16 - G) * D * static_cast<int>(sizeof(T)) / 16;
+    for (int it = tid; it < nz; it += kBlock) reinterpret_cast<u32x4*>(qf + G * D)[it] = u32x4{0u, 0u, 0u, 0u};
+  }
 #pragma unroll
   for (int i = 0; i < kQLoads; ++i) {
     const int v8 = tid + i * kBlock;
@@ -400,96 +399,148 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
   __syncthreads();
 
   FA_STAMP(2);
-  // scores of 16 rows per wave: A = K rows, B = q (one column per head)
-  {
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  // ---- scores of the wave's 64 rows: lane (head r16, q4) gets rows 16 rb + 4 q4 + v ----------------
+  f32x4 sacc[kRB];
 #pragma unroll
-    for (int cc = 0; cc < kKF; ++cc) {
-      if (cc * 32 < D) {
-        const int d0 = cc * 32 + 8 * q4;
-        Frag<T> a = ka[cc], bq;
-        if (d0 < D) {
-          bq.load(qf + r16 * D + d0);
-        } else {
-          bq.zero();
-          a.zero();
-        }
-        mma_k32(acc, a, bq);
-      }
-    }
-    // lane holds column h = r16, rows 4*q4 + v
-    if (r16 < G) {
+  for (int rb = 0; rb < kRB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  auto score_steps = [&](int c0) {   // four 32-dim steps from step c0 on, operands in ka
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int t = wave * 16 + 4 * q4 + v;
-        sc[t * kMaxG + r16] = (t < n) ? acc[v] * p.scale : -INFINITY;
-      }
+    for (int cc = 0; cc < 4; ++cc) {
+      const int dd = (c0 + cc) * 32 + 8 * q4;
+      Frag<T> bq;
+      bq.load(qf + r16 * D + min(dd, D - 8));
+      if (dd >= D) bq.zero();            // a step past the head dim multiplies re-read dims by zero
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], ka[cc][rb], bq);
     }
+  };
+  score_steps(0);
+  if (kcn > 4) {                         // head dims 136 .. 256
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb) ka[cc][rb].load(krow[rb] + min((4 + cc) * 32 + 8 * q4, D - 8));
+    score_steps(4);
   }
-  __syncthreads();
+  // V rows of this lane: 8 dims (dc) of rows rg, rg + nrg, ...; the first batch travels during the softmax
+  const int nch = D / 8, nrg = max(64 / nch, 1);
+  const bool lane_on = lane < nch * nrg;
+  const int dc = lane % nch, rg = min(lane / nch, nrg - 1);
+  const int vrows = (kWRows + nrg - 1) / nrg;
+  const T* vlane = vbase + dc * 8;
+  Frag<T> vf0[kWBatch];
+#pragma unroll
+  for (int i = 0; i < kWBatch; ++i) vf0[i].load(vlane + static_cast<int64_t>(min(jw + rg + i * nrg, jlast)) * D);
+
   FA_STAMP(3);
-  if (wave == 0) {
-    for (int h = 0; h < G; ++h) {
-      const float sv = sc[lane * kMaxG + h];
-      const float m = wave_max(sv);
-      const float e = __expf(sv - m);   // rows >= n hold -inf -> 0
-      const float l = wave_sum(e);
-      sc[lane * kMaxG + h] = e;
-      if (lane == 0) {
-        mx[h] = m;
-        lsum[h] = l;
-      }
+  // ---- softmax over the wave's rows, per head -----------------------------------------------------
+  float m_w = -INFINITY;
+#pragma unroll
+  for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int r = 16 * rb + 4 * q4 + v;
+      const float sv = (r < nw && r16 < G) ? sacc[rb][v] * p.scale : -INFINITY;
+      sacc[rb][v] = sv;
+      m_w = fmaxf(m_w, sv);
     }
+  m_w = fmaxf(m_w, __shfl_xor(m_w, 16, kWave));
+  m_w = fmaxf(m_w, __shfl_xor(m_w, 32, kWave));
+  const float m_ref = (m_w == -INFINITY) ? 0.0f : m_w;
+  float l_w = 0.0f;
+#pragma unroll
+  for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float e = __expf(sacc[rb][v] - m_ref);   // masked rows hold -inf -> 0
+      l_w += e;
+      pw[(16 * rb + 4 * q4 + v) * kMaxG + r16] = e;
+    }
+  l_w += __shfl_xor(l_w, 16, kWave);
+  l_w += __shfl_xor(l_w, 32, kWave);
+  if (q4 == 0) {
+    wm[wave][r16] = m_w;
+    wl[wave][r16] = l_w;
   }
-  __syncthreads();
+  __syncthreads();   // statistics of all waves (and this wave's p tile) are visible
+  FA_STAMP(4);
 
   // record of head h: [max, sum, -, -, acc[D]]
   float* part = p.part_w + (hq0 * p.Sw + s) * p.recw;
   const size_t part_h = static_cast<size_t>(p.Sw) * p.recw;
-  if (tid < G) {
-    part[tid * part_h + 0] = mx[tid];
-    part[tid * part_h + 1] = lsum[tid];
-  }
-
-  FA_STAMP(4);
-  // sum_j p_j V[j,:]
   for (int hg = 0; hg < G; hg += 4) {
     float acc[4][8];
 #pragma unroll
     for (int hh = 0; hh < 4; ++hh)
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
-    if (active) {
+    // factors that bring every wave to the workgroup's maximum
+    float fw[4];
 #pragma unroll
-      for (int r = 0; r < kMaxRows; ++r) {
-        const int j = ts + r * nts;
-        if (r * nts < kWChunk && j < n) {
-          float x[8];
-          unpack8(vf[r], x);
+    for (int hh = 0; hh < 4; ++hh) {
+      const int h = min(hg + hh, kMaxG - 1);
+      float ms = wm[0][h];
 #pragma unroll
-          for (int hh = 0; hh < 4; ++hh) {
-            const float pj = (hg + hh < G) ? sc[j * kMaxG + hg + hh] : 0.0f;
+      for (int w = 1; w < kWaves; ++w) ms = fmaxf(ms, wm[w][h]);
+      const float mine = wm[wave][h];
+      fw[hh] = (mine == -INFINITY) ? 0.0f : __expf(mine - ms);
+      if (tid == hh && hg + hh < G) {
+        float l = 0.0f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[hh][e] += pj * x[e];
-          }
-        }
+        for (int w = 0; w < kWaves; ++w) l += (wm[w][h] == -INFINITY) ? 0.0f : wl[w][h] * __expf(wm[w][h] - ms);
+        part[(hg + hh) * part_h + 0] = ms;
+        part[(hg + hh) * part_h + 1] = l;
       }
     }
-    __syncthreads();   // previous head group's reduction is finished with `red`
-    if (active) {
+    // sum_j p_j V[j,:] over this lane's rows
+    auto accumulate = [&](const Frag<T> (&vf)[kWBatch], int i0) {
 #pragma unroll
-      for (int hh = 0; hh < 4; ++hh)
+      for (int i = 0; i < kWBatch; ++i) {
+        const int r = rg + (i0 + i) * nrg;
+        if (i0 + i < vrows && r < nw && lane_on) {
+          const f32x4 p4 = *reinterpret_cast<const f32x4*>(pw + r * kMaxG + hg);
+          float x[8];
+          unpack8(vf[i], x);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) red[(ts * 4 + hh) * D + dc * 8 + e] = acc[hh][e];
+          for (int hh = 0; hh < 4; ++hh)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[hh][e] += p4[hh] * x[e];
+        }
+        if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // keep the p reads next to their rows
+      }
+    };
+    if (hg == 0) {
+      accumulate(vf0, 0);
+    } else {
+      Frag<T> vf[kWBatch];
+#pragma unroll
+      for (int i = 0; i < kWBatch; ++i) vf[i].load(vlane + static_cast<int64_t>(min(jw + rg + i * nrg, jlast)) * D);
+      accumulate(vf, 0);
+    }
+    for (int i0 = kWBatch; i0 < vrows; i0 += kWBatch) {   // head dims above 128 only
+      Frag<T> vf[kWBatch];
+#pragma unroll
+      for (int i = 0; i < kWBatch; ++i) vf[i].load(vlane + static_cast<int64_t>(min(jw + rg + (i0 + i) * nrg, jlast)) * D);
+      accumulate(vf, i0);
+    }
+    // park the scaled partial sums: red[wave * nrg + rg][hh][D]
+    if (hg > 0) __syncthreads();   // the previous head group's sums have been read
+    if (lane_on) {
+      float* dst = red + ((wave * nrg + rg) * 4) * D + dc * 8;
+#pragma unroll
+      for (int hh = 0; hh < 4; ++hh) {
+        *reinterpret_cast<f32x4*>(dst + hh * D) = f32x4{fw[hh] * acc[hh][0], fw[hh] * acc[hh][1], fw[hh] * acc[hh][2], fw[hh] * acc[hh][3]};
+        *reinterpret_cast<f32x4*>(dst + hh * D + 4) = f32x4{fw[hh] * acc[hh][4], fw[hh] * acc[hh][5], fw[hh] * acc[hh][6], fw[hh] * acc[hh][7]};
+      }
     }
     __syncthreads();
-    for (int it = tid; it < 4 * D; it += kBlock) {
-      const int hh = it / D, d = it % D;
+    const int nparts = kWaves * nrg;
+    for (int it = tid; it < D; it += kBlock) {   // 4 heads x D dims, four floats per item
+      const int hh = (4 * it) / D, d = (4 * it) % D;
       if (hg + hh < G) {
-        float v = 0.0f;
-#pragma unroll 8
-        for (int k = 0; k < nts; ++k) v += red[(k * 4 + hh) * D + d];
-        part[(hg + hh) * part_h + 4 + d] = v;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < nparts; ++k) v += *reinterpret_cast<const f32x4*>(red + (k * 4 + hh) * D + d);
+        *reinterpret_cast<f32x4*>(part + (hg + hh) * part_h + 4 + d) = v;
       }
     }
   }
@@ -1284,16 +1335,20 @@ static int series_chunks_per_wave(int M) {   // compiled series lengths: 128, 25
   return 0;
 }
 
-// steps per chunk when the caller leaves the split to the library: all workgroups of the launch
-// (middle chunks and full-row chunks) should be resident at once, two per compute unit when two
-// fit (short series), else one
+// Steps per chunk when the caller leaves the split to the library.  With few (sequence, head)
+// pairs the chunks are sized so that all workgroups of the launch (middle chunks and full-row
+// chunks) are resident at once, two per compute unit when two fit (short series), else one.
+// With many pairs that would make long chunks and a ragged last round: short chunks balance
+// better (measured: 3-5 steps per chunk is the flat optimum at two workgroups per unit).
 static int default_steps_per_chunk(int B, int Hkv, int N, int step, int cw, int Sw) {
   const long total_steps = static_cast<long>(B) * Hkv * ((N + step - 1) / step);
-  long target = (cw <= 2 ? 512 : 256) - static_cast<long>(B) * Hkv * Sw;
-  if (target < 64) target = 64;
+  const long slots = cw <= 2 ? 512 : 256;
+  long target = slots - static_cast<long>(B) * Hkv * Sw;
+  if (target < 3 * slots / 4) target = 3 * slots / 4;
   long spc = (total_steps + target - 1) / target;
+  const long cap = cw <= 2 ? 5 : 16;
+  if (spc > cap) spc = cap;
   if (spc < 1) spc = 1;
-  if (spc > 32) spc = 32;
   return static_cast<int>(spc);
 }
 
@@ -1329,7 +1384,7 @@ static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, 
   const unsigned tab = redb > kXchgBytes ? redb : kXchgBytes;
   pl.lds_tab = (tab + 255u) & ~255u;
   const unsigned mid = pl.lds_tab + G * (pl.Mint + 32) * 4 + G * Dkq * ts;
-  const unsigned wpath = 16 * FA_MAX_HEAD_DIM * ts + kWChunk * kMaxG * 4 + kBlock * 8 * 4 * 4;
+  const unsigned wpath = 16 * FA_MAX_HEAD_DIM * ts + kWChunk * kMaxG * 4 + kWaves * 512 * 4 * 4;   // q, p tiles, partial sums
   const unsigned t = mid > wpath ? mid : wpath;
   pl.lds_total = (t + 255u) & ~255u;
   if (pl.lds_total > kMaxDynLds) return false;
