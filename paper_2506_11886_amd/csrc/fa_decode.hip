@@ -256,30 +256,33 @@ __device__ __forceinline__ int dim_rank(const uint64_t* bal, int d) {
 // ---------------------------------------------------------------------------
 // 1. g = diag(w) C_k q_c, written in series order: slot s <-> basis function s+1
 // ---------------------------------------------------------------------------
-constexpr int kPrepRows = 8;                       // basis rows per workgroup
-constexpr int kPrepLoads = kPrepRows * FA_MAX_HEAD_DIM / kBlock;   // C_k loads per thread (worst case)
+constexpr int kPrepLd = FA_MAX_HEAD_DIM + 4;       // LDS pitch of a C_k row (floats)
 
-template <typename T>
+// kPrepRows: basis rows per workgroup (8 when the launch would otherwise not fill the chip, else 32)
+template <typename T, int kPrepRows>
 __global__ __launch_bounds__(kBlock) void decode_prepare(DecodeParams p) {
   __shared__ float qc[kMaxG * FA_MAX_HEAD_DIM];            // [G][Dkc] query at the compressed dims
-  __shared__ float crow[kPrepRows * (FA_MAX_HEAD_DIM + 1)];
+  __shared__ __attribute__((aligned(16))) float crow[kPrepRows * kPrepLd];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
   const int m0 = blockIdx.x * kPrepRows;
-  const int Dkc = p.Dkc, D = p.D, G = p.G, Gp = p.Gp;
-  const int ld = Dkc + 1;
+  const int Dkc = p.Dkc, D = p.D, G = p.G;
 
-  // all global operands first: C_k rows, the mask row, q of the group
+  // all global operands first (clamped, never predicated): C_k rows, the mask row, q of the group
   const float* ck = p.ck + static_cast<size_t>(bh) * p.M * Dkc;
-  const int nck = kPrepRows * Dkc;
-  float cval[kPrepLoads];
+  const bool vec4 = (Dkc & 3) == 0 && Dkc > 0;
+  constexpr int kV4 = (kPrepRows * FA_MAX_HEAD_DIM / 4 + kBlock - 1) / kBlock;   // float4 per thread, worst case
+  const int c4n = vec4 ? Dkc / 4 : 1;
+  const int nv4 = vec4 ? kPrepRows * c4n : 0;
+  f32x4 cv4[kV4];
+  if (vec4) {
 #pragma unroll
-  for (int i = 0; i < kPrepLoads; ++i) {
-    const int it = min(tid + i * kBlock, max(nck - 1, 0));
-    const int r = it / max(Dkc, 1), col = it % max(Dkc, 1);
-    const int m = min(m0 + r, p.M - 1);
-    cval[i] = (Dkc > 0) ? ck[static_cast<size_t>(m) * Dkc + col] : 0.0f;
+    for (int i = 0; i < kV4; ++i) {
+      const int it = min(tid + i * kBlock, nv4 - 1);
+      const int r = it / c4n, c4 = it - r * c4n;
+      cv4[i] = *reinterpret_cast<const f32x4*>(ck + static_cast<size_t>(min(m0 + r, p.M - 1)) * Dkc + 4 * c4);
+    }
   }
   uint64_t kbal[4];
   mask_ballots(p.kmask + static_cast<size_t>(bh) * D, D, lane, kbal);
@@ -291,12 +294,19 @@ __global__ __launch_bounds__(kBlock) void decode_prepare(DecodeParams p) {
 #pragma unroll
   for (int i = 0; i < kQElems; ++i) qe[i] = q[min(tid + i * kBlock, nqe - 1)];
 
+  if (vec4) {
 #pragma unroll
-  for (int i = 0; i < kPrepLoads; ++i) {
-    const int it = tid + i * kBlock;
-    if (it < nck) {
-      const int r = it / Dkc, col = it % Dkc;
-      crow[r * ld + col] = (m0 + r < p.M) ? cval[i] : 0.0f;
+    for (int i = 0; i < kV4; ++i) {
+      const int it = tid + i * kBlock;
+      if (it < nv4) {
+        const int r = it / c4n, c4 = it - r * c4n;
+        *reinterpret_cast<f32x4*>(crow + r * kPrepLd + 4 * c4) = cv4[i];
+      }
+    }
+  } else {   // odd column counts: element by element
+    for (int it = tid; it < kPrepRows * Dkc; it += kBlock) {
+      const int r = it / Dkc, col = it - r * Dkc;
+      crow[r * kPrepLd + col] = ck[static_cast<size_t>(min(m0 + r, p.M - 1)) * Dkc + col];
     }
   }
   // q splits into its compressed dims (fp32, for the products below) and its kept dims (packed and
@@ -320,20 +330,25 @@ __global__ __launch_bounds__(kBlock) void decode_prepare(DecodeParams p) {
   }
   __syncthreads();
 
-  // (row, head) dot products; nseg consecutive lanes share one of them
-  const int nseg = kBlock / (kPrepRows * Gp);   // power of two, >= 2
-  const int seg = tid % nseg, item = tid / nseg;
-  const int r = item % kPrepRows, h = item / kPrepRows;
-  float acc = 0.0f;
-  if (h < G)
-    for (int i = seg; i < Dkc; i += nseg) acc += crow[r * ld + i] * qc[h * Dkc + i];
-  for (int o = nseg >> 1; o > 0; o >>= 1) acc += __shfl_xor(acc, o, kWave);
-  const int m = m0 + r;
-  if (seg == 0 && h < G && m <= p.Mint) {
-    const float g = (m < p.M) ? acc * basis_weight((m + 1) / 2, p.T) : 0.0f;
-    const size_t hq = static_cast<size_t>(b) * p.Hq + hkv * G + h;
-    if (m == 0) p.g0[hq] = g;
-    else p.gs[hq * p.Mint + (m - 1)] = g;
+  // (row, head) dot products, nseg lanes each (a power of two that fills the workgroup)
+  int nseg = 1;
+  while (nseg < 64 && kPrepRows * G * nseg * 2 <= kBlock) nseg *= 2;
+  for (int item0 = 0; item0 < kPrepRows * G; item0 += kBlock / nseg) {
+    const int item = item0 + tid / nseg, seg = tid % nseg;
+    const int r = item % kPrepRows, h = item / kPrepRows;
+    float acc = 0.0f;
+    if (h < G) {
+      const float* cr = crow + r * kPrepLd;
+      const float* qh = qc + h * Dkc;
+      for (int i = seg; i < Dkc; i += nseg) acc += cr[i] * qh[i];
+    }
+    for (int o = nseg >> 1; o > 0; o >>= 1) acc += __shfl_xor(acc, o, kWave);
+    const int m = m0 + r;
+    if (seg == 0 && h < G && m <= p.Mint) {
+      const float g = (m < p.M) ? acc * basis_weight((m + 1) / 2, p.T) : 0.0f;
+      if (m == 0) p.g0[hq0 + h] = g;
+      else p.gs[(hq0 + h) * p.Mint + (m - 1)] = g;
+    }
   }
 }
 
@@ -1442,8 +1457,13 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
   const int BH = p.B * p.Hkv;
   if (ev) (void)hipEventRecord(ev[0], st);
   if (p.Sm > 0) {
-    dim3 g1((p.Mint + 1 + kPrepRows - 1) / kPrepRows, BH);
-    hipLaunchKernelGGL(decode_prepare<T>, g1, dim3(kBlock), 0, st, p);
+    if (static_cast<long>(BH) * ((p.Mint + 32) / 32) >= 512) {
+      dim3 g1((p.Mint + 32) / 32, BH);
+      hipLaunchKernelGGL((decode_prepare<T, 32>), g1, dim3(kBlock), 0, st, p);
+    } else {
+      dim3 g1((p.Mint + 8) / 8, BH);
+      hipLaunchKernelGGL((decode_prepare<T, 8>), g1, dim3(kBlock), 0, st, p);
+    }
   }
   if (ev) (void)hipEventRecord(ev[1], st);
   int rc;
