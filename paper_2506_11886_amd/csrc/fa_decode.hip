@@ -1172,8 +1172,9 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
   f32x4 rv[kUr];
   if (do_cv) {
 #pragma unroll
-    for (int u = 0; u < kUr; ++u)   // clamped, not predicated: a predicated load is waited for at once
-      rv[u] = *reinterpret_cast<const f32x4*>(pr + static_cast<size_t>(min(gr + u * ngr, Sm - 1)) * recm);
+    for (int u = 0; u < kUr; ++u)   // lanes are clamped, never predicated (a predicated load is waited for
+      if (u * ngr < Sm)             // at once); rounds no lane needs are skipped by the whole workgroup
+        rv[u] = *reinterpret_cast<const f32x4*>(pr + static_cast<size_t>(min(gr + u * ngr, Sm - 1)) * recm);
   }
   FA_FSTAMP(11);
   // (3) this slice's columns of the full-row records: thread (4 columns, group of records)
@@ -1186,7 +1187,8 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
   if (Sw > 0) {
 #pragma unroll
     for (int u = 0; u < kUw; ++u)
-      wv[u] = *reinterpret_cast<const f32x4*>(pw + static_cast<size_t>(min(gw + u * kWG, Sw - 1)) * recw + 4 + dw);
+      if (u * kWG < Sw)
+        wv[u] = *reinterpret_cast<const f32x4*>(pw + static_cast<size_t>(min(gw + u * kWG, Sw - 1)) * recw + 4 + dw);
   }
   FA_FSTAMP(12);
   // ranks of this slice's dims (needs only the mask)
@@ -1199,19 +1201,21 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
   const bool is_c = dme < D && rk < 0, is_k = dme < D && rk >= 0;
   FA_FSTAMP(13);
   // (4) compressed dim: its column of C_v, rows cg, cg + kCG, ...; kept dim: its accumulator column
-  constexpr int kUc = 32, kUk = 6;
+  constexpr int kUc = 64, kUk = 6;
   const float* cvc = p.cv + static_cast<size_t>(bh) * M * Dvc + (is_c ? -rk - 1 : 0);
   float cvv[kUc];
   if (do_cv) {
 #pragma unroll
-    for (int u = 0; u < kUc; ++u) cvv[u] = cvc[static_cast<size_t>(min(cg + u * kCG, M - 1)) * Dvc];
+    for (int u = 0; u < kUc; ++u)
+      if (u * kCG < M) cvv[u] = cvc[static_cast<size_t>(min(cg + u * kCG, M - 1)) * Dvc];
   }
   FA_FSTAMP(14);
   const float* pk = pm + 4 + (is_k ? rk : 0);
   float kv[kUk];
   if (Sm > 0) {
 #pragma unroll
-    for (int u = 0; u < kUk; ++u) kv[u] = pk[static_cast<size_t>(min(cg + u * kCG, Sm - 1)) * recm];
+    for (int u = 0; u < kUk; ++u)
+      if (u * kCG < Sm) kv[u] = pk[static_cast<size_t>(min(cg + u * kCG, Sm - 1)) * recm];
   }
 
   FA_FSTAMP(1);
