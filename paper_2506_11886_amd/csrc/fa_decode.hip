@@ -53,6 +53,7 @@ constexpr int kFinBlock = 256;     // threads of decode_finish
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2d __attribute__((ext_vector_type(2)));
 
 // Developer aid (compiled out unless FA_TRACE is defined): per-wave cycle stamps
 // at phase boundaries, written behind the partial records of the workspace.
@@ -572,10 +573,12 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
 //     operands) are built once and stay in registers;
 //   * the kept dims by rows: wave w multiplies a quarter of the step's K^mu row
 //     blocks and a quarter of its V^mu token blocks.
-// The partial scores are summed across the waves through LDS (the only barrier
-// of a step); every wave then runs the same online softmax on the full scores.
+// The partial scores meet in LDS; wave w then sums and exponentiates the four
+// columns 4 w .. 4 w + 3 (one token tile when the group has four heads), keeps
+// their running maximum and sum, and hands the probabilities back through LDS
+// as ready-made MFMA operands: two barriers per step, no work done twice.
 constexpr int kVU = 2;                                        // V^mu token blocks per wave and step
-constexpr unsigned kXchgBytes = 2 * kWaves * kRB * 64 * 16;   // double-buffered score exchange
+constexpr unsigned kXchgBytes = 32 * 1024;   // score exchange, probability tiles, statistics; E transpose tiles
 
 // cos / sin of 2 pi n u / T for a table entry (n u < 2^24): exact integer phase
 template <typename T>
@@ -626,7 +629,13 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
   const int NV = KT >= 2 ? KT / 2 : 1;               // V^mu token blocks of this wave per step
 
   // ---- LDS carve-up -------------------------------------------------------
-  f32x4* xs = reinterpret_cast<f32x4*>(smem);                   // [2][kWaves][kRB][64]
+  f32x4* xs = reinterpret_cast<f32x4*>(smem);                   // [kWaves][kRB][64] partial scores
+  constexpr unsigned kXsBytes = kWaves * kRB * 64 * 16;
+  ES* pse = reinterpret_cast<ES*>(smem + kXsBytes);             // [kXN][16][4][8] probabilities, series type
+  T* pte = reinterpret_cast<T*>(smem + kXsBytes + kXN * 16 * 4 * 8 * sizeof(ES));   // same, element type
+  float* alpha_s = reinterpret_cast<float*>(smem + kXsBytes + kXN * 16 * 4 * 8 * (sizeof(ES) + sizeof(T)));   // [16]
+  float* st_m = alpha_s + 16;                                   // [16] column maxima (after the loop)
+  float* st_l = st_m + 16;                                      // [16] column sums
   float* red_r = reinterpret_cast<float*>(smem);                // after the loop: [16][Mint + 4]
   const int pr = Mint + 4, po = 16 * DVT + 4;
   float* red_o = red_r + 16 * pr;                               // [kWaves][16][16 DVT + 4]
@@ -689,7 +698,11 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
 #pragma unroll
   for (int i = 0; i < kGLoads; ++i)
     gv[i] = *reinterpret_cast<const f32x4*>(p.gs + hq0 * Mint + 4 * min(tid + i * kBlock, ng4 - 1));
-  const float g0 = p.g0[hq0 + hsafe];
+  // this lane's share of the softmax: column ocol, rows 16 orb + 4 oq4 + v of the tile
+  const int ocol = 4 * wave + (lane & 3), orb = lane >> 4, oq4 = (lane >> 2) & 3;
+  const int ocol_k = ocol / Gp, ocol_h = ocol % Gp;
+  const bool olive = ocol_k < KT && ocol_h < G;
+  const float g0 = p.g0[hq0 + min(ocol_h, G - 1)];
   const int nq8 = G * Dkq / 8;
   Frag<T> qv[kQLoads];
   if (nq8 > 0) {
@@ -822,7 +835,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
   int last_base = c0;                       // origin of the latest step
   const bool quad_share = Gp >= 4;          // the 4 lanes of a quad then share (tile, q4)
   bool first = true;
-  int buf = 0;
 
   auto do_step = [&](Frag<T> (&kf)[kMaxKT], Frag<T> (&vf)[kVU][kVR], int base) {
     const bool tail = base + step > c1;
@@ -898,37 +910,33 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
     }
 
     if (traced) FA_STAMP(5);
-    // -- (c) sum the partial scores of the four waves (fixed order: every wave gets the same bits)
+    // -- (c) the partial scores of the four waves meet; this wave sums its four columns --------
     {
-      f32x4* xw = xs + ((buf * kWaves + wave) * kRB) * 64 + lane;
+      f32x4* xw = xs + (wave * kRB) * 64 + lane;
 #pragma unroll
       for (int rb = 0; rb < kRB; ++rb) xw[rb * 64] = sacc[rb];
-      if (traced) FA_STAMP(6);
-      __syncthreads();
-      if (traced) FA_STAMP(7);
-      const f32x4* xr = xs + (buf * kWaves * kRB) * 64 + lane;
-#pragma unroll
-      for (int rb = 0; rb < kRB; ++rb)
-        sacc[rb] = ((xr[(0 * kRB + rb) * 64] + xr[(1 * kRB + rb) * 64]) + xr[(2 * kRB + rb) * 64]) +
-                   xr[(3 * kRB + rb) * 64];
-      buf ^= 1;   // two buffers: a wave can be at most one barrier ahead of the slowest reader
     }
-
+    if (traced) FA_STAMP(6);
+    __syncthreads();
+    if (traced) FA_STAMP(7);
+    f32x4 sv;
+    {
+      const f32x4* xr = xs + orb * 64 + oq4 * 16 + ocol;
+      sv = ((xr[0 * kRB * 64] + xr[1 * kRB * 64]) + xr[2 * kRB * 64]) + xr[3 * kRB * 64];
+    }
     if (traced) FA_STAMP(8);
-    // -- (d) online softmax per column -----------------------------------------------
-    // lane (column, q4) holds rows u = 32x + 8*q4 + 4y + v  (rb = 2x + y)
-    float pv[kRB][4];
+    // -- (d) online softmax of the own columns: lane holds rows u = 32x + 8 oq4 + 4y + v (orb = 2x + y)
+    float pv[4];
     float m_tile = -INFINITY;
 #pragma unroll
-    for (int rb = 0; rb < kRB; ++rb)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int u = 32 * (rb >> 1) + 8 * q4 + 4 * (rb & 1) + v;
-        const int j = base + col_k * kTJ + u;
-        const float s = (col_live && j < c1) ? (sacc[rb][v] + g0) * p.scale : -INFINITY;
-        pv[rb][v] = s;
-        m_tile = fmaxf(m_tile, s);
-      }
+    for (int v = 0; v < 4; ++v) {
+      const int u = 32 * (orb >> 1) + 8 * oq4 + 4 * (orb & 1) + v;
+      const int j = base + ocol_k * kTJ + u;
+      const float sc = (olive && j < c1) ? (sv[v] + g0) * p.scale : -INFINITY;
+      pv[v] = sc;
+      m_tile = fmaxf(m_tile, sc);
+    }
+    m_tile = row_stride_max(m_tile, 4);                      // the 16 lanes of a column are 4 apart
     m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16, kWave));
     m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, kWave));
     const float m_new = fmaxf(m_run, m_tile);
@@ -936,22 +944,34 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
     const float alpha = __expf(m_run - m_ref);   // m_run = -inf -> 0
     float l_add = 0.0f;
 #pragma unroll
-    for (int rb = 0; rb < kRB; ++rb)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        pv[rb][v] = __expf(pv[rb][v] - m_ref);
-        l_add += pv[rb][v];
-      }
+    for (int v = 0; v < 4; ++v) {
+      pv[v] = __expf(pv[v] - m_ref);
+      l_add += pv[v];
+    }
     l_run = l_run * alpha + l_add;
     m_run = m_new;
-
+    // probabilities back as A operands: reader lane (column c, q4) takes rows 32x + 8 q4 + e, e < 8
+    {
+      const int slot = (((orb >> 1) * 16 + ocol) * 4 + oq4) * 8 + 4 * (orb & 1);
+      if constexpr (sizeof(ES) == 4) {
+        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(pse) + slot) = f32x4{pv[0], pv[1], pv[2], pv[3]};
+      } else {
+        u32x2d w;
+        w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[0], pv[1]}, f16x2));
+        w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[2], pv[3]}, f16x2));
+        *reinterpret_cast<u32x2d*>(reinterpret_cast<uint16_t*>(pse) + slot) = w;
+        w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[0], pv[1]}, bf16x2));
+        w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[2], pv[3]}, bf16x2));
+        *reinterpret_cast<u32x2d*>(reinterpret_cast<uint16_t*>(pte) + slot) = w;
+      }
+      if (lane < 4) alpha_s[ocol] = alpha;
+    }
+    __syncthreads();
     if (traced) FA_STAMP(9);
     // -- (e) bring the accumulators into this step's frame --------------------------------
     if (!first) {
-      // accumulator rows are S columns 4*q4 + v: fetch their rescale factors
-      float al[4];
-#pragma unroll
-      for (int v = 0; v < 4; ++v) al[v] = __shfl(alpha, 4 * q4 + v, kWave);
+      // accumulator rows are S columns 4*q4 + v
+      const f32x4 al = *reinterpret_cast<const f32x4*>(alpha_s + 4 * q4);
 #pragma unroll
       for (int t = 0; t < DVTM; ++t)
 #pragma unroll
@@ -973,12 +993,10 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
     Frag<T> pt[kXN];
 #pragma unroll
     for (int x = 0; x < kXN; ++x) {
-      float pe[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) pe[e] = pv[2 * x + (e >> 2)][e & 3];
       Frag<ES> ps;
-      pack8(ps, pe);
-      pack8(pt[x], pe);
+      ps.load(pse + ((x * 16 + r16) * 4 + q4) * 8);
+      if constexpr (sizeof(ES) == 4) pt[x].load(reinterpret_cast<const T*>(pse) + ((x * 16 + r16) * 4 + q4) * 8);
+      else pt[x].load(pte + ((x * 16 + r16) * 4 + q4) * 8);
 #pragma unroll
       for (int i = 0; i < CW; ++i) {
         mma_k32(racc[2 * i], ps, eB[i][0][x]);
@@ -1024,13 +1042,21 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
 
   FA_STAMP(13);
   // ---- merge the tiles of a head --------------------------------------------------------------
+  // the owners publish the statistics of their columns; then every lane takes those of its S column
+  l_run = row_stride_sum(l_run, 4);
   l_run += __shfl_xor(l_run, 16, kWave);
   l_run += __shfl_xor(l_run, 32, kWave);
-  const float mc = col_live ? m_run : -INFINITY;
+  if (lane < 4) {
+    st_m[ocol] = m_run;
+    st_l[ocol] = l_run;
+  }
+  __syncthreads();
+  const float mc = col_live ? st_m[r16] : -INFINITY;
+  const float lcol = st_l[r16];
   const float mstar = row_stride_max(mc, Gp);   // the columns of one head are Gp lanes apart
   const float fc = (mc != -INFINITY) ? __expf(mc - mstar) : 0.0f;
-  const float lstar = row_stride_sum(col_live ? l_run * fc : 0.0f, Gp);
-  __syncthreads();   // every wave has read the last score exchange: the region is reused below
+  const float lstar = row_stride_sum(col_live ? lcol * fc : 0.0f, Gp);
+  __syncthreads();   // every wave is done with the exchange regions: they are reused below
 
   // every wave rotates its r' rows to the global frame, scales rows to the head's maximum and
   // parks them in LDS: red_r[row][own orders], red_o[wave][row][kept dims]
