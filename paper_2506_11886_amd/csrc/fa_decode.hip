@@ -32,6 +32,8 @@
 //   3. decode_finish  : one workgroup per query head merges the partials,
 //      applies diag(w) C_v to r and normalises.
 
+#include <cstdlib>
+
 #include "fa_common.hpp"
 #include "fa_mma.hpp"
 
@@ -104,6 +106,7 @@ struct DecodeParams {
   float* out;       // [B,Hq,D]
 #ifdef FA_TRACE
   long long* trace;
+  int trace_step;   // which step of a chunk carries the fine stamps
 #endif
 };
 
@@ -838,7 +841,11 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
 
   auto do_step = [&](Frag<T> (&kf)[kMaxKT], Frag<T> (&vf)[kVU][kVR], int base) {
     const bool tail = base + step > c1;
-    [[maybe_unused]] const bool traced = base == c0 + step || c0 + step >= c1;   // developer trace: second step
+#ifdef FA_TRACE
+    const bool traced = base == c0 + p.trace_step * step;   // developer trace: the step that carries the fine stamps
+#else
+    constexpr bool traced = false;
+#endif
     f32x4 sacc[kRB];
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -1605,6 +1612,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   p.part_w = reinterpret_cast<float*>(ws + pl.off_pw);
   p.out = out;
 #ifdef FA_TRACE
+  p.trace_step = getenv("FA_TRACE_STEP") ? atoi(getenv("FA_TRACE_STEP")) : 1;
   p.trace = reinterpret_cast<long long*>(ws + pl.off_trace);
 #endif
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
