@@ -708,10 +708,10 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
     }
   };
   auto two_slots = [&](Frag<T> (&xnext)[4], int blk) {   // block blk; xnext holds block blk + 1
+    multiply_block(blk);
+    FA_CSTAMP(3 + 4 * blk);
     if (blk + 1 < nb) scatter_block(xnext, blk + 1);
     if (write_keep) keep_out(blk);
-    FA_CSTAMP(3 + 4 * blk);
-    multiply_block(blk);
     FA_CSTAMP(4 + 4 * blk);
     __syncthreads();
     FA_CSTAMP(5 + 4 * blk);

@@ -121,4 +121,12 @@ def small_variants():
                 Dkc=91, Dvc=101, M=40, dtype="bf16"),
         replace(base, name="g2_m1", index=18, B=3, Hq=4, Hkv=2, D=64, N=130, Lw=7,
                 Dkc=8, Dvc=56, M=1, dtype="f32"),
+        replace(base, name="wide_d256", index=20, B=1, Hq=2, Hkv=1, D=256, N=700, Lw=300, Li=3,
+                Dkc=168, Dvc=200, M=24, dtype="bf16"),
+        replace(base, name="gqa16", index=21, B=1, Hq=16, Hkv=1, D=64, N=450, Lw=150,
+                Dkc=40, Dvc=32, M=32, dtype="bf16"),
+        replace(base, name="wide_d256_f32", index=22, B=1, Hq=4, Hkv=2, D=256, N=260, Lw=90,
+                Dkc=128, Dvc=192, M=16, dtype="f32"),
+        replace(base, name="m512", index=23, B=1, Hq=4, Hkv=1, D=128, N=1500, Lw=40,
+                Dkc=112, Dvc=112, M=512, dtype="bf16"),
     )
