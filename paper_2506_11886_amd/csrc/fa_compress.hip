@@ -453,6 +453,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
 constexpr int kFB = 128;            // tokens per block
 constexpr int kFP = kFB + 8;        // LDS pitch (elements) of a transposed column
 constexpr int kFK = kFB / 32;       // 32-token contraction steps per block
+constexpr int kSchedGroups = 16;    // matrix instructions per tile of a wave: one interleave group each
 
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) {   // (a.lo, b.lo)
   return __builtin_amdgcn_perm(b, a, 0x05040100u);
@@ -461,9 +462,18 @@ __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) {   // (a.hi
   return __builtin_amdgcn_perm(b, a, 0x07060302u);
 }
 
-template <int DT>
+// KM selects the block step: 0 / 1 / 2 = the straight-line step with no kept dims to write /
+// kept dims as rows / kept dims in groups of 8 tokens (at most one 128-bit vector of kept dims
+// per thread and block); -1 = the general step (any number of kept dims, or nothing to project).
+template <int DT, int KM>
 __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams p) {
   using T = bf16_t;
+  constexpr int NW = kCBlock / 64;    // 8 waves
+  constexpr int kThreads = kCBlock;
+  constexpr int MT = 4;               // 16-row basis tiles per wave
+  constexpr int CH = 2;               // column groups of DT tiles
+  constexpr int TOK = 32 / NW;        // consecutive tokens a thread loads: 4
+  constexpr int RG = NW / CH;         // row groups of 16 MT = 64 basis rows
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int16_t cpos[FA_MAX_HEAD_DIM];
 
@@ -486,16 +496,20 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   const uint32_t ks_off = kCols * kFP * 2;
 
   // ---- first X block is requested before anything else --------------------------------
-  const int ch = tid & 15, quad = tid >> 4;        // 8 dims, 4 consecutive tokens
+  // 8 dims (vector ch of a row), TOK consecutive tokens (group quad).  Sixteen consecutive lanes
+  // hold 4 vectors x 4 token groups: each token's 64 bytes still load as one segment, and the
+  // transposed writes of one instruction spread over the LDS banks (16 different columns of
+  // one token group would land 8 columns apart on the same banks)
+  const int ch = (lane & 3) | ((lane >> 4) << 2), quad = ((lane >> 2) & 3) | (wave << 2);
   const T* xthr = static_cast<const T*>(p.x) + b * p.sx_b + h * p.sx_h + ch * 8;
-  Frag<T> xra[4], xrb[4];   // even / odd blocks: two blocks are in flight
+  Frag<T> xra[TOK], xrb[TOK];   // even / odd blocks: two blocks are in flight
   // Loads are never predicated: a load under a condition is merged with the old register contents
   // right after it, i.e. waited for at once.  Blocks past the chunk re-read its last block and rows
   // past the segment its last row; both are ignored downstream.
-  auto load_x = [&](Frag<T> (&xr)[4], int blk) {
-    const int js = j0 + min(blk, nb - 1) * kFB + 4 * quad;
+  auto load_x = [&](Frag<T> (&xr)[TOK], int blk) {
+    const int js = j0 + min(blk, nb - 1) * kFB + TOK * quad;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) xr[i].load(xthr + static_cast<int64_t>(min(js + i, p.N - 1)) * p.sx_n);
+    for (int i = 0; i < TOK; ++i) xr[i].load(xthr + static_cast<int64_t>(min(js + i, p.N - 1)) * p.sx_n);
   };
   FA_CSTAMP(0);
   // the mask row first (it is waited for first), then the first two X blocks
@@ -507,13 +521,13 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
 
   // ---- per-wave constants: E fragments (A operand) and frame twiddles -------------------
   const int rows_here = 2 * min(kPairs, p.nmax - mc * kPairs);   // live basis rows of this row block
-  const int rgw = wave & 3, chw = wave >> 2;       // row group (64 basis rows), column half of this wave
+  const int rgw = wave % RG, chw = wave / RG;      // row group (16 MT basis rows), column half of this wave
   const int ndt = (p.Dc + 15) / 16 - chw * DT;     // live column tiles of this wave (may be <= 0)
-  const bool wave_live = project && rgw * 64 < rows_here && ndt > 0;
+  const bool wave_live = project && rgw * 16 * MT < rows_here && ndt > 0;
   const bool wave_dc = do_dc && rgw < ndt && rgw < DT;   // this wave sums column tile rgw of its half
 
-  Frag<T> ea[4][kFK];            // [m tile][32-token step]
-  float twc[4][2], tws[4][2];    // cos/sin(omega_n * 128) of the two pairs a lane owns in every m tile
+  Frag<T> ea[MT][kFK];            // [m tile][32-token step]
+  float twc[MT][2], tws[MT][2];    // cos/sin(omega_n * 128) of the two pairs a lane owns in every m tile
   const uint32_t ph_blk = fixed_phase(kFB, p.ph_scale);
   if (wave_live) {
     // phase of token u as a 2^-32-turn fixed-point number; times n it wraps exactly, and the
@@ -523,8 +537,8 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
 #pragma unroll
     for (int ksx = 0; ksx < kFK; ++ksx) ph_u[ksx] = fixed_phase(32 * ksx + 8 * q4, p.ph_scale);
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-      const int rho = rgw * 64 + mt * 16 + r16;               // A-operand row of this lane
+    for (int mt = 0; mt < MT; ++mt) {
+      const int rho = rgw * 16 * MT + mt * 16 + r16;               // A-operand row of this lane
       const int n = mc * kPairs + (rho >> 1) + 1;
       const bool live = n <= p.nmax;
       // one exact evaluation per 32-token step; the 8 tokens of a lane follow by angle addition
@@ -548,7 +562,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
       }
 #pragma unroll
       for (int pr = 0; pr < 2; ++pr) {
-        const int n2 = mc * kPairs + ((rgw * 64 + mt * 16 + 4 * q4) >> 1) + pr + 1;   // accumulator rows 4*q4 + 2*pr
+        const int n2 = mc * kPairs + ((rgw * 16 * MT + mt * 16 + 4 * q4) >> 1) + pr + 1;   // accumulator rows 4*q4 + 2*pr
         fixed_phase_cs<T>(static_cast<uint32_t>(n2) * ph_blk, &twc[mt][pr], &tws[mt][pr]);
       }
     }
@@ -567,15 +581,15 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
     }
   }
   // unused columns / pad rows of the LDS tiles stay zero for the whole kernel
-  for (uint32_t it = tid; it < 2 * bufb / 16; it += kCBlock)
+  for (uint32_t it = tid; it < 2 * bufb / 16; it += kThreads)
     reinterpret_cast<u32x4*>(smem)[it] = u32x4{0u, 0u, 0u, 0u};
 
   Frag<T> ones;
   ones.v = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
 
-  f32x4 acc[4][DT];
+  f32x4 acc[MT][DT];
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) acc[mt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   f32x4 acc_dc = {0.f, 0.f, 0.f, 0.f};   // rows are identical: the column sums of tile rgw
@@ -588,8 +602,8 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int cp = cpos[ch * 8 + e];
-    if (cp < 0) sc_off[e] = (static_cast<uint32_t>(-cp - 1) * kFP + 4 * quad) * 2;
-    else if (write_keep) sc_off[e] = ks_off + (static_cast<uint32_t>(cp) * kFP + 4 * quad) * 2;
+    if (cp < 0) sc_off[e] = (static_cast<uint32_t>(-cp - 1) * kFP + TOK * quad) * 2;
+    else if (write_keep) sc_off[e] = ks_off + (static_cast<uint32_t>(cp) * kFP + TOK * quad) * 2;
     else sc_off[e] = ks_off + static_cast<uint32_t>(kp) * kFP * 2;   // spare slot: the value is not needed
   }
   // ---- kept dims leave the staging tile as 128-bit stores: one or more vectors per thread ------
@@ -597,16 +611,12 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   // (dim, 8 tokens 8 g..): contiguous in the tile
   const int nvec = rows_layout ? kFB * (kp / 8) : Du * (kFB / 8);
   const int c8n = max(kp / 8, 1), dun = max(Du, 1);
-  const int kv_0 = tid;                                          // first vector of this thread
+  const int kv_0 = max(min(tid, nvec - 1), 0);                   // first vector of this thread
   const int kv_a = rows_layout ? kv_0 / c8n : kv_0 / dun;        // token (rows) or 8-token group (tok8)
   const int kv_b = rows_layout ? kv_0 - kv_a * c8n : kv_0 - kv_a * dun;   // 8-dim group (rows) or dim (tok8)
 
   FA_CSTAMP(1);
-  // The two column halves of the workgroup (waves 0-3 and 4-7; wave w and w + 4 share a SIMD) run
-  // half a block out of phase: while one half multiplies block b on the matrix cores, the other
-  // scatters its tokens of block b + 1 and writes out kept dims of block b, then they swap.
-  const int grp = chw;
-  auto scatter_block = [&](Frag<T> (&xr)[4], int blk) {   // this thread's 4 tokens x 8 dims of block blk -> LDS
+  auto scatter_block = [&](Frag<T> (&xr)[TOK], int blk) {   // this thread's 4 tokens x 8 dims of block blk -> LDS
     const int js = j0 + blk * kFB;
     unsigned char* bb = smem + (blk & 1) * bufb;
 #pragma unroll
@@ -624,8 +634,8 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
     }
     if (js + kFB > jend) {   // ragged last block: tokens past the end count as zeros (written over)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (js + 4 * quad + i >= jend) {
+      for (int i = 0; i < TOK; ++i)
+        if (js + TOK * quad + i >= jend) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) *reinterpret_cast<uint16_t*>(bb + sc_off[e] + 2 * i) = 0;
         }
@@ -637,7 +647,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
     const int64_t tok0 = static_cast<int64_t>(p.keep_offset) + js;
     const int it0 = tid;
     if (rows_layout) {
-      for (int it = it0; it < nvec; it += kCBlock) {
+      for (int it = it0; it < nvec; it += kThreads) {
         const int jt = (it == it0) ? kv_a : it / c8n, c8 = (it == it0) ? kv_b : it - (it / c8n) * c8n;
         if (js + jt < jend) {
           const uint16_t* src = reinterpret_cast<const uint16_t*>(ks) + (8 * c8) * kFP + jt;
@@ -649,7 +659,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
         }
       }
     } else {
-      for (int it = it0; it < nvec; it += kCBlock) {
+      for (int it = it0; it < nvec; it += kThreads) {
         const int g = (it == it0) ? kv_a : it / dun, dim = (it == it0) ? kv_b : it - (it / dun) * dun;
         if (js + 8 * g < jend) {
           Frag<T> f;
@@ -672,7 +682,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
       // (also for the first block: the accumulators are zero then, and an unconditional turn keeps
       // them in place in their registers)
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int pr = 0; pr < 2; ++pr) {
           const float c = twc[mt][pr], sn = tws[mt][pr];
@@ -697,7 +707,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
 #pragma unroll
         for (int ksx = 0; ksx < kFK; ++ksx)
 #pragma unroll
-          for (int mt = 0; mt < 4; ++mt) mma_k32(acc[mt][dt], ea[mt][ksx], cur[ksx]);
+          for (int mt = 0; mt < MT; ++mt) mma_k32(acc[mt][dt], ea[mt][ksx], cur[ksx]);
       }
       // constant function: a row of ones against column tile rgw of this wave's half
       if (wave_dc && dt == rgw) {
@@ -707,11 +717,113 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  auto two_slots = [&](Frag<T> (&xnext)[4], int blk) {   // block blk; xnext holds block blk + 1
-    multiply_block(blk);
-    FA_CSTAMP(3 + 4 * blk);
-    if (blk + 1 < nb) scatter_block(xnext, blk + 1);
-    if (write_keep) keep_out(blk);
+  // One straight-line pass over block blk for a wave with live basis rows: the products of block
+  // blk, the scatter of block blk + 1 (into the other buffer) and the kept dims of block blk leave
+  // in ONE instruction stream without branches, so that the scatter and the frame turn issue in
+  // the shadow of the matrix instructions.  Ragged edges are handled by value: tokens past the
+  // chunk are masked to zero, vectors past the end re-store the last valid one.
+  const int dcl = min(rgw, DT - 1);   // column tile whose sums this wave forms (used if wave_dc)
+  auto fused_step = [&](Frag<T> (&xnext)[TOK], int blk) {
+    constexpr int kMode = KM;   // kept dims: 0 none to write, 1 rows, 2 groups of 8 tokens
+    const int js = j0 + blk * kFB;
+    const unsigned char* cb = smem + (blk & 1) * bufb;
+    unsigned char* fb = smem + ((blk & 1) ^ 1) * bufb;
+    const T* bcol = reinterpret_cast<const T*>(cb) + (chw * DT * 16 + r16) * kFP + 8 * q4;
+    Frag<T> bxa[kFK], bxb[kFK];
+#pragma unroll
+    for (int ksx = 0; ksx < kFK; ++ksx) bxa[ksx].load(bcol + 32 * ksx);
+    // kept dims of block blk: out of the staging tile
+    u32x4 kvv = {0u, 0u, 0u, 0u};
+    T* kdst = keep;
+    if constexpr (kMode == 1) {
+      const int jt = max(min(kv_a, jend - js - 1), 0);
+      const uint16_t* src = reinterpret_cast<const uint16_t*>(cb + ks_off) + (8 * kv_b) * kFP + jt;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        kvv[k] = static_cast<uint32_t>(src[(2 * k) * kFP]) | (static_cast<uint32_t>(src[(2 * k + 1) * kFP]) << 16);
+      kdst = keep + (static_cast<int64_t>(p.keep_offset) + js + jt) * kp + 8 * kv_b;
+    } else if constexpr (kMode == 2) {
+      const int g = max(min(kv_a, (jend - js - 1) >> 3), 0);
+      kvv = *reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(cb + ks_off) + kv_b * kFP + 8 * g);
+      kdst = keep + ((((static_cast<int64_t>(p.keep_offset) + js) >> 3) + g) * Du + kv_b) * 8;
+    }
+    // the frame turns by 128 tokens (also before the first block: the accumulators are zero then);
+    // tile dt + 1 turns while tile dt is multiplied
+    auto turn = [&](int dt) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+          const float c = twc[mt][pr], sn = tws[mt][pr];
+          const float ac = acc[mt][dt][2 * pr], as = acc[mt][dt][2 * pr + 1];
+          acc[mt][dt][2 * pr] = c * ac + sn * as;
+          acc[mt][dt][2 * pr + 1] = c * as - sn * ac;
+        }
+    };
+    // this thread's tokens of block blk + 1, zeros past the end of the chunk
+    const int left = jend - (js + kFB) - TOK * quad;
+    uint32_t vm[TOK / 2];
+#pragma unroll
+    for (int i = 0; i < TOK / 2; ++i)
+      vm[i] = (left > 2 * i ? 0x0000ffffu : 0u) | (left > 2 * i + 1 ? 0xffff0000u : 0u);
+    auto scatter_dim = [&](int e) {
+      const int w = e >> 1;
+      uint32_t pk[TOK / 2];
+#pragma unroll
+      for (int i = 0; i < TOK / 2; ++i)
+        pk[i] = ((e & 1) ? pack_hi(xnext[2 * i].v[w], xnext[2 * i + 1].v[w])
+                         : pack_lo(xnext[2 * i].v[w], xnext[2 * i + 1].v[w])) & vm[i];
+      *reinterpret_cast<u32x2c*>(fb + sc_off[e]) = u32x2c{pk[0], pk[1]};
+    };
+    turn(0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      Frag<T> (&cur)[kFK] = (dt & 1) ? bxb : bxa;
+      Frag<T> (&nxt)[kFK] = (dt & 1) ? bxa : bxb;
+      // next tile's operands; after the last tile the tile whose column sums this wave forms
+      const T* nsrc = bcol + ((dt + 1 < DT) ? (dt + 1) * 16 * kFP : dcl * 16 * kFP);
+#pragma unroll
+      for (int ksx = 0; ksx < kFK; ++ksx) nxt[ksx].load(nsrc + 32 * ksx);
+      if (dt + 1 < DT) turn(dt + 1);
+      if (dt == 0) {
+        // the whole scatter rides on the first tile, so that the registers can be refilled at once:
+        // the block after next is requested a full block and a half before its turn
+#pragma unroll
+        for (int e = 0; e < 8; ++e) scatter_dim(e);
+        load_x(xnext, blk + 3);
+      }
+#pragma unroll
+      for (int ksx = 0; ksx < kFK; ++ksx)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) mma_k32(acc[mt][dt], ea[mt][ksx], cur[ksx]);
+#pragma unroll
+      for (int i = 0; i < kSchedGroups; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one matrix instruction,
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // three vector instructions,
+        __builtin_amdgcn_sched_group_barrier(0x300, 1, 0);   // one LDS access
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (dt == 0) FA_CSTAMP(3 + 4 * blk);
+      if (dt == DT - 1) FA_CSTAMP(6 + 4 * blk);
+    }
+    {
+      Frag<T> (&dcx)[kFK] = (DT & 1) ? bxb : bxa;
+#pragma unroll
+      for (int ksx = 0; ksx < kFK; ++ksx) mma_k32(acc_dc, ones, dcx[ksx]);
+    }
+    if constexpr (kMode > 0) {
+      if (write_keep && blk < nb) *reinterpret_cast<u32x4*>(kdst) = kvv;
+    }
+  };
+  auto two_slots = [&](Frag<T> (&xnext)[TOK], int blk) {   // block blk; xnext holds block blk + 1
+    if constexpr (KM >= 0) {
+      fused_step(xnext, blk);
+    } else {
+      multiply_block(blk);
+      if (blk + 1 < nb) scatter_block(xnext, blk + 1);
+      if (write_keep) keep_out(blk);
+    }
     FA_CSTAMP(4 + 4 * blk);
     __syncthreads();
     FA_CSTAMP(5 + 4 * blk);
@@ -723,11 +835,20 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   load_x(xra, 2);
   __syncthreads();
   FA_CSTAMP(2);
-  for (int blk = 0; blk < nb; blk += 2) {
-    two_slots(xrb, blk);
-    load_x(xrb, blk + 3);
-    if (blk + 1 < nb) two_slots(xra, blk + 1);
-    load_x(xra, blk + 4);
+  if constexpr (KM >= 0) {
+    // blocks go in pairs without a branch in between; an odd chunk ends with a block of zeros
+    // (the scatter past the chunk writes zeros), which only turns the frame once more
+    for (int blk = 0; blk < nb; blk += 2) {
+      two_slots(xrb, blk);
+      two_slots(xra, blk + 1);
+    }
+  } else {
+    for (int blk = 0; blk < nb; blk += 2) {
+      two_slots(xrb, blk);
+      load_x(xrb, blk + 3);
+      if (blk + 1 < nb) two_slots(xra, blk + 1);
+      load_x(xra, blk + 4);
+    }
   }
 
   FA_CSTAMP(30);
@@ -741,12 +862,13 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
     if (i < p.Dc) dst[i] = add ? dst[i] + acc_dc[0] : acc_dc[0];
   }
   if (wave_live) {
-    const uint32_t ph_last = fixed_phase(p.t0 + j0 + (nb - 1) * kFB, p.ph_scale);   // frame origin
+    const int nbr = (KM >= 0) ? ((nb + 1) & ~1) : nb;   // blocks the frame has turned through
+    const uint32_t ph_last = fixed_phase(p.t0 + j0 + (nbr - 1) * kFB, p.ph_scale);   // frame origin
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int pr = 0; pr < 2; ++pr) {
-        const int n = mc * kPairs + ((rgw * 64 + mt * 16 + 4 * q4) >> 1) + pr + 1;
+        const int n = mc * kPairs + ((rgw * 16 * MT + mt * 16 + 4 * q4) >> 1) + pr + 1;
         if (n > p.nmax) continue;
         float c, sn;
         fixed_phase_cs<T>(static_cast<uint32_t>(n) * ph_last, &c, &sn);
@@ -838,9 +960,9 @@ static int check_compress_shapes(int dtype, int B, int H, int N, int D, int Dc, 
   return FA_OK;
 }
 
-template <int DT>
+template <int DT, int KM>
 static int launch_project_fast(const CompressParams& p, const CompressPlan& pl, unsigned lds, hipStream_t st) {
-  auto kern = compress_project_fast<DT>;
+  auto kern = compress_project_fast<DT, KM>;
   static unsigned granted = 48 * 1024;
   if (lds > granted) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -953,7 +1075,16 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
     const unsigned fast_lds = 2u * (kCols * kFP + static_cast<unsigned>(keep_pitch) * kFP + 8u) * 2u;
     const bool staged_ok = x_keep == nullptr || Du == 0 || keep_layout == FA_KEEP_ROWS || keep_offset % 8 == 0;
     if (dtype == FA_BF16 && D == 128 && staged_ok && fast_lds <= kMaxCLds) {
-      rc = narrow ? launch_project_fast<3>(p, pl, fast_lds, stream) : launch_project_fast<4>(p, pl, fast_lds, stream);
+      // straight-line block step when every thread has at most one vector of kept dims to store
+      const int nvec = (x_keep == nullptr || Du == 0) ? 0 : (keep_layout == FA_KEEP_ROWS ? kFB * (keep_pitch / 8) : Du * (kFB / 8));
+      const int km = (Dc == 0 || nvec > kCBlock) ? -1 : (nvec == 0 ? 0 : (keep_layout == FA_KEEP_ROWS ? 1 : 2));
+#define FA_LAUNCH_FAST(KM_) \
+  rc = narrow ? launch_project_fast<3, KM_>(p, pl, fast_lds, stream) : launch_project_fast<4, KM_>(p, pl, fast_lds, stream)
+      if (km == 0) FA_LAUNCH_FAST(0);
+      else if (km == 1) FA_LAUNCH_FAST(1);
+      else if (km == 2) FA_LAUNCH_FAST(2);
+      else FA_LAUNCH_FAST(-1);
+#undef FA_LAUNCH_FAST
     } else if (dtype == FA_F32) {
       FA_LAUNCH_PROJECT(float);
     } else {
