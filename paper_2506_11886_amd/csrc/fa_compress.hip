@@ -541,21 +541,30 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
       const int rho = rgw * 16 * MT + mt * 16 + r16;               // A-operand row of this lane
       const int n = mc * kPairs + (rho >> 1) + 1;
       const bool live = n <= p.nmax;
-      // one exact evaluation per 32-token step; the 8 tokens of a lane follow by angle addition
-      float c1, s1;
-      fixed_phase_cs<T>(static_cast<uint32_t>(n) * ph_1, &c1, &s1);
+      // A lane needs ONE sequence per 32-token step: cos (even row) or sin (odd row) of 8
+      // consecutive tokens.  Two evaluations start it; the rest follows from the three-term
+      // recurrence v[e+1] = 2 cos(step) v[e] - v[e-1], written in differences
+      //   d[e+1] = d[e] - kappa v[e],  v[e+1] = v[e] + d[e+1],  kappa = 4 sin^2(step / 2),
+      // which keeps its accuracy for the tiny steps of low harmonics (2 cos(step) would round
+      // to 2).  Over 8 steps the rounding stays far below a bf16 ulp.
+      const uint32_t stepn = static_cast<uint32_t>(n) * ph_1;   // <= half a turn: n <= T / 2
+      const uint32_t quarter = (rho & 1) ? 0x40000000u : 0u;    // sin x = cos(x - 1/4 turn)
+      const float sh = sinpif(static_cast<float>(stepn) * 2.3283064365386963e-10f);   // sin(step / 2)
+      const float kappa = 4.0f * sh * sh;
 #pragma unroll
       for (int ksx = 0; ksx < kFK; ++ksx) {
-        float c, sn;
-        fixed_phase_cs<T>(static_cast<uint32_t>(n) * ph_u[ksx], &c, &sn);
+        const uint32_t ph0 = static_cast<uint32_t>(n) * ph_u[ksx] - quarter;
         float vals[8];
+        vals[0] = __builtin_amdgcn_cosf(static_cast<float>(static_cast<int32_t>(ph0)) * 2.3283064365386963e-10f);
+        vals[1] = __builtin_amdgcn_cosf(static_cast<float>(static_cast<int32_t>(ph0 + stepn)) * 2.3283064365386963e-10f);
+        float dv = vals[1] - vals[0];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          vals[e] = live ? ((rho & 1) ? sn : c) : 0.0f;
-          const float cn = c * c1 - sn * s1;
-          sn = sn * c1 + c * s1;
-          c = cn;
+        for (int e = 2; e < 8; ++e) {
+          dv -= kappa * vals[e - 1];
+          vals[e] = vals[e - 1] + dv;
         }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vals[e] = live ? vals[e] : 0.0f;
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           ea[mt][ksx].v[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2c{vals[2 * e], vals[2 * e + 1]}, bf16x2c));
