@@ -171,12 +171,14 @@ int fa_append(const void* k_new, const void* v_new, int dtype,
 
 /*
  * Measurement aids.  Same arguments and effect as fa_compress / fa_decode, but
- * synchronous: HIP events are recorded on `hip_stream` around every kernel of
- * the call, the call waits for the last one, and the per-kernel durations in
- * milliseconds are written to `kernel_ms`, a HOST array:
+ * synchronous: every kernel of the call is launched on `hip_stream` with its
+ * own pair of HIP events, stamped by the runtime with the begin and the end of
+ * that dispatch on the GPU (launch latency excluded); the call waits for the
+ * stream, and the per-kernel durations in milliseconds are written to
+ * `kernel_ms`, a HOST array:
  *   fa_compress_timed: 2 floats (projection, chunk reduction)
  *   fa_decode_timed  : 3 floats (prepare, per-chunk partial, finish)
- * A kernel that was not launched for these sizes reports ~0.
+ * A kernel that was not launched for these sizes reports 0.
  */
 int fa_compress_timed(const void* x, int dtype,
                       int64_t sx_b, int64_t sx_h, int64_t sx_n,

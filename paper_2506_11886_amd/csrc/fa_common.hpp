@@ -2,11 +2,50 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "fourier_attn.h"
 
 namespace fa {
+
+// Per-kernel timing of the *_timed entry points: every launch carries its own start / stop
+// event pair, which the runtime stamps with the dispatch's begin and end on the GPU (the
+// interval between two ordinary stream events would also hold the launch latency).
+struct KernelTimers {
+  static constexpr int kMax = 3;
+  hipEvent_t start[kMax] = {nullptr, nullptr, nullptr};
+  hipEvent_t stop[kMax] = {nullptr, nullptr, nullptr};
+  bool used[kMax] = {false, false, false};
+  int create() {
+    for (int i = 0; i < kMax; ++i)
+      if (hipEventCreate(&start[i]) != hipSuccess || hipEventCreate(&stop[i]) != hipSuccess) return FA_ERR_HIP;
+    return FA_OK;
+  }
+  void destroy() {
+    for (int i = 0; i < kMax; ++i) {
+      if (start[i]) (void)hipEventDestroy(start[i]);
+      if (stop[i]) (void)hipEventDestroy(stop[i]);
+    }
+  }
+  // milliseconds of kernels 0 .. n-1 (0 for a kernel that was not launched); waits for the last one
+  int read(int n, float* ms) {
+    for (int i = 0; i < n; ++i) {
+      ms[i] = 0.0f;
+      if (!used[i]) continue;
+      if (hipEventSynchronize(stop[i]) != hipSuccess) return FA_ERR_HIP;
+      if (hipEventElapsedTime(&ms[i], start[i], stop[i]) != hipSuccess) return FA_ERR_HIP;
+    }
+    return FA_OK;
+  }
+};
+// launch with the optional timers' event pair number i
+#define FA_LAUNCH_TIMED(tm_, i_, kern_, grid_, block_, lds_, st_, ...)                               \
+  do {                                                                                              \
+    hipExtLaunchKernelGGL(kern_, grid_, block_, lds_, st_, (tm_) ? (tm_)->start[i_] : nullptr,      \
+                          (tm_) ? (tm_)->stop[i_] : nullptr, 0, __VA_ARGS__);                       \
+    if (tm_) (tm_)->used[i_] = true;                                                                \
+  } while (0)
 
 constexpr int kWave = 64;
 

@@ -557,14 +557,13 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
         float vals[8];
         vals[0] = __builtin_amdgcn_cosf(static_cast<float>(static_cast<int32_t>(ph0)) * 2.3283064365386963e-10f);
         vals[1] = __builtin_amdgcn_cosf(static_cast<float>(static_cast<int32_t>(ph0 + stepn)) * 2.3283064365386963e-10f);
+        if (!live) vals[0] = vals[1] = 0.0f;   // rows past the highest harmonic: the recurrence keeps them zero
         float dv = vals[1] - vals[0];
 #pragma unroll
         for (int e = 2; e < 8; ++e) {
           dv -= kappa * vals[e - 1];
           vals[e] = vals[e - 1] + dv;
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) vals[e] = live ? vals[e] : 0.0f;
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           ea[mt][ksx].v[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2c{vals[2 * e], vals[2 * e + 1]}, bf16x2c));
@@ -970,7 +969,8 @@ static int check_compress_shapes(int dtype, int B, int H, int N, int D, int Dc, 
 }
 
 template <int DT, int KM>
-static int launch_project_fast(const CompressParams& p, const CompressPlan& pl, unsigned lds, hipStream_t st) {
+static int launch_project_fast(const CompressParams& p, const CompressPlan& pl, unsigned lds, hipStream_t st,
+                               KernelTimers* tm) {
   auto kern = compress_project_fast<DT, KM>;
   static unsigned granted = 48 * 1024;
   if (lds > granted) {
@@ -981,12 +981,12 @@ static int launch_project_fast(const CompressParams& p, const CompressPlan& pl, 
     granted = kMaxCLds;
   }
   dim3 grid(pl.Sc, pl.MC, p.B * p.H);
-  hipLaunchKernelGGL(kern, grid, dim3(kCBlock), lds, st, p);
+  FA_LAUNCH_TIMED(tm, 0, kern, grid, dim3(kCBlock), lds, st, p);
   return FA_OK;
 }
 
 template <typename T, int DT, int kXR, bool kFast>
-static int launch_project(const CompressParams& p, const CompressPlan& pl, hipStream_t st) {
+static int launch_project(const CompressParams& p, const CompressPlan& pl, hipStream_t st, KernelTimers* tm) {
   auto kern = compress_project<T, DT, kXR, kFast>;
   static unsigned granted = 48 * 1024;
   if (pl.lds > granted) {
@@ -997,7 +997,7 @@ static int launch_project(const CompressParams& p, const CompressPlan& pl, hipSt
     granted = kMaxCLds;
   }
   dim3 grid(pl.Sc, pl.MC * pl.DCn, p.B * p.H);
-  hipLaunchKernelGGL(kern, grid, dim3(kCBlock), pl.lds, st, p);
+  FA_LAUNCH_TIMED(tm, 0, kern, grid, dim3(kCBlock), pl.lds, st, p);
   return FA_OK;
 }
 
@@ -1015,7 +1015,7 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
                          int H, int N, int D, const uint8_t* dim_mask, int Dc, int M, int T, int t0,
                          int accumulate, float* coeffs, void* x_keep, int keep_layout,
                          int64_t keep_stride_bh, int keep_offset, void* workspace,
-                         size_t workspace_bytes, void* hip_stream, hipEvent_t* ev) {
+                         size_t workspace_bytes, void* hip_stream, fa::KernelTimers* tm) {
   using namespace fa;
   const int st = check_compress_shapes(dtype, B, H, N, D, Dc, M, T, t0);
   if (st != FA_OK) return st;
@@ -1062,7 +1062,6 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const size_t total = static_cast<size_t>(B) * H * M * Dc;
-  if (ev) (void)hipEventRecord(ev[0], stream);
   if (pl.Sc > 0) {
     const int cols = Dc < kCols ? Dc : kCols;
     int rc;
@@ -1070,8 +1069,8 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
     // every thread routes fixed dims when the row vectors divide the workgroup and kept dims are staged
     const bool fast = (kCBlock % (D / 8)) == 0 && (pl.stage || Du == 0 || x_keep == nullptr);
 #define FA_LAUNCH_PROJECT2(T_, F_)                                                                  \
-  rc = narrow ? (small_d ? launch_project<T_, 3, 2, F_>(p, pl, stream) : launch_project<T_, 3, 4, F_>(p, pl, stream)) \
-              : (small_d ? launch_project<T_, 4, 2, F_>(p, pl, stream) : launch_project<T_, 4, 4, F_>(p, pl, stream))
+  rc = narrow ? (small_d ? launch_project<T_, 3, 2, F_>(p, pl, stream, tm) : launch_project<T_, 3, 4, F_>(p, pl, stream, tm)) \
+              : (small_d ? launch_project<T_, 4, 2, F_>(p, pl, stream, tm) : launch_project<T_, 4, 4, F_>(p, pl, stream, tm))
 #define FA_LAUNCH_PROJECT(T_)       \
   do {                              \
     if (fast) {                     \
@@ -1088,7 +1087,7 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
       const int nvec = (x_keep == nullptr || Du == 0) ? 0 : (keep_layout == FA_KEEP_ROWS ? kFB * (keep_pitch / 8) : Du * (kFB / 8));
       const int km = (Dc == 0 || nvec > kCBlock) ? -1 : (nvec == 0 ? 0 : (keep_layout == FA_KEEP_ROWS ? 1 : 2));
 #define FA_LAUNCH_FAST(KM_) \
-  rc = narrow ? launch_project_fast<3, KM_>(p, pl, fast_lds, stream) : launch_project_fast<4, KM_>(p, pl, fast_lds, stream)
+  rc = narrow ? launch_project_fast<3, KM_>(p, pl, fast_lds, stream, tm) : launch_project_fast<4, KM_>(p, pl, fast_lds, stream, tm)
       if (km == 0) FA_LAUNCH_FAST(0);
       else if (km == 1) FA_LAUNCH_FAST(1);
       else if (km == 2) FA_LAUNCH_FAST(2);
@@ -1103,13 +1102,11 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
 #undef FA_LAUNCH_PROJECT
     if (rc != FA_OK) return rc;
   }
-  if (ev) (void)hipEventRecord(ev[1], stream);
   if (total > 0 && (pl.Sc > 1 || (pl.Sc == 0 && !accumulate))) {
     const unsigned blocks = static_cast<unsigned>((total / 4 + 1 + 255) / 256);
-    hipLaunchKernelGGL(compress_reduce, dim3(blocks), dim3(256), 0, stream, p.part, coeffs, total,
-                       p.part_stride, pl.Sc, p.accumulate);
+    FA_LAUNCH_TIMED(tm, 1, compress_reduce, dim3(blocks), dim3(256), 0, stream, p.part, coeffs, total,
+                    p.part_stride, pl.Sc, p.accumulate);
   }
-  if (ev) (void)hipEventRecord(ev[2], stream);
   return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
 }
 
@@ -1128,18 +1125,15 @@ int fa_compress_timed(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int6
                       int64_t keep_stride_bh, int keep_offset, void* workspace,
                       size_t workspace_bytes, void* hip_stream, float* kernel_ms) {
   if (!kernel_ms) return FA_ERR_NULL;
-  hipEvent_t ev[3];
-  for (int i = 0; i < 3; ++i)
-    if (hipEventCreate(&ev[i]) != hipSuccess) return FA_ERR_HIP;
-  int st = compress_impl(x, dtype, sx_b, sx_h, sx_n, B, H, N, D, dim_mask, Dc, M, T, t0, accumulate,
-                         coeffs, x_keep, keep_layout, keep_stride_bh, keep_offset, workspace,
-                         workspace_bytes, hip_stream, ev);
-  if (st == FA_OK) {
-    if (hipEventSynchronize(ev[2]) != hipSuccess) st = FA_ERR_HIP;
-    for (int i = 0; i < 2 && st == FA_OK; ++i)
-      if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = FA_ERR_HIP;
-  }
-  for (int i = 0; i < 3; ++i) (void)hipEventDestroy(ev[i]);
+  fa::KernelTimers tm;
+  int st = tm.create();
+  if (st == FA_OK)
+    st = compress_impl(x, dtype, sx_b, sx_h, sx_n, B, H, N, D, dim_mask, Dc, M, T, t0, accumulate,
+                       coeffs, x_keep, keep_layout, keep_stride_bh, keep_offset, workspace,
+                       workspace_bytes, hip_stream, &tm);
+  if (st == FA_OK) st = tm.read(2, kernel_ms);
+  if (st == FA_OK && hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)) != hipSuccess) st = FA_ERR_HIP;
+  tm.destroy();
   return st;
 }
 

@@ -1472,7 +1472,7 @@ static int check_decode_shapes(int dtype, int B, int Hq, int Hkv, int D, int Dkc
 }
 
 template <typename T, int CW, int DVTM, bool KC1>
-static int launch_partial(const DecodeParams& p, unsigned lds, hipStream_t st) {
+static int launch_partial(const DecodeParams& p, unsigned lds, hipStream_t st, KernelTimers* tm) {
   auto kern = decode_partial<T, CW, DVTM, KC1>;
   // raising the dynamic-LDS ceiling is a property of the loaded kernel: do it once
   static unsigned granted = 48 * 1024;
@@ -1484,32 +1484,30 @@ static int launch_partial(const DecodeParams& p, unsigned lds, hipStream_t st) {
     granted = kMaxDynLds;
   }
   dim3 g2(p.Sw + p.Sm, p.B * p.Hkv);
-  hipLaunchKernelGGL(kern, g2, dim3(kBlock), lds, st, p);
+  FA_LAUNCH_TIMED(tm, 1, kern, g2, dim3(kBlock), lds, st, p);
   return FA_OK;
 }
 
-// ev (optional): 4 events recorded before/after each kernel, for fa_decode_timed
+// tm (optional): per-kernel event pairs, for fa_decode_timed
 template <typename T>
-static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_t st, hipEvent_t* ev) {
+static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_t st, KernelTimers* tm) {
   const int BH = p.B * p.Hkv;
-  if (ev) (void)hipEventRecord(ev[0], st);
   if (p.Sm > 0) {
     if (static_cast<long>(BH) * ((p.Mint + 32) / 32) >= 512) {
       dim3 g1((p.Mint + 32) / 32, BH);
-      hipLaunchKernelGGL((decode_prepare<T, 32>), g1, dim3(kBlock), 0, st, p);
+      FA_LAUNCH_TIMED(tm, 0, (decode_prepare<T, 32>), g1, dim3(kBlock), 0, st, p);
     } else {
       dim3 g1((p.Mint + 8) / 8, BH);
-      hipLaunchKernelGGL((decode_prepare<T, 8>), g1, dim3(kBlock), 0, st, p);
+      FA_LAUNCH_TIMED(tm, 0, (decode_prepare<T, 8>), g1, dim3(kBlock), 0, st, p);
     }
   }
-  if (ev) (void)hipEventRecord(ev[1], st);
   int rc;
   const bool narrow = p.Dvu <= 32;   // kept V dims fit two MFMA column tiles
   const bool kc1 = p.Dku <= 32;      // kept K dims fit one MFMA step
 #define FA_LAUNCH_PARTIAL(CW_)                                                                      \
-  rc = (narrow && kc1) ? launch_partial<T, CW_, 2, true>(p, pl.lds_total, st)                       \
-       : narrow        ? launch_partial<T, CW_, 2, false>(p, pl.lds_total, st)                      \
-                       : launch_partial<T, CW_, kMaxDvTiles, false>(p, pl.lds_total, st)
+  rc = (narrow && kc1) ? launch_partial<T, CW_, 2, true>(p, pl.lds_total, st, tm)                       \
+       : narrow        ? launch_partial<T, CW_, 2, false>(p, pl.lds_total, st, tm)                      \
+                       : launch_partial<T, CW_, kMaxDvTiles, false>(p, pl.lds_total, st, tm)
   switch (pl.cw) {
     case 1: FA_LAUNCH_PARTIAL(1); break;
     case 2: FA_LAUNCH_PARTIAL(2); break;
@@ -1523,9 +1521,7 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
   }
 #undef FA_LAUNCH_PARTIAL
   if (rc != FA_OK) return rc;
-  if (ev) (void)hipEventRecord(ev[2], st);
-  hipLaunchKernelGGL(decode_finish<T>, dim3((p.D + kFinDims - 1) / kFinDims, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
-  if (ev) (void)hipEventRecord(ev[3], st);
+  FA_LAUNCH_TIMED(tm, 2, decode_finish<T>, dim3((p.D + kFinDims - 1) / kFinDims, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
   return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
 }
 
@@ -1558,7 +1554,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
                        const void* v_keep, int64_t vk_stride_bh, const void* k_full,
                        const void* v_full, int W, int64_t full_stride_bh, float scale,
                        int num_splits, float* out, void* workspace, size_t workspace_bytes,
-                       void* hip_stream, hipEvent_t* ev) {
+                       void* hip_stream, fa::KernelTimers* tm) {
   using namespace fa;
   const int st = check_decode_shapes(dtype, B, Hq, Hkv, D, Dkc, Dvc, M, T, t0, N, W, num_splits);
   if (st != FA_OK) return st;
@@ -1616,8 +1612,8 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   p.trace = reinterpret_cast<long long*>(ws + pl.off_trace);
 #endif
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  return dtype == FA_F32 ? launch_decode<float>(p, pl, stream, ev)
-                         : launch_decode<bf16_t>(p, pl, stream, ev);
+  return dtype == FA_F32 ? launch_decode<float>(p, pl, stream, tm)
+                         : launch_decode<bf16_t>(p, pl, stream, tm);
 }
 
 int fa_decode(const void* q, int dtype, int B, int Hq, int Hkv, int D, const float* ck,
@@ -1639,18 +1635,15 @@ int fa_decode_timed(const void* q, int dtype, int B, int Hq, int Hkv, int D, con
                     float* out, void* workspace, size_t workspace_bytes, void* hip_stream,
                     float* kernel_ms) {
   if (!kernel_ms) return FA_ERR_NULL;
-  hipEvent_t ev[4];
-  for (int i = 0; i < 4; ++i)
-    if (hipEventCreate(&ev[i]) != hipSuccess) return FA_ERR_HIP;
-  int st = decode_impl(q, dtype, B, Hq, Hkv, D, ck, kmask, Dkc, cv, vmask, Dvc, M, T, t0, N, k_keep,
-                       kk_stride_bh, v_keep, vk_stride_bh, k_full, v_full, W, full_stride_bh, scale,
-                       num_splits, out, workspace, workspace_bytes, hip_stream, ev);
-  if (st == FA_OK) {
-    if (hipEventSynchronize(ev[3]) != hipSuccess) st = FA_ERR_HIP;
-    for (int i = 0; i < 3 && st == FA_OK; ++i)
-      if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = FA_ERR_HIP;
-  }
-  for (int i = 0; i < 4; ++i) (void)hipEventDestroy(ev[i]);
+  fa::KernelTimers tm;
+  int st = tm.create();
+  if (st == FA_OK)
+    st = decode_impl(q, dtype, B, Hq, Hkv, D, ck, kmask, Dkc, cv, vmask, Dvc, M, T, t0, N, k_keep,
+                     kk_stride_bh, v_keep, vk_stride_bh, k_full, v_full, W, full_stride_bh, scale,
+                     num_splits, out, workspace, workspace_bytes, hip_stream, &tm);
+  if (st == FA_OK) st = tm.read(3, kernel_ms);
+  if (st == FA_OK && hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)) != hipSuccess) st = FA_ERR_HIP;
+  tm.destroy();
   return st;
 }
 
