@@ -39,12 +39,17 @@ struct KernelTimers {
     return FA_OK;
   }
 };
-// launch with the optional timers' event pair number i
+// launch, with the timers' event pair number i_ when timers are given (the plain launch is kept
+// for the untimed entry points, which callers may record into a HIP graph)
 #define FA_LAUNCH_TIMED(tm_, i_, kern_, grid_, block_, lds_, st_, ...)                               \
   do {                                                                                              \
-    hipExtLaunchKernelGGL(kern_, grid_, block_, lds_, st_, (tm_) ? (tm_)->start[i_] : nullptr,      \
-                          (tm_) ? (tm_)->stop[i_] : nullptr, 0, __VA_ARGS__);                       \
-    if (tm_) (tm_)->used[i_] = true;                                                                \
+    if (tm_) {                                                                                      \
+      hipExtLaunchKernelGGL(kern_, grid_, block_, lds_, st_, (tm_)->start[i_], (tm_)->stop[i_], 0,  \
+                            __VA_ARGS__);                                                           \
+      (tm_)->used[i_] = true;                                                                       \
+    } else {                                                                                        \
+      hipLaunchKernelGGL(kern_, grid_, block_, lds_, st_, __VA_ARGS__);                             \
+    }                                                                                               \
   } while (0)
 
 constexpr int kWave = 64;
