@@ -453,7 +453,6 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
 constexpr int kFB = 128;            // tokens per block
 constexpr int kFP = kFB + 8;        // LDS pitch (elements) of a transposed column
 constexpr int kFK = kFB / 32;       // 32-token contraction steps per block
-constexpr int kSchedGroups = 16;    // matrix instructions per tile of a wave: one interleave group each
 
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) {   // (a.lo, b.lo)
   return __builtin_amdgcn_perm(b, a, 0x05040100u);
@@ -470,10 +469,10 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   using T = bf16_t;
   constexpr int NW = kCBlock / 64;    // 8 waves
   constexpr int kThreads = kCBlock;
-  constexpr int MT = 4;               // 16-row basis tiles per wave
-  constexpr int CH = 2;               // column groups of DT tiles
+  constexpr int MT = 2;               // 16-row basis tiles per wave
+  constexpr int CH = 1;               // column groups of DT tiles: every wave multiplies all columns
   constexpr int TOK = 32 / NW;        // consecutive tokens a thread loads: 4
-  constexpr int RG = NW / CH;         // row groups of 16 MT = 64 basis rows
+  constexpr int RG = NW / CH;         // row groups of 16 MT = 32 basis rows
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int16_t cpos[FA_MAX_HEAD_DIM];
 
@@ -526,16 +525,18 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   const bool wave_live = project && rgw * 16 * MT < rows_here && ndt > 0;
   const bool wave_dc = do_dc && rgw < ndt && rgw < DT;   // this wave sums column tile rgw of its half
 
-  Frag<T> ea[MT][kFK];            // [m tile][32-token step]
-  float twc[MT][2], tws[MT][2];    // cos/sin(omega_n * 128) of the two pairs a lane owns in every m tile
-  const uint32_t ph_blk = fixed_phase(kFB, p.ph_scale);
+  // Two basis sets: tokens 0..127 and 128..255 of a pair of blocks.  The frame then moves once per
+  // PAIR of blocks (by 256 tokens), which halves the turning arithmetic per token.
+  Frag<T> ea[2][MT][kFK];          // [block of the pair][m tile][32-token step]
+  float twc[MT][2], tws[MT][2];    // cos/sin(omega_n * 256) of the two pairs a lane owns in every m tile
+  const uint32_t ph_blk = fixed_phase(2 * kFB, p.ph_scale);
   if (wave_live) {
     // phase of token u as a 2^-32-turn fixed-point number; times n it wraps exactly, and the
     // rounding of the unit (< 2^-32 turn) grows to at most n * 2^-32 turn: far below a bf16 ulp
     const uint32_t ph_1 = fixed_phase(1, p.ph_scale);
-    uint32_t ph_u[kFK];
+    uint32_t ph_u[2 * kFK];
 #pragma unroll
-    for (int ksx = 0; ksx < kFK; ++ksx) ph_u[ksx] = fixed_phase(32 * ksx + 8 * q4, p.ph_scale);
+    for (int ksx = 0; ksx < 2 * kFK; ++ksx) ph_u[ksx] = fixed_phase(32 * ksx + 8 * q4, p.ph_scale);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int rho = rgw * 16 * MT + mt * 16 + r16;               // A-operand row of this lane
@@ -552,7 +553,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
       const float sh = sinpif(static_cast<float>(stepn) * 2.3283064365386963e-10f);   // sin(step / 2)
       const float kappa = 4.0f * sh * sh;
 #pragma unroll
-      for (int ksx = 0; ksx < kFK; ++ksx) {
+      for (int ksx = 0; ksx < 2 * kFK; ++ksx) {
         const uint32_t ph0 = static_cast<uint32_t>(n) * ph_u[ksx] - quarter;
         float vals[8];
         vals[0] = __builtin_amdgcn_cosf(static_cast<float>(static_cast<int32_t>(ph0)) * 2.3283064365386963e-10f);
@@ -566,7 +567,8 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          ea[mt][ksx].v[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2c{vals[2 * e], vals[2 * e + 1]}, bf16x2c));
+          ea[ksx / kFK][mt][ksx % kFK].v[e] =
+              __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2c{vals[2 * e], vals[2 * e + 1]}, bf16x2c));
       }
 #pragma unroll
       for (int pr = 0; pr < 2; ++pr) {
@@ -677,7 +679,8 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
       }
     }
   };
-  auto multiply_block = [&](int blk) {
+  auto multiply_block = [&](int blk, auto odd_c) {
+    constexpr int kOdd = decltype(odd_c)::value;   // second block of a pair: second basis set, no turn
     if (!wave_live && !wave_dc) return;
     const T* xcb = reinterpret_cast<const T*>(smem + (blk & 1) * bufb);
     const T* bcol = xcb + (chw * DT * 16 + r16) * kFP + 8 * q4;   // this lane's column in tile 0
@@ -686,7 +689,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
     Frag<T> bxa[kFK], bxb[kFK];
 #pragma unroll
     for (int ksx = 0; ksx < kFK; ++ksx) bxa[ksx].load(bcol + 32 * ksx);
-    if (wave_live) {
+    if (wave_live && !kOdd) {
       // (also for the first block: the accumulators are zero then, and an unconditional turn keeps
       // them in place in their registers)
 #pragma unroll
@@ -715,7 +718,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
 #pragma unroll
         for (int ksx = 0; ksx < kFK; ++ksx)
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) mma_k32(acc[mt][dt], ea[mt][ksx], cur[ksx]);
+          for (int mt = 0; mt < MT; ++mt) mma_k32(acc[mt][dt], ea[kOdd][mt][ksx], cur[ksx]);
       }
       // constant function: a row of ones against column tile rgw of this wave's half
       if (wave_dc && dt == rgw) {
@@ -731,7 +734,8 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   // the shadow of the matrix instructions.  Ragged edges are handled by value: tokens past the
   // chunk are masked to zero, vectors past the end re-store the last valid one.
   const int dcl = min(rgw, DT - 1);   // column tile whose sums this wave forms (used if wave_dc)
-  auto fused_step = [&](Frag<T> (&xnext)[TOK], int blk) {
+  auto fused_step = [&](Frag<T> (&xnext)[TOK], int blk, auto odd_c) {
+    constexpr int kOdd = decltype(odd_c)::value;   // second block of a pair: second basis set, no turn
     constexpr int kMode = KM;   // kept dims: 0 none to write, 1 rows, 2 groups of 8 tokens
     const int js = j0 + blk * kFB;
     const unsigned char* cb = smem + (blk & 1) * bufb;
@@ -783,7 +787,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
                          : pack_lo(xnext[2 * i].v[w], xnext[2 * i + 1].v[w])) & vm[i];
       *reinterpret_cast<u32x2c*>(fb + sc_off[e]) = u32x2c{pk[0], pk[1]};
     };
-    turn(0);
+    if constexpr (!kOdd) turn(0);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
@@ -793,7 +797,9 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
       const T* nsrc = bcol + ((dt + 1 < DT) ? (dt + 1) * 16 * kFP : dcl * 16 * kFP);
 #pragma unroll
       for (int ksx = 0; ksx < kFK; ++ksx) nxt[ksx].load(nsrc + 32 * ksx);
-      if (dt + 1 < DT) turn(dt + 1);
+      if constexpr (!kOdd) {
+        if (dt + 1 < DT) turn(dt + 1);
+      }
       if (dt == 0) {
         // the whole scatter rides on the first tile, so that the registers can be refilled at once:
         // the block after next is requested a full block and a half before its turn
@@ -804,9 +810,9 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
 #pragma unroll
       for (int ksx = 0; ksx < kFK; ++ksx)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) mma_k32(acc[mt][dt], ea[mt][ksx], cur[ksx]);
+        for (int mt = 0; mt < MT; ++mt) mma_k32(acc[mt][dt], ea[kOdd][mt][ksx], cur[ksx]);
 #pragma unroll
-      for (int i = 0; i < kSchedGroups; ++i) {
+      for (int i = 0; i < MT * kFK; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one matrix instruction,
         __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // three vector instructions,
         __builtin_amdgcn_sched_group_barrier(0x300, 1, 0);   // one LDS access
@@ -824,11 +830,11 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
       if (write_keep && blk < nb) *reinterpret_cast<u32x4*>(kdst) = kvv;
     }
   };
-  auto two_slots = [&](Frag<T> (&xnext)[TOK], int blk) {   // block blk; xnext holds block blk + 1
+  auto two_slots = [&](Frag<T> (&xnext)[TOK], int blk, auto odd_c) {   // block blk; xnext holds block blk + 1
     if constexpr (KM >= 0) {
-      fused_step(xnext, blk);
+      fused_step(xnext, blk, odd_c);
     } else {
-      multiply_block(blk);
+      multiply_block(blk, odd_c);
       if (blk + 1 < nb) scatter_block(xnext, blk + 1);
       if (write_keep) keep_out(blk);
     }
@@ -847,14 +853,14 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
     // blocks go in pairs without a branch in between; an odd chunk ends with a block of zeros
     // (the scatter past the chunk writes zeros), which only turns the frame once more
     for (int blk = 0; blk < nb; blk += 2) {
-      two_slots(xrb, blk);
-      two_slots(xra, blk + 1);
+      two_slots(xrb, blk, std::integral_constant<int, 0>{});
+      two_slots(xra, blk + 1, std::integral_constant<int, 1>{});
     }
   } else {
     for (int blk = 0; blk < nb; blk += 2) {
-      two_slots(xrb, blk);
+      two_slots(xrb, blk, std::integral_constant<int, 0>{});
       load_x(xrb, blk + 3);
-      if (blk + 1 < nb) two_slots(xra, blk + 1);
+      if (blk + 1 < nb) two_slots(xra, blk + 1, std::integral_constant<int, 1>{});
       load_x(xra, blk + 4);
     }
   }
@@ -870,8 +876,10 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
     if (i < p.Dc) dst[i] = add ? dst[i] + acc_dc[0] : acc_dc[0];
   }
   if (wave_live) {
-    const int nbr = (KM >= 0) ? ((nb + 1) & ~1) : nb;   // blocks the frame has turned through
-    const uint32_t ph_last = fixed_phase(p.t0 + j0 + (nbr - 1) * kFB, p.ph_scale);   // frame origin
+    // the frame's origin is the first block of the last pair (an odd chunk of the straight-line
+    // step ends with a block of zeros, which belongs to the last pair)
+    const int last_even = (nb - 1) & ~1;
+    const uint32_t ph_last = fixed_phase(p.t0 + j0 + last_even * kFB, p.ph_scale);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -1087,7 +1095,7 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
       const int nvec = (x_keep == nullptr || Du == 0) ? 0 : (keep_layout == FA_KEEP_ROWS ? kFB * (keep_pitch / 8) : Du * (kFB / 8));
       const int km = (Dc == 0 || nvec > kCBlock) ? -1 : (nvec == 0 ? 0 : (keep_layout == FA_KEEP_ROWS ? 1 : 2));
 #define FA_LAUNCH_FAST(KM_) \
-  rc = narrow ? launch_project_fast<3, KM_>(p, pl, fast_lds, stream, tm) : launch_project_fast<4, KM_>(p, pl, fast_lds, stream, tm)
+  rc = narrow ? launch_project_fast<6, KM_>(p, pl, fast_lds, stream, tm) : launch_project_fast<8, KM_>(p, pl, fast_lds, stream, tm)
       if (km == 0) FA_LAUNCH_FAST(0);
       else if (km == 1) FA_LAUNCH_FAST(1);
       else if (km == 2) FA_LAUNCH_FAST(2);
