@@ -127,6 +127,8 @@ def small_variants():
                 Dkc=40, Dvc=32, M=32, dtype="bf16"),
         replace(base, name="wide_d256_f32", index=22, B=1, Hq=4, Hkv=2, D=256, N=260, Lw=90,
                 Dkc=128, Dvc=192, M=16, dtype="f32"),
+        replace(base, name="all_compress_bf16", index=24, B=2, Hq=4, Hkv=2, D=128, N=650, Lw=30,
+                Dkc=128, Dvc=128, M=33, dtype="bf16"),
         replace(base, name="m512", index=23, B=1, Hq=4, Hkv=1, D=128, N=1500, Lw=40,
                 Dkc=112, Dvc=112, M=512, dtype="bf16"),
     )
