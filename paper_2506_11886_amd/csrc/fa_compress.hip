@@ -36,14 +36,23 @@ constexpr unsigned kMaxCLds = 160 * 1024 - 8192;
 
 // Developer aid (compiled out unless FA_TRACE is defined): per-wave cycle stamps.
 #ifdef FA_TRACE
-#define FA_CSTAMP(i)                                                                          \
+#ifdef FA_TRACE_PRO
+#define FA_STAMP_OK(i) ((i) < 3 || (i) > 29)
+#define FA_PSTAMP(i) FA_CSTAMP(100 + (i))
+#else
+#define FA_STAMP_OK(i) true
+#define FA_PSTAMP(i) do {} while (0)
+#endif
+#define FA_CSTAMP(i_)                                                                         \
   do {                                                                                        \
-    if ((threadIdx.x & 63) == 0 && (i) < 32)                                                  \
+    const int i = (i_) >= 100 ? (i_) - 100 : (i_);                                            \
+    if ((threadIdx.x & 63) == 0 && (i) < 32 && ((i_) >= 100 || FA_STAMP_OK(i)))                                                \
       p.trace[(((static_cast<size_t>(blockIdx.z) * gridDim.y + blockIdx.y) * gridDim.x +      \
                 blockIdx.x) * 8 + (threadIdx.x >> 6)) * 32 + (i)] = clock64();                \
   } while (0)
 #else
 #define FA_CSTAMP(i) do {} while (0)
+#define FA_PSTAMP(i) do {} while (0)
 #endif
 
 typedef float f32x2c __attribute__((ext_vector_type(2)));
@@ -65,6 +74,7 @@ struct CompressParams {
   int Sc, chunk;    // token chunks and their length (multiple of kTB)
   int MC, DCn;      // row blocks (128 harmonics each), column blocks
   int nmax;         // highest harmonic: M / 2
+  uint32_t kv_magic;   // ceil(2^16 / kept-dim vectors per token (rows) or kept dims (groups of 8 tokens))
   unsigned ks_elems;   // elements of one keep-staging buffer
   double ph_scale;  // 2^32 / T
   float* part;      // [Sc][part_stride] when Sc > 1, chunk s holds [B*H][M][Dc]
@@ -474,7 +484,6 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   constexpr int TOK = 32 / NW;        // consecutive tokens a thread loads: 4
   constexpr int RG = NW / CH;         // row groups of 16 MT = 32 basis rows
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ int16_t cpos[FA_MAX_HEAD_DIM];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -517,6 +526,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   for (int j = 0; j < 2; ++j) mb[j] = p.mask[static_cast<size_t>(bh) * D + lane + 64 * j];
   load_x(xra, 0);
   load_x(xrb, 1);
+  FA_PSTAMP(23);
 
   // ---- per-wave constants: E fragments (A operand) and frame twiddles -------------------
   const int rows_here = 2 * min(kPairs, p.nmax - mc * kPairs);   // live basis rows of this row block
@@ -577,22 +587,38 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
       }
     }
   }
-  // ---- dimension ranks: >= 0 index among kept dims, < 0: -(1 + index among compressed) ------
+  FA_PSTAMP(24);
+  // ---- dimension ranks, wave-local (no LDS, no barrier): the mask bits of all 128 dims sit in two
+  // ballots; a lane's 8 dims are consecutive, so one byte of a ballot holds their bits and the
+  // rank of its first dim is a population count below it
+  uint32_t sc_off[8];   // where each of the thread's 8 dims goes inside a buffer (bytes)
   {
-    uint64_t bal[2];
+    const uint64_t bal0 = __ballot(mb[0] != 0), bal1 = __ballot(mb[1] != 0);
+    const int d0 = ch * 8;                                   // first dim of this lane
+    const uint64_t word = d0 < 64 ? bal0 : bal1;
+    const uint32_t bits = static_cast<uint32_t>(word >> (d0 & 63)) & 0xffu;
+    const int below0 = __popcll(word & ((1ull << (d0 & 63)) - 1ull)) + (d0 < 64 ? 0 : __popcll(bal0));
 #pragma unroll
-    for (int j = 0; j < 2; ++j) bal[j] = __ballot(mb[j] != 0);
-    if (tid < D) {
-      const int w = tid >> 6;
-      const uint64_t bit = 1ull << (tid & 63);
-      const int nc = __popcll(bal[0] & (w ? ~0ull : bit - 1ull)) + (w ? __popcll(bal[1] & (bit - 1ull)) : 0);
-      const bool hit = (bal[w ? 1 : 0] & bit) != 0;
-      cpos[tid] = hit ? static_cast<int16_t>(-(1 + nc)) : static_cast<int16_t>(tid - nc);
+    for (int e = 0; e < 8; ++e) {
+      const int nc = below0 + __popc(bits & ((1u << e) - 1u));   // compressed dims below dim d0 + e
+      const bool hit = (bits >> e) & 1u;
+      if (hit) sc_off[e] = (static_cast<uint32_t>(nc) * kFP + TOK * quad) * 2;
+      else if (write_keep) sc_off[e] = ks_off + (static_cast<uint32_t>(d0 + e - nc) * kFP + TOK * quad) * 2;
+      else sc_off[e] = ks_off + static_cast<uint32_t>(kp) * kFP * 2;   // spare slot: the value is not needed
     }
   }
-  // unused columns / pad rows of the LDS tiles stay zero for the whole kernel
-  for (uint32_t it = tid; it < 2 * bufb / 16; it += kThreads)
-    reinterpret_cast<u32x4*>(smem)[it] = u32x4{0u, 0u, 0u, 0u};
+  FA_PSTAMP(25);
+  // The pad rows of the kept-dim staging tiles (dims Du .. kp-1, which leave as the zero pad of the
+  // rows layout) are zero for the whole kernel.  Nothing else needs clearing: every token of a used
+  // column is written before it is read, and columns past Dc only feed accumulator columns that
+  // are never stored (a matrix product keeps columns apart).
+  {
+    const uint32_t pad_words = static_cast<uint32_t>(kp - Du) * kFP / 2;   // 32-bit words per buffer
+    for (uint32_t it = tid; it < 2 * pad_words; it += kThreads) {
+      const uint32_t bsel = it >= pad_words ? 1u : 0u;
+      reinterpret_cast<uint32_t*>(smem + bsel * bufb + ks_off + static_cast<uint32_t>(Du) * kFP * 2)[it - bsel * pad_words] = 0u;
+    }
+  }
 
   Frag<T> ones;
   ones.v = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
@@ -605,25 +631,22 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   f32x4 acc_dc = {0.f, 0.f, 0.f, 0.f};   // rows are identical: the column sums of tile rgw
 
   T* keep = static_cast<T*>(p.keep) + static_cast<int64_t>(bh) * p.keep_stride;
-  __syncthreads();   // cpos and the zero fills are visible
-
-  // ---- where each of the thread's 8 dims goes inside a buffer (bytes) -----------------------
-  uint32_t sc_off[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int cp = cpos[ch * 8 + e];
-    if (cp < 0) sc_off[e] = (static_cast<uint32_t>(-cp - 1) * kFP + TOK * quad) * 2;
-    else if (write_keep) sc_off[e] = ks_off + (static_cast<uint32_t>(cp) * kFP + TOK * quad) * 2;
-    else sc_off[e] = ks_off + static_cast<uint32_t>(kp) * kFP * 2;   // spare slot: the value is not needed
-  }
+  FA_PSTAMP(26);
+  // (no barrier here: the first scatter touches no pad row, and the barrier after it also orders
+  // the zero fill before the first read of the staging tile)
   // ---- kept dims leave the staging tile as 128-bit stores: one or more vectors per thread ------
   // rows layout: vector (token jt, 8 dims 8 c8..): gathered from 8 tile rows; tok8 layout: vector
   // (dim, 8 tokens 8 g..): contiguous in the tile
   const int nvec = rows_layout ? kFB * (kp / 8) : Du * (kFB / 8);
   const int c8n = max(kp / 8, 1), dun = max(Du, 1);
   const int kv_0 = max(min(tid, nvec - 1), 0);                   // first vector of this thread
-  const int kv_a = rows_layout ? kv_0 / c8n : kv_0 / dun;        // token (rows) or 8-token group (tok8)
-  const int kv_b = rows_layout ? kv_0 - kv_a * c8n : kv_0 - kv_a * dun;   // 8-dim group (rows) or dim (tok8)
+  // (division by the layout's vectors per token / dims per group through the host's 16-bit reciprocal:
+  // exact for indices below 512 and divisors up to 64)
+  const int kv_d = rows_layout ? c8n : dun;
+  int kv_a;   // token (rows) or 8-token group (tok8)
+  if constexpr (KM >= 0) kv_a = static_cast<int>((static_cast<uint32_t>(kv_0) * p.kv_magic) >> 16);   // (one vector per thread: d <= 32)
+  else kv_a = kv_0 / kv_d;
+  const int kv_b = kv_0 - kv_a * kv_d;                           // 8-dim group (rows) or dim (tok8)
 
   FA_CSTAMP(1);
   auto scatter_block = [&](Frag<T> (&xr)[TOK], int blk) {   // this thread's 4 tokens x 8 dims of block blk -> LDS
@@ -1060,6 +1083,10 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
   p.keep_stride = keep_stride_bh; p.keep_offset = keep_offset; p.stage_keep = pl.stage;
   p.Sc = pl.Sc; p.chunk = pl.chunk; p.MC = pl.MC; p.DCn = pl.DCn; p.nmax = pl.nmax;
   p.ks_elems = pl.ks_elems;
+  {
+    const int kv_d = (keep_layout == FA_KEEP_ROWS) ? (keep_pitch / 8 > 0 ? keep_pitch / 8 : 1) : (Du > 0 ? Du : 1);
+    p.kv_magic = static_cast<uint32_t>((65536 + kv_d - 1) / kv_d);
+  }
   p.ph_scale = 4294967296.0 / static_cast<double>(T);
   p.part = static_cast<float*>(workspace);
   p.part_stride = (static_cast<size_t>(B) * H * M * Dc + 3) & ~size_t(3);
