@@ -903,6 +903,45 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
     // step ends with a block of zeros, which belongs to the last pair)
     const int last_even = (nb - 1) & ~1;
     const uint32_t ph_last = fixed_phase(p.t0 + j0 + last_even * kFB, p.ph_scale);
+    // Rows whose length is a multiple of 4 leave as 128-bit stores: a lane owns 4 ROWS of one column,
+    // so each 16-row tile set goes through a wave-private piece of LDS (the token tiles are done
+    // with) and comes back as 4 consecutive columns of one row per lane.
+    if ((p.Dc & 3) == 0 && !add) {
+      constexpr int P = DT * 16 + 4;   // floats per LDS row: keeps the 4-row groups of a write on distinct banks
+      float* ep = reinterpret_cast<float*>(smem) + wave * (16 * P);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+          const int n = mc * kPairs + ((rgw * 16 * MT + mt * 16 + 4 * q4) >> 1) + pr + 1;
+          float c, sn;
+          fixed_phase_cs<T>(static_cast<uint32_t>(n) * ph_last, &c, &sn);   // (rows past the highest harmonic are not stored)
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) {
+            const float ac = acc[mt][dt][2 * pr], as = acc[mt][dt][2 * pr + 1];
+            ep[(4 * q4 + 2 * pr) * P + dt * 16 + r16] = c * ac - sn * as;
+            ep[(4 * q4 + 2 * pr + 1) * P + dt * 16 + r16] = sn * ac + c * as;
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wave's LDS writes before its reads
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int k = 0; k < DT; ++k) {   // 16 rows x 4 DT vectors = DT per lane
+          const int v = lane + 64 * k;
+          const int row = v / (DT * 4), c4 = v - row * (DT * 4);
+          const int rho = rgw * 16 * MT + mt * 16 + row;
+          const int n = mc * kPairs + (rho >> 1) + 1;
+          const int m = (rho & 1) ? 2 * n : 2 * n - 1;
+          const f32x4 val = *reinterpret_cast<const f32x4*>(ep + row * P + 4 * c4);
+          if (n <= p.nmax && m < M && 4 * c4 < p.Dc)
+            *reinterpret_cast<f32x4*>(dst + static_cast<size_t>(m) * p.Dc + 4 * c4) = val;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+      }
+      FA_CSTAMP(31);
+      return;
+    }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
