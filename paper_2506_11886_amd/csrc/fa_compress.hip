@@ -27,7 +27,7 @@
 
 namespace fa {
 
-constexpr int kCBlock = 512;      // 8 waves: 4 row groups of 64 basis rows x 2 column halves
+constexpr int kCBlock = 512;      // 8 waves (generic kernel: 4 row groups of 64 basis rows x 2 column halves)
 constexpr int kTB = 64;          // tokens per block
 constexpr int kLdX = kTB + 8;    // LDS pitch (elements) of a transposed column: 16-byte aligned, bank-spread
 constexpr int kPairs = 128;      // harmonics per workgroup (256 basis rows)
@@ -457,9 +457,11 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
 // Same decomposition as compress_project, specialised for the common shape.  A thread
 // loads 8 dims of 4 consecutive tokens, so that every dim leaves as ONE 64-bit LDS
 // write into the transposed tiles (compressed dims: MFMA B operands; kept dims: a
-// staging tile in the same [dim][token] layout that serves both output layouts).  The
-// frame moves once per 128 tokens, the constant function rides on the matrix cores as
-// a row of ones, and all addressing is decided before the loop.
+// staging tile in the same [dim][token] layout that serves both output layouts).  Each
+// of the 8 waves owns 32 basis rows and all compressed columns; it holds the basis of a
+// PAIR of blocks (256 tokens) in registers, so the frame moves once per 256 tokens.  The
+// constant function rides on the matrix cores as a row of ones, and all addressing is
+// decided before the loop.
 constexpr int kFB = 128;            // tokens per block
 constexpr int kFP = kFB + 8;        // LDS pitch (elements) of a transposed column
 constexpr int kFK = kFB / 32;       // 32-token contraction steps per block
@@ -530,10 +532,10 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
 
   // ---- per-wave constants: E fragments (A operand) and frame twiddles -------------------
   const int rows_here = 2 * min(kPairs, p.nmax - mc * kPairs);   // live basis rows of this row block
-  const int rgw = wave % RG, chw = wave / RG;      // row group (16 MT basis rows), column half of this wave
+  const int rgw = wave % RG, chw = wave / RG;      // row group (16 MT basis rows), column group (always 0 for CH = 1)
   const int ndt = (p.Dc + 15) / 16 - chw * DT;     // live column tiles of this wave (may be <= 0)
   const bool wave_live = project && rgw * 16 * MT < rows_here && ndt > 0;
-  const bool wave_dc = do_dc && rgw < ndt && rgw < DT;   // this wave sums column tile rgw of its half
+  const bool wave_dc = do_dc && rgw < ndt && rgw < DT;   // this wave sums column tile rgw
 
   // Two basis sets: tokens 0..127 and 128..255 of a pair of blocks.  The frame then moves once per
   // PAIR of blocks (by 256 tokens), which halves the turning arithmetic per token.
@@ -674,7 +676,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
         }
     }
   };
-  auto keep_out = [&](int blk) {   // this half's share of the kept dims of block blk: tile -> 128-bit stores
+  auto keep_out = [&](int blk) {   // kept dims of block blk: staging tile -> 128-bit stores (general step)
     const int js = j0 + blk * kFB;
     const T* ks = reinterpret_cast<const T*>(smem + (blk & 1) * bufb + ks_off);
     const int64_t tok0 = static_cast<int64_t>(p.keep_offset) + js;
@@ -743,7 +745,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) mma_k32(acc[mt][dt], ea[kOdd][mt][ksx], cur[ksx]);
       }
-      // constant function: a row of ones against column tile rgw of this wave's half
+      // constant function: a row of ones against column tile rgw
       if (wave_dc && dt == rgw) {
 #pragma unroll
         for (int ksx = 0; ksx < kFK; ++ksx) mma_k32(acc_dc, ones, cur[ksx]);
@@ -865,9 +867,9 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
     __syncthreads();
     FA_CSTAMP(5 + 4 * blk);
   };
-  // Loads are issued where every wave passes (never inside the half-specific branches, where the
-  // result would have to be merged with the other path, i.e. waited for): once both halves have
-  // scattered a register set, the block two ahead is requested into it.
+  // Loads are issued where every wave passes, never under a condition (the result would have to be
+  // merged with the other path, i.e. waited for at once): as soon as a register set has been
+  // scattered, the block two ahead is requested into it.
   scatter_block(xra, 0);
   load_x(xra, 2);
   __syncthreads();
