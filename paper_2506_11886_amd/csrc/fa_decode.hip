@@ -29,7 +29,7 @@
 //      chunks of middle rows and chunks of full-width sink/window rows; emits
 //      a flash-decoding partial per query head: (max, sum, acc[kept dims],
 //      r[Mint]) for middle rows, (max, sum, acc[D]) for full-width rows.
-//   3. decode_finish  : one workgroup per query head merges the partials,
+//   3. decode_finish  : a few workgroups per query head (one per slice of output dims) merge the partials,
 //      applies diag(w) C_v to r and normalises.
 
 #include <cstdlib>
@@ -1155,9 +1155,10 @@ __global__ __launch_bounds__(kBlock, (CW <= 2 && sizeof(T) == 2) ? 2 : 1) void d
 // records (replicated work, a few tens of KB), then finishes its own dims: kept
 // dims from the accumulators, compressed dims from r and its columns of C_v.
 // Nothing is exchanged between workgroups.
-constexpr int kFinDims = 32;   // output dims per workgroup
-
-template <typename T>
+// kFinDims: output dims per workgroup.  Every workgroup of a head re-reads the head's statistics and
+// series sums, so few wide slices read less and many narrow slices fill the chip sooner: 32 dims
+// when there are few query heads, 64 once the heads alone give enough workgroups.
+template <typename T, int kFinDims>
 __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
   constexpr int kNW = kFinBlock / 64;
   constexpr int kSP = kMaxPartials / kFinBlock;   // records per thread when reading statistics
@@ -1521,7 +1522,11 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
   }
 #undef FA_LAUNCH_PARTIAL
   if (rc != FA_OK) return rc;
-  FA_LAUNCH_TIMED(tm, 2, decode_finish<T>, dim3((p.D + kFinDims - 1) / kFinDims, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
+  if (static_cast<long>(p.B) * p.Hq >= 256) {
+    FA_LAUNCH_TIMED(tm, 2, (decode_finish<T, 64>), dim3((p.D + 63) / 64, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
+  } else {
+    FA_LAUNCH_TIMED(tm, 2, (decode_finish<T, 32>), dim3((p.D + 31) / 32, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
+  }
   return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
 }
 
