@@ -47,6 +47,8 @@ __all__ = [
     "compress_batched",
     "decode_batched",
     "append_token",
+    "reconstruction_mse",
+    "select_dims",
 ]
 
 
@@ -210,3 +212,33 @@ def append_token(Ck, Cv, kmask, vmask, k_keep, v_keep, k_full, v_full, slot: int
     k_full[slot] = np.asarray(k_new, dtype=np.float64)
     v_full[slot] = np.asarray(v_new, dtype=np.float64)
     return Ck, Cv, k_keep, v_keep, k_full, v_full
+
+
+def reconstruction_mse(X, M: int) -> np.ndarray:
+    """Section 3.4: per head dimension, the mean squared error of compressing the
+    whole segment onto the first M basis functions and rebuilding it (Eq. 3 then
+    Eq. 6), with the segment spanning exactly one period (T = N, t0 = 0).
+
+    X [N, d] -> mse [d].  Written as the definition: compress every dim, rebuild
+    every row, subtract.
+    """
+    X = np.asarray(X, dtype=np.float64)
+    N, d = X.shape
+    ones = np.ones(d, dtype=np.uint8)
+    C, keep = compress_segment(X, ones, M, N, 0)
+    Xr = reconstruct_segment(C, keep, ones, N, 0, N)
+    return np.mean((X - Xr) ** 2, axis=0)
+
+
+def select_dims(X, M: int, Dc: int):
+    """Section 3.4: the Dc head dimensions with the lowest reconstruction error are
+    the ones to compress.  Equal errors go to the lower dimension index.
+
+    Returns (mask uint8 [d] with Dc ones, mse [d]).
+    """
+    mse = reconstruction_mse(X, M)
+    order = np.argsort(mse, kind="stable")
+    mask = np.zeros(mse.shape[0], dtype=np.uint8)
+    mask[order[:Dc]] = 1
+    return mask, mse
+

@@ -436,3 +436,75 @@ def test_append_token_without_eviction_only_fills_the_window():
     assert np.array_equal(out[2], kk) and np.array_equal(out[3], vk)
     assert np.array_equal(out[4][4], kn) and np.array_equal(out[5][4], vn)
     assert np.array_equal(np.delete(out[4], 4, axis=0), np.delete(k_full, 4, axis=0))
+
+
+# --------------------------------------------------------------------------
+# dimension selection (Section 3.4)
+# --------------------------------------------------------------------------
+
+def _mse_from_fft(X, M):
+    """Independent route to the reconstruction error: with the segment spanning one period the
+    first M real basis functions span the DC bin and the lowest complex bins of numpy's FFT, so
+    the error is the energy of the discarded bins (Parseval), no basis matrix involved."""
+    N = X.shape[0]
+    F = np.fft.rfft(X, axis=0)                      # bins 0 .. N//2
+    power = np.abs(F) ** 2
+    power[1:(N + 1) // 2] *= 2.0                    # bins with a conjugate twin count twice
+    kept = np.zeros(F.shape[0])
+    nfull = (M - 1) // 2                            # orders with both cosine and sine kept
+    kept[: nfull + 1] = 1.0
+    err = (power * (1.0 - kept)[:, None]).sum(axis=0) / N
+    if M % 2 == 0:                                  # one more cosine without its sine
+        n = M // 2
+        if 2 * n == N:                              # the Nyquist bin is real: its cosine is all of it
+            err -= power[n] / N
+        else:
+            err -= 2.0 * F[n].real ** 2 / N         # cosine part of bin n (half of the doubled power)
+    return err / N
+
+
+def test_reconstruction_mse_is_the_energy_of_the_discarded_fft_bins():
+    rng = np.random.default_rng(5)
+    for N, M in ((64, 9), (64, 10), (50, 50), (50, 49), (37, 1), (128, 64), (33, 33)):
+        X = rng.standard_normal((N, 5))
+        got = fk.reconstruction_mse(X, M)
+        want = _mse_from_fft(X, M)
+        assert np.allclose(got, want, rtol=1e-9, atol=1e-12), (N, M, got, want)
+
+
+def test_select_dims_picks_the_band_limited_dimensions():
+    rng = np.random.default_rng(6)
+    N, d, M = 240, 12, 17
+    t = np.arange(N)
+    X = rng.standard_normal((N, d))
+    smooth = [1, 4, 5, 9]
+    for i, dim in enumerate(smooth):                # in-band tones (orders <= 8) plus a little noise
+        X[:, dim] = np.cos(2 * np.pi * (i + 1) * t / N + 0.3 * i) + 0.5 * np.sin(2 * np.pi * (i + 3) * t / N) \
+            + 0.01 * rng.standard_normal(N)
+    mask, mse = fk.select_dims(X, M, len(smooth))
+    assert sorted(np.flatnonzero(mask)) == smooth
+    assert mse[smooth].max() < 2e-4 and np.delete(mse, smooth).min() > 0.5
+    # ties go to the lower index, and the count is exact
+    Z = np.zeros((N, 6))
+    m0, e0 = fk.select_dims(Z, M, 4)
+    assert m0.tolist() == [1, 1, 1, 1, 0, 0] and not e0.any()
+    assert fk.select_dims(X, M, 0)[0].sum() == 0 and fk.select_dims(X, M, d)[0].sum() == d
+
+
+def test_reconstruction_mse_brute_force_tiny():
+    rng = np.random.default_rng(7)
+    N, M = 7, 4
+    X = rng.standard_normal((N, 2))
+    want = np.zeros(2)
+    for dcol in range(2):
+        x = X[:, dcol]
+        # plain loops: coefficients, weights, rebuilt samples
+        fn = [lambda j: 1.0,
+              lambda j: math.cos(2 * math.pi * j / N), lambda j: math.sin(2 * math.pi * j / N),
+              lambda j: math.cos(4 * math.pi * j / N)]
+        c = [sum(f(j) * x[j] for j in range(N)) for f in fn]
+        w = [1.0 / N, 2.0 / N, 2.0 / N, 2.0 / N]
+        for j in range(N):
+            xr = sum(w[m] * c[m] * fn[m](j) for m in range(M))
+            want[dcol] += (x[j] - xr) ** 2 / N
+    assert np.allclose(fk.reconstruction_mse(X, M), want, rtol=1e-12, atol=1e-14)
