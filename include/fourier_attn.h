@@ -2,7 +2,7 @@
  * fourier_attn.h -- C ABI of the MI355X (gfx950) FourierAttention hot path.
  *
  * Three operations of the paper's Section 3.3 ("Online Compression via
- * HiPPO-FourierT"):
+ * HiPPO-FourierT") and the calibration step of Section 3.4:
  *
  *   fa_compress  Eq. 1-4 (and Eq. 5 when `accumulate` is set): split the head
  *                dimensions of a middle token segment of K or of V into
@@ -15,6 +15,8 @@
  *                the fly and never written to memory.
  *   fa_append    Eq. 5: the per-token update between two decode steps (the
  *                token leaving the recent window is folded into the state).
+ *   fa_select_dims  Section 3.4: rank the head dimensions of a segment by
+ *                their reconstruction error and mark the Dc best for compression.
  *
  * Conventions shared by every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
@@ -168,6 +170,38 @@ int fa_append(const void* k_new, const void* v_new, int dtype,
               float* ck, float* cv,
               void* k_keep, int64_t kk_stride_bh, void* v_keep, int64_t vk_stride_bh,
               void* hip_stream);
+
+/*
+ * fa_select_dims -- which head dimensions to compress (paper, Section 3.4).
+ *
+ * Every head dimension of the segment x[b,h] ([N, D], the middle rows of K or of V)
+ * is compressed onto the first M basis functions and rebuilt (Eq. 3, then Eq. 6)
+ * with the segment spanning exactly one period (T = N, positions 0 .. N-1);
+ *     mse[b,h,d] = (1/N) sum_j ( x[j,d] - rebuilt[j,d] )^2 ,
+ * and dim_mask[b,h,d] = 1 for the Dc dimensions of lowest mse (equal errors go to
+ * the lower dimension index), 0 for the others: the mask fa_compress / fa_decode /
+ * fa_append take.  Over one period the basis is orthogonal, so the error is
+ * evaluated as (sum_j x^2 - sum_m w_m C[m,d]^2) / N from fp32 coefficients (bf16
+ * segments are widened first); results below ~1e-5 of a dimension's mean square
+ * are rounding noise and rank arbitrarily among themselves.
+ *
+ *   x         DEVICE, dtype elements, element strides as for fa_compress (rows
+ *             16-byte aligned); read only
+ *   M, Dc     1 <= M <= N; 0 <= Dc <= D
+ *   dim_mask  DEVICE uint8 [B, H, D], written
+ *   mse       DEVICE fp32 [B, H, D], written; may be NULL
+ *   workspace DEVICE, 256-byte aligned, >= fa_select_workspace_bytes(...) bytes
+ *             (holds the fp32 copy of a bf16 segment: 4*B*H*N*D bytes, the
+ *             coefficients of all dims and the workspace of the projection)
+ * Asynchronous on hip_stream; nothing is allocated.  Same limits as fa_compress.
+ * Returns FA_OK or an FA_ERR_* code (arguments are checked on the host first).
+ */
+size_t fa_select_workspace_bytes(int dtype, int B, int H, int N, int D, int M);
+int fa_select_dims(const void* x, int dtype,
+                   int64_t sx_b, int64_t sx_h, int64_t sx_n,
+                   int B, int H, int N, int D, int M, int Dc,
+                   uint8_t* dim_mask, float* mse,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Measurement aids.  Same arguments and effect as fa_compress / fa_decode, but

@@ -53,6 +53,10 @@ def _load(path: str = _LIB_PATH):
     lib.fa_append.restype = i32
     lib.fa_append.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i64, i32, i32,
                               vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, i64, vp, i64, vp]
+    lib.fa_select_workspace_bytes.restype = sz
+    lib.fa_select_workspace_bytes.argtypes = [i32] * 6
+    lib.fa_select_dims.restype = i32
+    lib.fa_select_dims.argtypes = [vp, i32, i64, i64, i64, i32, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.fa_status_string.restype = c.c_char_p
     lib.fa_status_string.argtypes = [i32]
     return lib
@@ -204,3 +208,25 @@ def fa_append(k_new, v_new, k_full, v_full, slot, evict, kmask=None, vmask=None,
                        _stream_ptr(stream))
     if st != FA_OK:
         raise FourierAttnError(st, "fa_append")
+
+
+def select_workspace_bytes(dtype_code, B, H, N, D, M) -> int:
+    return int(lib.fa_select_workspace_bytes(dtype_code, B, H, N, D, M))
+
+
+def fa_select_dims(x, M, Dc, want_mse=True, workspace=None, stream=None):
+    """Enqueue fa_select_dims on `stream` for x [B,H,N,D]; returns (dim_mask uint8 [B,H,D],
+    mse fp32 [B,H,D] or None)."""
+    B, H, N, D = x.shape
+    dev = x.device
+    mask = torch.empty((B, H, D), dtype=torch.uint8, device=dev)
+    mse = torch.empty((B, H, D), dtype=torch.float32, device=dev) if want_mse else None
+    if workspace is None:
+        need = select_workspace_bytes(_dtype_code(x), B, H, N, D, M)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    st = lib.fa_select_dims(_ptr(x), _dtype_code(x), x.stride(0), x.stride(1), x.stride(2), B, H, N, D, M, Dc,
+                            _ptr(mask), _ptr(mse), _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    if st != FA_OK:
+        raise FourierAttnError(st, "fa_select_dims")
+    return mask, mse
+

@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(fa_[a-z_0-9]+)\s*\(", hdr))
     assert {"fa_compress", "fa_decode", "fa_compress_workspace_bytes",
             "fa_decode_workspace_bytes", "fa_decode_default_splits", "fa_status_string",
-            "fa_append"} <= names
+            "fa_append", "fa_select_dims", "fa_select_workspace_bytes"} <= names
     for n in names:
         assert hasattr(fa.lib, n), n
 
@@ -109,3 +109,26 @@ def test_append_rejects_bad_arguments_on_the_host():
     assert call(ck=None) == -1
     assert call(dtype=7) == -3
     assert call(kks=5) == -2             # slab too small for n_mid + 1 rows
+
+
+def test_select_rejects_bad_arguments_on_the_host():
+    fa = _fa()
+    a = dict(x=FAKE, dtype=1, sb=8 * 300 * 64, sh=300 * 64, sn=64, B=1, H=8, N=300, D=64, M=32, Dc=48,
+             mask=FAKE, mse=None, ws=FAKE, ws_bytes=0, stream=None)
+
+    def call(**kw):
+        d = dict(a, **kw)
+        return fa.lib.fa_select_dims(d["x"], d["dtype"], d["sb"], d["sh"], d["sn"], d["B"], d["H"], d["N"],
+                                     d["D"], d["M"], d["Dc"], d["mask"], d["mse"], d["ws"], d["ws_bytes"],
+                                     d["stream"])
+    assert call(M=301) == -2             # more basis functions than positions in the period
+    assert call(Dc=65) == -2
+    assert call(D=60, sn=60) == -3
+    assert call(dtype=3) == -3
+    assert call(x=None) == -1
+    assert call(mask=None) == -1
+    assert call(sn=60) == -2             # rows overlap
+    assert call() == -4                  # workspace too small
+    assert fa.select_workspace_bytes(1, 1, 8, 300, 64, 32) > 4 * 8 * 300 * 64
+    assert fa.select_workspace_bytes(0, 1, 8, 300, 64, 32) < fa.select_workspace_bytes(1, 1, 8, 300, 64, 32)
+

@@ -240,3 +240,59 @@ def test_append_without_eviction_only_writes_the_row():
     assert torch.equal(k_full[:, :, 5], kn) and torch.equal(v_full[:, :, 5], vn)
     assert not k_full[:, :, :5].any() and not k_full[:, :, 6:].any()
     assert (v_full[:, :, :5] == 1).all() and (v_full[:, :, 6:] == 1).all()
+
+
+# --------------------------------------------------------------------------
+# dimension selection (Section 3.4)
+# --------------------------------------------------------------------------
+
+def _select_case(cfg, M, nheads=None):
+    """The synthetic law plants in-band sinusoids (plus a little noise) in the masked dims of every
+    head and white noise elsewhere, so selection with Dc = the mask's count must return the mask."""
+    import oracle.fourier_kv as fk
+    fa = _fa()
+    ctx = cached_context(cfg)
+    x = to_dev(ctx["k_mid"], cfg)
+    mask, mse = fa.fa_select_dims(x, M, cfg.Dkc)
+    torch.cuda.synchronize()
+    mask, mse = mask.cpu().numpy(), mse.cpu().numpy()
+    xh = x.float().cpu().numpy().astype(np.float64)     # what the kernel saw (bf16 already rounded)
+    for b, h in sample_heads(cfg, nheads):
+        want_mask, want_mse = fk.select_dims(xh[b, h], M, cfg.Dkc)
+        scale = np.mean(xh[b, h] ** 2, axis=0)          # mean square of each dim
+        assert np.all(np.abs(mse[b, h] - want_mse) <= 2e-5 * scale + 1e-12), (b, h, np.abs(mse[b, h] - want_mse).max())
+        assert mask[b, h].sum() == cfg.Dkc
+        # the selected set is unique wherever the errors are separated by more than the rounding floor
+        order = np.argsort(want_mse, kind="stable")
+        if 0 < cfg.Dkc < cfg.D:
+            gap = want_mse[order[cfg.Dkc]] - want_mse[order[cfg.Dkc - 1]]
+            if gap > 1e-4 * scale.max():
+                assert np.array_equal(mask[b, h], want_mask), (b, h)
+        else:
+            assert np.array_equal(mask[b, h], want_mask), (b, h)
+        if M == cfg.M and 0 < cfg.Dkc < cfg.D:           # the planted dims are the ones to compress
+            assert np.array_equal(mask[b, h], ctx["kmask"][b, h]), (b, h)
+
+
+@pytest.mark.parametrize("name", ["tiny", "gqa8_oddM", "odd_dims", "wide_d256_f32", "all_compress_bf16", "no_compress"])
+def test_select_dims_matches_oracle(name):
+    cfg = next(c for c in SMALL if c.name == name)
+    print(f"[case] select {cfg}", flush=True)
+    _select_case(cfg, cfg.M)
+
+
+def test_select_dims_ties_go_to_the_lower_index():
+    fa = _fa()
+    x = torch.zeros((1, 2, 64, 32), dtype=torch.bfloat16, device="cuda")
+    mask, mse = fa.fa_select_dims(x, 5, 7)
+    torch.cuda.synchronize()
+    assert not mse.any().item()
+    assert mask.cpu().numpy().tolist() == [[[1] * 7 + [0] * 25] * 2]
+
+
+def test_select_dims_full_size():
+    """The bench workload's K segment (31740 tokens, 128 dims, M = 256), two sampled heads."""
+    cfg = CONFIGS[1]
+    print(f"[case] select full size {cfg}", flush=True)
+    _select_case(cfg, cfg.M, nheads=2)
+
