@@ -49,6 +49,9 @@ def parse_args():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch a converting copy of known size (bf16 -> fp32, 64 MiB read, "
                          "128 MiB written) three times: the yardstick that HBM counter runs are scaled by")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the calls outside the step: fa_append (one token per sequence and KV head) "
+                         "and fa_select_dims (the K segment) -> phases.append / phases.select")
     return ap.parse_args()
 
 
@@ -199,6 +202,36 @@ def main():
                          "roofline": roof_cmp},
         },
     }
+
+    if args.extras:
+        s0 = sets[0]
+        k_new = torch.randn((B, Hkv, D), device="cuda").to(dt)
+        v_new = torch.randn((B, Hkv, D), device="cuda").to(dt)
+        kk_ap = torch.zeros((B, Hkv, N + 64, fa.keep_rows_pitch(Dku)), dtype=dt, device="cuda")
+        vk_ap = torch.zeros((B, Hkv, fa.tok8_numel(N + 64, Dvu)), dtype=dt, device="cuda")
+        T_ap = T + 64
+
+        def append(i):   # evicting appends at successive middle positions (the state drifts: timing only)
+            fa.fa_append(k_new, v_new, s0["k_full"], s0["v_full"], cfg.Li + i % max(cfg.Lw, 1), cfg.Lw > 0,
+                         s0["kmask"], s0["vmask"], M, T_ap, N + i % 64, s0["ck"], s0["cv"], kk_ap, vk_ap)
+        if W > 0:
+            for i in range(8):
+                append(i)
+            t_app = timed_loop(append, min(args.steps, 64))
+            app_bytes = B * Hkv * (2 * M * (cfg.Dkc + cfg.Dvc) * 4 + 4 * D * (2 if dt == torch.bfloat16 else 4))
+            result["phases"]["append"] = {"ms": round(t_app * 1e3, 5), "algorithmic_bytes": app_bytes,
+                                          "GBps": round(app_bytes / t_app / 1e9, 1)}
+        if N >= M:
+            ws_s = torch.empty(max(256, fa.select_workspace_bytes(fa.FA_BF16 if dt == torch.bfloat16 else fa.FA_F32,
+                                                                  B, Hkv, N, D, M)), dtype=torch.uint8, device="cuda")
+            sel = lambda i: fa.fa_select_dims(sets[i % n_sets]["k_mid"], M, cfg.Dkc, workspace=ws_s)
+            for i in range(2):
+                sel(i)
+            t_sel = timed_loop(sel, max(4, min(args.steps, 20)))
+            sel_flop = 2.0 * B * Hkv * N * M * D
+            result["phases"]["select"] = {"ms": round(t_sel * 1e3, 5), "flop": sel_flop,
+                                          "fp32_matrix_tflops": round(sel_flop / t_sel / 1e12, 1),
+                                          "fp32_matrix_frac": round(sel_flop / t_sel / 1e12 / FP32_MATRIX_PEAK_TFLOPS, 4)}
 
     if args.copy_probe:
         src = torch.ones(32 << 20, dtype=torch.bfloat16, device="cuda")
