@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0
 # same counter reads for the --copy-probe kernel), keyed by (kernel, config index).
 # Source: profiles/bench_cfg*_hbm_traffic.txt; null for anything not measured there.
 MEASURED_TRAFFIC = {
-    ("compress_project", 2): 105918962,   # 65.29 MB read + 40.63 MB written (24.4 MB of it chunk partials)
+    ("compress_project", 2): 105890000,   # 65.26 MB read + 40.63 MB written (24.4 MB of it chunk partials)
     ("decode_partial", 2): 39249139,      # 37.57 MB read + 1.68 MB written (split-K partial records)
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0
