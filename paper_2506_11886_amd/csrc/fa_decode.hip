@@ -1234,11 +1234,37 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
   const int rk = (dme < D) ? dim_rank(vbal, dme) : 0;
   const bool is_c = dme < D && rk < 0, is_k = dme < D && rk >= 0;
   FA_FSTAMP(13);
-  // (4) compressed dim: its column of C_v, rows cg, cg + kCG, ...; kept dim: its accumulator column
-  constexpr int kUc = 64, kUk = 6;
-  const float* cvc = p.cv + static_cast<size_t>(bh) * M * Dvc + (is_c ? -rk - 1 : 0);
+  // (4) C_v.  The compressed dims of a slice have consecutive ranks r0 .. r0 + nc - 1, i.e. the slice
+  // needs a contiguous band of C_v's columns.  With Dvc a multiple of 4 the band is read as 128-bit
+  // vectors: thread (column quad cq, row group rg) takes rows rg, rg + ngrp, ...  Otherwise every
+  // thread reads its own dim's column element by element (rows cg, cg + kCG, ...).
+  constexpr int kUc = 64, kUk = 6, kUv = 16;
+  const bool vec_cv = do_cv && (Dvc & 3) == 0;
+  int r0 = 0, nc = 0;
+  {
+    const int w0 = d0 >> 6, sh = d0 & 63;   // kFinDims divides 64: the slice lies inside one ballot word
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (j < w0) r0 += __popcll(vbal[j]);
+      if (j == w0) {
+        r0 += __popcll(vbal[j] & ((1ull << sh) - 1ull));
+        nc = __popcll((vbal[j] >> sh) & (kFinDims == 64 ? ~0ull : ((1ull << kFinDims) - 1ull)));
+      }
+    }
+  }
+  const int q0 = r0 >> 2, nq = nc > 0 ? ((r0 + nc + 3) >> 2) - q0 : 1;   // column quads of the band
+  const int ngrp = kFinBlock / nq;                                       // row groups
+  const int rgv = tid / nq, cqv = tid - rgv * nq;
+  const float* cvb = p.cv + static_cast<size_t>(bh) * M * Dvc;
+  const float* cvc = cvb + (is_c ? -rk - 1 : 0);
   float cvv[kUc];
-  if (do_cv) {
+  f32x4 cv4[kUv];
+  if (vec_cv) {
+    const float* cq_ptr = cvb + 4 * min(q0 + cqv, Dvc / 4 - 1);
+#pragma unroll
+    for (int u = 0; u < kUv; ++u)
+      if (u * ngrp < M) cv4[u] = *reinterpret_cast<const f32x4*>(cq_ptr + static_cast<size_t>(min(rgv + u * ngrp, M - 1)) * Dvc);
+  } else if (do_cv) {
 #pragma unroll
     for (int u = 0; u < kUc; ++u)
       if (u * kCG < M) cvv[u] = cvc[static_cast<size_t>(min(cg + u * kCG, M - 1)) * Dvc];
@@ -1340,9 +1366,23 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
   FA_FSTAMP(3);
 
   // ---- per dim: sum_m rr[m] C_v[m, i] (compressed) or the merged accumulator (kept) ------------
+  if (vec_cv) {   // band of C_v: partial sums per (row group, column quad); red4 is free again
+    f32x4 o4 = {0.f, 0.f, 0.f, 0.f};
+    if (rgv < ngrp) {
+#pragma unroll
+      for (int u = 0; u < kUv; ++u) {
+        const int mm = rgv + u * ngrp;
+        if (mm < M) o4 += rr[mm] * cv4[u];
+      }
+      const float* cq_ptr = cvb + 4 * min(q0 + cqv, Dvc / 4 - 1);
+      for (int mm = rgv + kUv * ngrp; mm < M; mm += ngrp)
+        o4 += rr[mm] * *reinterpret_cast<const f32x4*>(cq_ptr + static_cast<size_t>(mm) * Dvc);
+    }
+    red4[tid] = o4;
+  }
   {
     float o = 0.0f;
-    if (do_cv && is_c) {
+    if (do_cv && is_c && !vec_cv) {
 #pragma unroll
       for (int u = 0; u < kUc; ++u) {
         const int mm = cg + u * kCG;
@@ -1365,6 +1405,11 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
     float v = outw[tid];
 #pragma unroll
     for (int g = 0; g < kCG; ++g) v += redc[g * kFinDims + tid];
+    if (vec_cv && is_c) {   // (tid < kFinDims: col == tid, so rk is this dim's rank)
+      const int c = (-rk - 1) - 4 * q0;
+      const float* src = reinterpret_cast<const float*>(red4) + 4 * (c >> 2) + (c & 3);
+      for (int g = 0; g < ngrp; ++g) v += src[4 * g * nq];
+    }
     p.out[static_cast<size_t>(hq) * D + d0 + tid] = v / L;
   }
   FA_FSTAMP(4);
@@ -1582,7 +1627,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   if ((vk_stride_bh % 8) || (full_stride_bh % 8) || (kk_stride_bh % 8)) return FA_ERR_SHAPE;
   if ((reinterpret_cast<uintptr_t>(k_keep) | reinterpret_cast<uintptr_t>(v_keep) |
        reinterpret_cast<uintptr_t>(k_full) | reinterpret_cast<uintptr_t>(v_full) |
-       reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(cv)) & 15u)
+       reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(cv) | reinterpret_cast<uintptr_t>(ck)) & 15u)
     return FA_ERR_SHAPE;
   // kernels index slabs with 32-bit element offsets
   if (kk_dense > 0x7fffffffLL || vk_dense > 0x7fffffffLL || full_dense > 0x7fffffffLL)
