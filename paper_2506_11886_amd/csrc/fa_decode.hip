@@ -260,13 +260,20 @@ __device__ __forceinline__ int dim_rank(const uint64_t* bal, int d) {
 // ---------------------------------------------------------------------------
 // 1. g = diag(w) C_k q_c, written in series order: slot s <-> basis function s+1
 // ---------------------------------------------------------------------------
-constexpr int kPrepLd = FA_MAX_HEAD_DIM + 4;       // LDS pitch of a C_k row (floats)
+// LDS of decode_prepare is sized by the launch (rows of C_k at a pitch of Dkc rounded up to 4, plus 4
+// floats; then the group's queries at the compressed dims), so that many workgroups fit a unit
+static inline int prep_pitch(int Dkc) { return ((Dkc + 3) & ~3) + 4; }
+static inline unsigned prep_lds_bytes(int rows, int G, int Dkc) {
+  return static_cast<unsigned>(rows * prep_pitch(Dkc) + ((G * Dkc + 3) & ~3)) * sizeof(float);
+}
 
 // kPrepRows: basis rows per workgroup (8 when the launch would otherwise not fill the chip, else 32)
 template <typename T, int kPrepRows>
 __global__ __launch_bounds__(kBlock) void decode_prepare(DecodeParams p) {
-  __shared__ float qc[kMaxG * FA_MAX_HEAD_DIM];            // [G][Dkc] query at the compressed dims
-  __shared__ __attribute__((aligned(16))) float crow[kPrepRows * kPrepLd];
+  extern __shared__ __attribute__((aligned(16))) unsigned char prep_smem[];
+  const int kPrepLd = ((p.Dkc + 3) & ~3) + 4;                          // LDS pitch of a C_k row (floats)
+  float* crow = reinterpret_cast<float*>(prep_smem);                   // [kPrepRows][kPrepLd]
+  float* qc = crow + kPrepRows * kPrepLd;                              // [G][Dkc] query at the compressed dims
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
@@ -1541,10 +1548,10 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
   if (p.Sm > 0) {
     if (static_cast<long>(BH) * ((p.Mint + 32) / 32) >= 512) {
       dim3 g1((p.Mint + 32) / 32, BH);
-      FA_LAUNCH_TIMED(tm, 0, (decode_prepare<T, 32>), g1, dim3(kBlock), 0, st, p);
+      FA_LAUNCH_TIMED(tm, 0, (decode_prepare<T, 32>), g1, dim3(kBlock), prep_lds_bytes(32, p.G, p.Dkc), st, p);
     } else {
       dim3 g1((p.Mint + 8) / 8, BH);
-      FA_LAUNCH_TIMED(tm, 0, (decode_prepare<T, 8>), g1, dim3(kBlock), 0, st, p);
+      FA_LAUNCH_TIMED(tm, 0, (decode_prepare<T, 8>), g1, dim3(kBlock), prep_lds_bytes(8, p.G, p.Dkc), st, p);
     }
   }
   int rc;
