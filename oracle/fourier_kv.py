@@ -49,6 +49,7 @@ __all__ = [
     "append_token",
     "reconstruction_mse",
     "select_dims",
+    "decode_multi_query",
 ]
 
 
@@ -241,4 +242,29 @@ def select_dims(X, M: int, Dc: int):
     mask = np.zeros(mse.shape[0], dtype=np.uint8)
     mask[order[:Dc]] = 1
     return mask, mse
+
+
+def decode_multi_query(q, Ck, kmask, Cv, vmask, T, t0, N,
+                       k_keep, v_keep, k_full, v_full, scale=None) -> np.ndarray:
+    """Eq. 6 for Tq consecutive query tokens of one KV head (chunked decoding / verification of
+    drafted tokens, the FlashAttention side of Section 3.3's kernel).
+
+    q [Tq, G, d].  The last Tq rows of k_full / v_full are the Tq new tokens in order; query t sees
+    every other row and the new tokens 0 .. t (causal among the new tokens, everything older is
+    visible to all).  Returns out [Tq, G, d]: each query is an ordinary single-query decode over
+    the rows it may see.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    Tq = q.shape[0]
+    k_full = np.asarray(k_full, np.float64)
+    v_full = np.asarray(v_full, np.float64)
+    W = k_full.shape[0]
+    if Tq < 1 or Tq > W:
+        raise ValueError("need 1 <= Tq <= number of full-width rows")
+    out = []
+    for t in range(Tq):
+        vis = W - Tq + t + 1
+        out.append(decode_head_group(q[t], Ck, kmask, Cv, vmask, T, t0, N, k_keep, v_keep,
+                                     k_full[:vis], v_full[:vis], scale))
+    return np.stack(out)
 

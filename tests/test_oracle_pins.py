@@ -508,3 +508,63 @@ def test_reconstruction_mse_brute_force_tiny():
             xr = sum(w[m] * c[m] * fn[m](j) for m in range(M))
             want[dcol] += (x[j] - xr) ** 2 / N
     assert np.allclose(fk.reconstruction_mse(X, M), want, rtol=1e-12, atol=1e-14)
+
+
+# --------------------------------------------------------------------------
+# several query tokens per step (causal among the new tokens)
+# --------------------------------------------------------------------------
+
+def _mq_case(seed=11, N=40, W=9, d=8, G=2, Tq=3, M=7):
+    rng = np.random.default_rng(seed)
+    kmask = (rng.random(d) < 0.5).astype(np.uint8)
+    vmask = (rng.random(d) < 0.5).astype(np.uint8)
+    K, V = rng.standard_normal((N, d)), rng.standard_normal((N, d))
+    Ck, kk = fk.compress_segment(K, kmask, M, N, 0)
+    Cv, vk = fk.compress_segment(V, vmask, M, N, 0)
+    kf, vf = rng.standard_normal((W, d)), rng.standard_normal((W, d))
+    q = rng.standard_normal((Tq, G, d))
+    return dict(q=q, Ck=Ck, kmask=kmask, Cv=Cv, vmask=vmask, T=N, t0=0, N=N, k_keep=kk, v_keep=vk,
+                k_full=kf, v_full=vf)
+
+
+def test_multi_query_decode_is_causal_among_the_new_tokens():
+    c = _mq_case()
+    base = fk.decode_multi_query(**c)
+    Tq, W = c["q"].shape[0], c["k_full"].shape[0]
+    # one query token = the ordinary decode over all rows
+    one = fk.decode_multi_query(**dict(c, q=c["q"][-1:]))
+    assert np.allclose(one[0], fk.decode_head_group(c["q"][-1], c["Ck"], c["kmask"], c["Cv"], c["vmask"], c["T"], 0,
+                                                    c["N"], c["k_keep"], c["v_keep"], c["k_full"], c["v_full"]))
+    # the last query sees everything: same as the ordinary decode too
+    assert np.allclose(base[-1], one[0])
+    # changing new token t leaves the outputs of queries < t untouched and changes query t
+    for t in range(1, Tq):
+        kf2, vf2 = c["k_full"].copy(), c["v_full"].copy()
+        kf2[W - Tq + t] += 1.0
+        vf2[W - Tq + t] -= 2.0
+        alt = fk.decode_multi_query(**dict(c, k_full=kf2, v_full=vf2))
+        assert np.array_equal(alt[:t], base[:t])
+        assert not np.allclose(alt[t], base[t])
+    # an older row is visible to every query
+    kf3 = c["k_full"].copy()
+    kf3[0] += 3.0
+    alt = fk.decode_multi_query(**dict(c, k_full=kf3))
+    assert all(not np.allclose(alt[t], base[t]) for t in range(Tq))
+
+
+def test_multi_query_decode_brute_force():
+    c = _mq_case(seed=12, N=12, W=5, d=4, G=1, Tq=2, M=5)
+    got = fk.decode_multi_query(**c)
+    Km = fk.reconstruct_segment(c["Ck"], c["k_keep"], c["kmask"], c["T"], 0, c["N"])
+    Vm = fk.reconstruct_segment(c["Cv"], c["v_keep"], c["vmask"], c["T"], 0, c["N"])
+    W, Tq, d = 5, 2, 4
+    for t in range(Tq):
+        rows_k = [c["k_full"][j] for j in range(W) if j <= W - Tq + t] + [Km[j] for j in range(c["N"])]
+        rows_v = [c["v_full"][j] for j in range(W) if j <= W - Tq + t] + [Vm[j] for j in range(c["N"])]
+        s = [sum(c["q"][t, 0, i] * rk[i] for i in range(d)) / math.sqrt(d) for rk in rows_k]
+        mx = max(s)
+        e = [math.exp(x - mx) for x in s]
+        z = sum(e)
+        want = [sum(e[j] / z * rows_v[j][i] for j in range(len(e))) for i in range(d)]
+        assert np.allclose(got[t, 0], want, rtol=1e-12, atol=1e-14)
+
