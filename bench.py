@@ -225,6 +225,23 @@ def main():
             app_bytes = B * Hkv * (2 * M * (cfg.Dkc + cfg.Dvc) * 4 + 4 * D * (2 if dt == torch.bfloat16 else 4))
             result["phases"]["append"] = {"ms": round(t_app * 1e3, 5), "algorithmic_bytes": app_bytes,
                                           "GBps": round(app_bytes / t_app / 1e9, 1)}
+        Tq = max(1, 16 // (Hq // Hkv))
+        if Tq > 1 and W >= Tq:   # as many query tokens per step as the group limit allows
+            q_mq = torch.randn((B, Hkv, Tq, Hq // Hkv, D), device="cuda").to(dt)
+            out_mq = torch.empty((B, Hkv, Tq, Hq // Hkv, D), dtype=torch.float32, device="cuda")
+            ws_mq = torch.empty(max(256, fa.decode_workspace_bytes(B, Hq * Tq, Hkv, D, cfg.Dkc, cfg.Dvc, M, N, W,
+                                                                   cfg.num_splits)), dtype=torch.uint8, device="cuda")
+
+            def decode_mq(i):
+                s = sets[i % n_sets]
+                fa.fa_decode_mq(q_mq, s["ck"], s["kmask"], s["cv"], s["vmask"], M, T, 0, N, s["kk"], s["vk"],
+                                s["k_full"], s["v_full"], num_splits=cfg.num_splits, out=out_mq, workspace=ws_mq)
+            for i in range(4):
+                decode_mq(i)
+            t_mq = timed_loop(decode_mq, args.steps)
+            result["phases"]["decode_mq"] = {"query_tokens": Tq, "ms": round(t_mq * 1e3, 5),
+                                             "ms_per_query_token": round(t_mq * 1e3 / Tq, 5),
+                                             "call_GBps": round(dec_bytes / t_mq / 1e9, 1)}
         if N >= M:
             ws_s = torch.empty(max(256, fa.select_workspace_bytes(fa.FA_BF16 if dt == torch.bfloat16 else fa.FA_F32,
                                                                   B, Hkv, N, D, M)), dtype=torch.uint8, device="cuda")

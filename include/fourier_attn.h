@@ -15,6 +15,8 @@
  *                the fly and never written to memory.
  *   fa_append    Eq. 5: the per-token update between two decode steps (the
  *                token leaving the recent window is folded into the state).
+ *   fa_decode_mq    the same for several consecutive query tokens (causal
+ *                among themselves).
  *   fa_select_dims  Section 3.4: rank the head dimensions of a segment by
  *                their reconstruction error and mark the Dc best for compression.
  *
@@ -170,6 +172,31 @@ int fa_append(const void* k_new, const void* v_new, int dtype,
               float* ck, float* cv,
               void* k_keep, int64_t kk_stride_bh, void* v_keep, int64_t vk_stride_bh,
               void* hip_stream);
+
+/*
+ * fa_decode_mq -- fa_decode for Tq consecutive query tokens per sequence (paper,
+ * Section 3.3: the FlashAttention side of the fused kernel; chunked decoding or
+ * the verification of drafted tokens).
+ *
+ * Same arguments, layouts and limits as fa_decode, except:
+ *   q, out    [B, Hkv, Tq, G, D] (G = Hq / Hkv): the queries of one KV head are
+ *             contiguous, token-major.  With Tq = 1 this is fa_decode's [B, Hq, D].
+ *   k_full, v_full   the LAST Tq of the W rows are the Tq new tokens, in order;
+ *             query token t sees every other row, every middle row, and new
+ *             tokens 0 .. t (causal among the new tokens).  1 <= Tq <= W.
+ *   Tq * G <= 16 (the group limit of fa_decode applies to tokens x heads).
+ *   workspace >= fa_decode_workspace_bytes(B, Tq * Hq, Hkv, ...).
+ * The middle rows and the older full-width rows are read once for all Tq tokens.
+ */
+int fa_decode_mq(const void* q, int dtype, int B, int Tq, int Hq, int Hkv, int D,
+                 const float* ck, const uint8_t* kmask, int Dkc,
+                 const float* cv, const uint8_t* vmask, int Dvc,
+                 int M, int T, int t0, int N,
+                 const void* k_keep, int64_t kk_stride_bh,
+                 const void* v_keep, int64_t vk_stride_bh,
+                 const void* k_full, const void* v_full, int W, int64_t full_stride_bh,
+                 float scale, int num_splits, float* out,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * fa_select_dims -- which head dimensions to compress (paper, Section 3.4).

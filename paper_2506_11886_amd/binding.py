@@ -53,6 +53,10 @@ def _load(path: str = _LIB_PATH):
     lib.fa_append.restype = i32
     lib.fa_append.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i64, i32, i32,
                               vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, i64, vp, i64, vp]
+    lib.fa_decode_mq.restype = i32
+    lib.fa_decode_mq.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp, i32,
+                                 i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, i32, i64,
+                                 f32, i32, vp, vp, sz, vp]
     lib.fa_select_workspace_bytes.restype = sz
     lib.fa_select_workspace_bytes.argtypes = [i32] * 6
     lib.fa_select_dims.restype = i32
@@ -229,4 +233,28 @@ def fa_select_dims(x, M, Dc, want_mse=True, workspace=None, stream=None):
     if st != FA_OK:
         raise FourierAttnError(st, "fa_select_dims")
     return mask, mse
+
+
+def fa_decode_mq(q, ck, kmask, cv, vmask, M, T, t0, N, k_keep, v_keep, k_full, v_full,
+                 scale=0.0, num_splits=0, out=None, workspace=None, stream=None):
+    """Enqueue fa_decode_mq on `stream`: q [B, Hkv, Tq, G, D] -> out fp32 of the same shape; the last
+    Tq rows of k_full / v_full are the new tokens."""
+    B, Hkv, Tq, G, D = q.shape
+    Hq = Hkv * G
+    Dkc = ck.shape[-1] if ck is not None else 0
+    Dvc = cv.shape[-1] if cv is not None else 0
+    W = k_full.shape[2]
+    dev = q.device
+    if out is None:
+        out = torch.empty((B, Hkv, Tq, G, D), dtype=torch.float32, device=dev)
+    if workspace is None:
+        need = decode_workspace_bytes(B, Hq * Tq, Hkv, D, Dkc, Dvc, M, N, W, num_splits)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    st = lib.fa_decode_mq(_ptr(q), _dtype_code(q), B, Tq, Hq, Hkv, D, _ptr(ck), _ptr(kmask), Dkc, _ptr(cv),
+                          _ptr(vmask), Dvc, M, T, t0, N, _ptr(k_keep), 0, _ptr(v_keep), 0, _ptr(k_full),
+                          _ptr(v_full), W, 0, float(scale), num_splits, _ptr(out), _ptr(workspace),
+                          workspace.numel(), _stream_ptr(stream))
+    if st != FA_OK:
+        raise FourierAttnError(st, "fa_decode_mq")
+    return out
 

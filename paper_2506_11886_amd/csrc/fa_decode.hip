@@ -90,6 +90,7 @@ struct DecodeParams {
   const void* v_full;
   int64_t kk_stride, vk_stride, full_stride;
   int B, Hq, Hkv, G, D, Dkc, Dvc, Dku, Dvu, M, T, t0, N, W;
+  int Tq, Gq;       // query tokens per sequence (1: plain decode) and query heads per KV head and token
   int Gp, KT;       // group size padded to a power of two, tiles per wave step
   int Mint;         // series length: 2 * (M/2) padded to a compiled size
   int Sw, Sm;       // chunks of full-width rows / of middle rows (middle chunks come first)
@@ -384,6 +385,7 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
   const int jw = s * kWChunk + wave * kWRows;          // first row of this wave
   const int nw = max(0, min(kWRows, p.W - jw));        // its valid rows (0: the wave only joins the barriers)
   const int jlast = p.W - 1;
+  const int jvis = p.W - p.Tq + r16 / p.Gq;            // last row the query token of column r16 may see
 
   // LDS carve-up: q [16][D] | p tiles [4][64][16] | partial sums [parts][4][D]
   T* qf = reinterpret_cast<T*>(smem);
@@ -466,7 +468,7 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int r = 16 * rb + 4 * q4 + v;
-      const float sv = (r < nw && r16 < G) ? sacc[rb][v] * p.scale : -INFINITY;
+      const float sv = (r < nw && r16 < G && jw + r <= jvis) ? sacc[rb][v] * p.scale : -INFINITY;
       sacc[rb][v] = sv;
       m_w = fmaxf(m_w, sv);
     }
@@ -1611,8 +1613,15 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
                        const void* v_keep, int64_t vk_stride_bh, const void* k_full,
                        const void* v_full, int W, int64_t full_stride_bh, float scale,
                        int num_splits, float* out, void* workspace, size_t workspace_bytes,
-                       void* hip_stream, fa::KernelTimers* tm) {
+                       void* hip_stream, fa::KernelTimers* tm, int Tq = 1) {
   using namespace fa;
+  // Tq query tokens per sequence are Tq * Hq query heads to every kernel (group index = token * G +
+  // head); only the full-width rows know about tokens: the last Tq rows are the new tokens, and
+  // query t sees new tokens 0 .. t
+  if (Tq < 1 || (Tq > 1 && Tq > W) || Hq <= 0 || Hkv <= 0) return FA_ERR_SHAPE;
+  const int Gq = Hq / Hkv;
+  if (static_cast<long>(Hq) * Tq / Hkv > FA_MAX_GROUP) return FA_ERR_UNSUPPORTED;
+  Hq *= Tq;
   const int st = check_decode_shapes(dtype, B, Hq, Hkv, D, Dkc, Dvc, M, T, t0, N, W, num_splits);
   if (st != FA_OK) return st;
   if (!q || !kmask || !vmask || !out || !workspace) return FA_ERR_NULL;
@@ -1650,6 +1659,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   p.k_keep = k_keep; p.v_keep = v_keep; p.k_full = k_full; p.v_full = v_full;
   p.kk_stride = kk_stride_bh; p.vk_stride = vk_stride_bh; p.full_stride = full_stride_bh;
   p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv; p.D = D;
+  p.Tq = Tq; p.Gq = Gq > 0 ? Gq : 1;
   p.Dkc = Dkc; p.Dvc = Dvc; p.Dku = Dku; p.Dvu = Dvu;
   p.M = M; p.T = T; p.t0 = t0; p.N = N; p.W = W;
   p.Gp = pl.Gp; p.KT = pl.KT; p.Mint = pl.Mint;
@@ -1682,6 +1692,17 @@ int fa_decode(const void* q, int dtype, int B, int Hq, int Hkv, int D, const flo
   return decode_impl(q, dtype, B, Hq, Hkv, D, ck, kmask, Dkc, cv, vmask, Dvc, M, T, t0, N, k_keep,
                      kk_stride_bh, v_keep, vk_stride_bh, k_full, v_full, W, full_stride_bh, scale,
                      num_splits, out, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+int fa_decode_mq(const void* q, int dtype, int B, int Tq, int Hq, int Hkv, int D, const float* ck,
+                 const uint8_t* kmask, int Dkc, const float* cv, const uint8_t* vmask, int Dvc, int M,
+                 int T, int t0, int N, const void* k_keep, int64_t kk_stride_bh, const void* v_keep,
+                 int64_t vk_stride_bh, const void* k_full, const void* v_full, int W,
+                 int64_t full_stride_bh, float scale, int num_splits, float* out, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  return decode_impl(q, dtype, B, Hq, Hkv, D, ck, kmask, Dkc, cv, vmask, Dvc, M, T, t0, N, k_keep,
+                     kk_stride_bh, v_keep, vk_stride_bh, k_full, v_full, W, full_stride_bh, scale,
+                     num_splits, out, workspace, workspace_bytes, hip_stream, nullptr, Tq);
 }
 
 int fa_decode_timed(const void* q, int dtype, int B, int Hq, int Hkv, int D, const float* ck,

@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(fa_[a-z_0-9]+)\s*\(", hdr))
     assert {"fa_compress", "fa_decode", "fa_compress_workspace_bytes",
             "fa_decode_workspace_bytes", "fa_decode_default_splits", "fa_status_string",
-            "fa_append", "fa_select_dims", "fa_select_workspace_bytes"} <= names
+            "fa_append", "fa_select_dims", "fa_select_workspace_bytes", "fa_decode_mq"} <= names
     for n in names:
         assert hasattr(fa.lib, n), n
 
@@ -131,4 +131,16 @@ def test_select_rejects_bad_arguments_on_the_host():
     assert call() == -4                  # workspace too small
     assert fa.select_workspace_bytes(1, 1, 8, 300, 64, 32) > 4 * 8 * 300 * 64
     assert fa.select_workspace_bytes(0, 1, 8, 300, 64, 32) < fa.select_workspace_bytes(1, 1, 8, 300, 64, 32)
+
+
+def test_decode_mq_rejects_bad_arguments_on_the_host():
+    fa = _fa()
+
+    def call(Tq, Hq=8, Hkv=2, W=16):
+        return fa.lib.fa_decode_mq(FAKE, 1, 1, Tq, Hq, Hkv, 128, FAKE, FAKE, 96, FAKE, FAKE, 96, 32, 512, 0, 512,
+                                   FAKE, 0, FAKE, 0, FAKE, FAKE, W, 0, 0.0, 0, FAKE, FAKE, 0, None)
+    assert call(0) == -2                 # no query token
+    assert call(3, W=2) == -2            # more new tokens than full-width rows
+    assert call(5) == -3                 # 5 tokens x 4 heads per KV head exceed the group limit
+    assert call(4) == -4                 # legal, but the workspace is too small
 

@@ -296,3 +296,52 @@ def test_select_dims_full_size():
     print(f"[case] select full size {cfg}", flush=True)
     _select_case(cfg, cfg.M, nheads=2)
 
+
+# --------------------------------------------------------------------------
+# several query tokens per step
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,Tq", [("tiny", 2), ("tiny", 4), ("tiny_bf16", 3), ("gqa8_oddM", 2), ("mha_ragged", 5),
+                                     ("odd_dims", 4), ("window_only", 8), ("m512", 4)])
+def test_decode_multi_query_matches_oracle(name, Tq):
+    import oracle.fourier_kv as fk
+    fa = _fa()
+    cfg = next(c for c in SMALL if c.name == name)
+    print(f"[case] multi-query Tq={Tq} {cfg}", flush=True)
+    ctx = cached_context(cfg)
+    heads = sample_heads(cfg, None)
+    st = oracle_state(cfg, ctx, heads)
+    G, D = cfg.G, cfg.D
+    rng = np.random.default_rng(100 + cfg.index)
+    # Tq query tokens per sequence; the stored dtype decides what both sides see
+    q = rng.standard_normal((cfg.B, cfg.Hkv, Tq, G, D)).astype(np.float32)
+    qd = to_dev(q, cfg)
+    qh = qd.float().cpu().numpy().astype(np.float64)
+    out = fa.fa_decode_mq(qd, to_dev(st["ck32"]), to_dev(ctx["kmask"]), to_dev(st["cv32"]), to_dev(ctx["vmask"]),
+                          cfg.M, cfg.T, 0, cfg.N, to_dev(rows_pad8(st["kk"]), cfg), to_dev(rows_to_tok8(st["vk"]), cfg),
+                          to_dev(ctx["k_full"], cfg), to_dev(ctx["v_full"], cfg), num_splits=cfg.num_splits)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    for b, h in heads:
+        want = fk.decode_multi_query(qh[b, h], st["ck32"][b, h].astype(np.float64), ctx["kmask"][b, h],
+                                     st["cv32"][b, h].astype(np.float64), ctx["vmask"][b, h], cfg.T, 0, cfg.N,
+                                     st["kk"][b, h], st["vk"][b, h], ctx["k_full"][b, h], ctx["v_full"][b, h])
+        assert np.isfinite(out[b, h]).all()
+        for t in range(Tq):
+            assert rel_err(out[b, h, t], want[t]) <= cfg.tol, ("out", b, h, t, rel_err(out[b, h, t], want[t]))
+
+
+def test_decode_multi_query_with_one_token_is_fa_decode():
+    fa = _fa()
+    cfg = next(c for c in SMALL if c.name == "gqa8_oddM")
+    ctx = cached_context(cfg)
+    st = oracle_state(cfg, ctx, sample_heads(cfg, None))
+    args = (to_dev(st["ck32"]), to_dev(ctx["kmask"]), to_dev(st["cv32"]), to_dev(ctx["vmask"]), cfg.M, cfg.T, 0, cfg.N,
+            to_dev(rows_pad8(st["kk"]), cfg), to_dev(rows_to_tok8(st["vk"]), cfg), to_dev(ctx["k_full"], cfg),
+            to_dev(ctx["v_full"], cfg))
+    q = to_dev(ctx["q"], cfg)                                   # [B, Hq, D]
+    a = fa.fa_decode(q, *args, num_splits=cfg.num_splits)
+    b = fa.fa_decode_mq(q.view(cfg.B, cfg.Hkv, 1, cfg.G, cfg.D), *args, num_splits=cfg.num_splits)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(-1), b.view(-1))                  # bit-identical: the same kernels, the same launch
+
