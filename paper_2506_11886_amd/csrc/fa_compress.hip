@@ -852,7 +852,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
       for (int ksx = 0; ksx < kFK; ++ksx) mma_k32(acc_dc, ones, dcx[ksx]);
     }
     if constexpr (kMode > 0) {
-      if (write_keep && blk < nb) *reinterpret_cast<u32x4*>(kdst) = kvv;
+      if (write_keep && blk < nb) __builtin_nontemporal_store(kvv, reinterpret_cast<u32x4*>(kdst));   // streamed: nobody reads it soon
     }
   };
   auto two_slots = [&](Frag<T> (&xnext)[TOK], int blk, auto odd_c) {   // block blk; xnext holds block blk + 1
