@@ -33,9 +33,9 @@ MEASURED_TRAFFIC = {
     ("compress_project", 2): 105890000,   # 65.26 MB read + 40.63 MB written (24.4 MB of it chunk partials)
     ("decode_partial", 2): 39249139,      # 37.57 MB read + 1.68 MB written (split-K partial records)
     # the other workloads (profiles/bench_cfgN_hbm_traffic.txt)
-    ("compress_project", 3): 339825000, ("decode_partial", 3): 165350000,
-    ("compress_project", 4): 357340000, ("decode_partial", 4): 80480000,   # M = 512: X is read by two row blocks
-    ("compress_project", 5): 386120000, ("decode_partial", 5): 205460000,
+    ("compress_project", 3): 327200000, ("decode_partial", 3): 165380000,
+    ("compress_project", 4): 328780000, ("decode_partial", 4): 80500000,   # M = 512: X is read by two row blocks
+    ("compress_project", 5): 360920000, ("decode_partial", 5): 205500000,
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_MATRIX_PEAK_TFLOPS = 157.3
