@@ -85,32 +85,49 @@ __global__ __launch_bounds__(kSBlock) void select_energy(SelectParams p) {
   }
 }
 
-// grid (B*H); thread d owns head dimension d
-__global__ __launch_bounds__(kSBlock) void select_rank(SelectParams p) {
+// grid (B*H), 1024 threads: thread (dim d, row group g) sums its share of the chunk energies and of
+// the weighted squared coefficients (independent loads, several in flight), the groups meet in
+// LDS, then thread d ranks its dim
+constexpr int kRBlock = 1024;
+__global__ __launch_bounds__(kRBlock) void select_rank(SelectParams p) {
+  __shared__ double ex_s[kRBlock], ec_s[kRBlock];
   __shared__ float err[FA_MAX_HEAD_DIM];
-  const int d = threadIdx.x, bh = blockIdx.x;
+  const int tid = threadIdx.x, bh = blockIdx.x;
   const int D = p.D, M = p.M, N = p.N;
-  float e = 0.0f;
-  if (d < D) {
-    double ex = 0.0, ec = 0.0;
-    for (int c = 0; c < p.chunks; ++c) ex += p.epart[(static_cast<size_t>(c) * gridDim.x + bh) * D + d];
+  const int ng = kRBlock / D;                  // row groups (4 .. 128)
+  const int d = tid % D, g = tid / D;
+  double ex = 0.0, ec = 0.0;
+  if (g < ng) {
+    for (int c = g; c < p.chunks; c += ng) ex += p.epart[(static_cast<size_t>(c) * gridDim.x + bh) * D + d];
     const float* C = p.coeffs + static_cast<size_t>(bh) * M * D + d;
-    for (int m = 0; m < M; ++m) {
+#pragma unroll 8
+    for (int m = g; m < M; m += ng) {
       const double cm = C[static_cast<size_t>(m) * D];
       ec += static_cast<double>(basis_weight((m + 1) / 2, N)) * cm * cm;
     }
-    e = static_cast<float>(fmax(ex - ec, 0.0) / N);
-    err[d] = e;
-    if (p.mse_out) p.mse_out[static_cast<size_t>(bh) * D + d] = e;
+  }
+  ex_s[tid] = ex;
+  ec_s[tid] = ec;
+  __syncthreads();
+  float e = 0.0f;
+  if (tid < D) {
+    double sx = 0.0, sc = 0.0;
+    for (int k = 0; k < ng; ++k) {             // fixed order: reproducible
+      sx += ex_s[k * D + tid];
+      sc += ec_s[k * D + tid];
+    }
+    e = static_cast<float>(fmax(sx - sc, 0.0) / N);
+    err[tid] = e;
+    if (p.mse_out) p.mse_out[static_cast<size_t>(bh) * D + tid] = e;
   }
   __syncthreads();
-  if (d < D) {
+  if (tid < D) {
     int rank = 0;
     for (int o = 0; o < D; ++o) {
       const float eo = err[o];
-      rank += (eo < e || (eo == e && o < d)) ? 1 : 0;
+      rank += (eo < e || (eo == e && o < tid)) ? 1 : 0;
     }
-    p.mask_out[static_cast<size_t>(bh) * D + d] = rank < p.Dc ? 1 : 0;
+    p.mask_out[static_cast<size_t>(bh) * D + tid] = rank < p.Dc ? 1 : 0;
   }
 }
 
@@ -196,7 +213,7 @@ int fa_select_dims(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t
   }
   if (rc != FA_OK) return rc;
 
-  hipLaunchKernelGGL(select_rank, dim3(B * H), dim3(kSBlock), 0, stream, p);
+  hipLaunchKernelGGL(select_rank, dim3(B * H), dim3(kRBlock), 0, stream, p);
   return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
 }
 
