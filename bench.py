@@ -30,12 +30,12 @@ HBM_PEAK_GBS = 8000.0
 # same counter reads for the --copy-probe kernel), keyed by (kernel, config index).
 # Source: profiles/bench_cfg*_hbm_traffic.txt; null for anything not measured there.
 MEASURED_TRAFFIC = {
-    ("compress_project", 2): 105890000,   # 65.26 MB read + 40.63 MB written (24.4 MB of it chunk partials)
-    ("decode_partial", 2): 39249139,      # 37.57 MB read + 1.68 MB written (split-K partial records)
-    # the other workloads (profiles/bench_cfgN_hbm_traffic.txt)
-    ("compress_project", 3): 327200000, ("decode_partial", 3): 165380000,
-    ("compress_project", 4): 328780000, ("decode_partial", 4): 80500000,   # M = 512: X is read by two row blocks
-    ("compress_project", 5): 360920000, ("decode_partial", 5): 205500000,
+    # compress_project = the K | V pair launch (both tensors); cfg2: 130.3 MB read + 81.3 MB written,
+    # 48.8 MB of it chunk partials
+    ("compress_project", 2): 211520000, ("decode_partial", 2): 39270000,
+    ("compress_project", 3): 654170000, ("decode_partial", 3): 165390000,
+    ("compress_project", 4): 660390000, ("decode_partial", 4): 80510000,   # M = 512: X is read by two row blocks
+    ("compress_project", 5): 721580000, ("decode_partial", 5): 205500000,
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_MATRIX_PEAK_TFLOPS = 157.3
@@ -99,17 +99,15 @@ def main():
         s["vk"] = torch.zeros((B, Hkv, fa.tok8_numel(N, Dvu)), dtype=dt, device="cuda")
         s["out"] = torch.empty((B, Hq, D), dtype=torch.float32, device="cuda")
         sets.append(s)
-    ws_c = torch.empty(max(256, fa.compress_workspace_bytes(B, Hkv, N, D, max(cfg.Dkc, cfg.Dvc), M)),
+    ws_c = torch.empty(max(256, fa.compress_kv_workspace_bytes(B, Hkv, N, D, cfg.Dkc, cfg.Dvc, M)),
                        dtype=torch.uint8, device="cuda")
     ws_d = torch.empty(max(256, fa.decode_workspace_bytes(B, Hq, Hkv, D, cfg.Dkc, cfg.Dvc, M, N, W,
                                                           cfg.num_splits)),
                        dtype=torch.uint8, device="cuda")
 
-    def compress(s, kms=None):
-        fa.fa_compress(s["k_mid"], s["kmask"], cfg.Dkc, M, T, coeffs=s["ck"], x_keep=s["kk"],
-                       keep_layout=fa.FA_KEEP_ROWS, workspace=ws_c, kernel_ms=kms)
-        fa.fa_compress(s["v_mid"], s["vmask"], cfg.Dvc, M, T, coeffs=s["cv"], x_keep=s["vk"],
-                       keep_layout=fa.FA_KEEP_TOK8, workspace=ws_c, kernel_ms=kms)
+    def compress(s, kms=None):   # K and V of the same tokens: one call (one projection launch when both qualify)
+        fa.fa_compress_kv(s["k_mid"], s["v_mid"], s["kmask"], s["vmask"], cfg.Dkc, cfg.Dvc, M, T, ck=s["ck"],
+                          cv=s["cv"], k_keep=s["kk"], v_keep=s["vk"], workspace=ws_c, kernel_ms=kms)
 
     def decode(s, kms=None):
         fa.fa_decode(s["q"], s["ck"], s["kmask"], s["cv"], s["vmask"], M, T, 0, N, s["kk"], s["vk"],
@@ -144,9 +142,9 @@ def main():
         decode(sets[i % n_sets], kd)
         compress(sets[i % n_sets], kc)
     kd = np.array(kd).reshape(reps, 3).mean(0) * 1e-3        # prepare, partial, finish [s]
-    kc = np.array(kc).reshape(reps, 2, 2).mean(0) * 1e-3     # [K|V][project, reduce] [s]
+    kc = np.array(kc).reshape(reps, 2).mean(0) * 1e-3        # [projection of K and V, their reductions] [s]
     t_partial = float(kd[1])
-    t_project = float(kc[:, 0].sum())                          # K and V projections together
+    t_project = float(kc[0])                                   # K and V projections together
 
     def roof_hbm(bytes_, t, kernel):
         a = bytes_ / t / 1e9
@@ -164,7 +162,7 @@ def main():
         roof_cmp = {"kernel": "compress_project", "bound": "mfma", "achieved": round(a, 1),
                     "peak": mm_peak, "unit": "TFLOP/s", "frac": round(a / mm_peak, 4),
                     "traffic": MEASURED_TRAFFIC.get(("compress_project", cfg.index))}
-    roof_cmp["launches_per_step"] = 2       # K and V; achieved = bytes (flop) of both / duration of both
+    roof_cmp["launches_per_step"] = 1       # K and V in one launch; achieved = bytes (flop) of both / its duration
     roof_cmp["mfma_tflops"] = round(cmp_flops / t_project / 1e12, 1)
     roof_cmp["mfma_frac"] = round(cmp_flops / t_project / 1e12 / mm_peak, 4)
     dominant = roof_cmp if t_project > t_partial else roof_dec
@@ -185,7 +183,7 @@ def main():
         "config": {
             "workload": f"cfg{cfg.index} {cfg.name}: B={B} Hq={Hq} Hkv={Hkv} D={D} L={cfg.L} "
                         f"(sink {cfg.Li} + middle {N} + window {cfg.Lw}) Dkc={cfg.Dkc} Dvc={cfg.Dvc} M={M}",
-            "step": "fa_compress(K) + fa_compress(V) + fa_decode",
+            "step": "fa_compress_kv(K, V) + fa_decode",
             "buffer_sets": n_sets,
         },
         "roofline": dominant,
@@ -199,10 +197,8 @@ def main():
                        "roofline": roof_dec},
             "compress": {"ms": round(t_cmp * 1e3, 5), "tokens_per_s": round(B * N / t_cmp, 1),
                          "algorithmic_bytes": cmp_bytes, "flop": cmp_flops,
-                         "kernel_ms": {"project_k": round(float(kc[0, 0]) * 1e3, 5),
-                                       "project_v": round(float(kc[1, 0]) * 1e3, 5),
-                                       "reduce_k": round(float(kc[0, 1]) * 1e3, 5),
-                                       "reduce_v": round(float(kc[1, 1]) * 1e3, 5)},
+                         "kernel_ms": {"project_kv": round(float(kc[0]) * 1e3, 5),
+                                       "reduce_kv": round(float(kc[1]) * 1e3, 5)},
                          "roofline": roof_cmp},
         },
     }

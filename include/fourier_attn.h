@@ -9,6 +9,8 @@
  *                compressed and kept ones, project the compressed ones onto
  *                the first M real Fourier basis functions, and pack the kept
  *                ones.
+ *   fa_compress_kv  the same for the K and the V segment of the same tokens in
+ *                one call (fewer launches).
  *   fa_decode    Eq. 6: single-query attention over cat(sink+window rows,
  *                reconstructed middle rows) where the compressed dimensions
  *                of the middle rows are evaluated from their coefficients on
@@ -174,6 +176,32 @@ int fa_append(const void* k_new, const void* v_new, int dtype,
               void* hip_stream);
 
 /*
+ * fa_compress_kv -- fa_compress for the K and the V segment of the same tokens in
+ * one call (Eq. 2-4 applied to both caches, as prefill does).
+ *
+ * Equivalent to
+ *   fa_compress(k, ..., kmask, Dkc, ..., ck, k_keep, FA_KEEP_ROWS, kk_stride_bh, keep_offset, ...)
+ *   fa_compress(v, ..., vmask, Dvc, ..., cv, v_keep, FA_KEEP_TOK8, vk_stride_bh, keep_offset, ...)
+ * (the layouts fa_decode reads), with identical results; k and v share dtype,
+ * shape [B,H,N,D] and strides.  When both sides qualify for the specialised
+ * projection kernel (bf16, D = 128, at most 32 kept dims each, keep_offset a
+ * multiple of 8) the two projections run as ONE launch and the two chunk
+ * reductions as one: two kernel launches per call instead of four.
+ * workspace: >= fa_compress_kv_workspace_bytes(B, H, N, D, Dkc, Dvc, M), 256-byte
+ * aligned.  Everything else (argument meaning, errors, asynchrony) as fa_compress.
+ */
+size_t fa_compress_kv_workspace_bytes(int B, int H, int N, int D, int Dkc, int Dvc, int M);
+int fa_compress_kv(const void* k, const void* v, int dtype,
+                   int64_t sx_b, int64_t sx_h, int64_t sx_n,
+                   int B, int H, int N, int D,
+                   const uint8_t* kmask, int Dkc, const uint8_t* vmask, int Dvc,
+                   int M, int T, int t0, int accumulate,
+                   float* ck, float* cv,
+                   void* k_keep, int64_t kk_stride_bh, void* v_keep, int64_t vk_stride_bh,
+                   int keep_offset,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * fa_decode_mq -- fa_decode for Tq consecutive query tokens per sequence (paper,
  * Section 3.3: the FlashAttention side of the fused kernel; chunked decoding or
  * the verification of drafted tokens).
@@ -238,9 +266,21 @@ int fa_select_dims(const void* x, int dtype,
  * stream, and the per-kernel durations in milliseconds are written to
  * `kernel_ms`, a HOST array:
  *   fa_compress_timed: 2 floats (projection, chunk reduction)
+ *   fa_compress_kv_timed: 2 floats (projection of K and V, their chunk reductions;
+ *                      sums over the two calls when the pair does not run as one launch)
  *   fa_decode_timed  : 3 floats (prepare, per-chunk partial, finish)
  * A kernel that was not launched for these sizes reports 0.
  */
+int fa_compress_kv_timed(const void* k, const void* v, int dtype,
+                         int64_t sx_b, int64_t sx_h, int64_t sx_n,
+                         int B, int H, int N, int D,
+                         const uint8_t* kmask, int Dkc, const uint8_t* vmask, int Dvc,
+                         int M, int T, int t0, int accumulate,
+                         float* ck, float* cv,
+                         void* k_keep, int64_t kk_stride_bh, void* v_keep, int64_t vk_stride_bh,
+                         int keep_offset,
+                         void* workspace, size_t workspace_bytes, void* hip_stream,
+                         float* kernel_ms);
 int fa_compress_timed(const void* x, int dtype,
                       int64_t sx_b, int64_t sx_h, int64_t sx_n,
                       int B, int H, int N, int D,

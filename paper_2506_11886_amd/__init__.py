@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     FA_OK, FA_F32, FA_BF16, FA_KEEP_ROWS, FA_KEEP_TOK8,
     FourierAttnError, lib, library_path, status_string,
     compress_workspace_bytes, decode_workspace_bytes, decode_default_splits,
-    fa_compress, fa_decode, fa_decode_mq, fa_append, fa_select_dims, select_workspace_bytes,
+    fa_compress, fa_compress_kv, compress_kv_workspace_bytes, fa_decode, fa_decode_mq, fa_append, fa_select_dims, select_workspace_bytes,
     keep_rows_from_tok8, tok8_numel, keep_rows_pitch,
 )

@@ -53,6 +53,13 @@ def _load(path: str = _LIB_PATH):
     lib.fa_append.restype = i32
     lib.fa_append.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i64, i32, i32,
                               vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, i64, vp, i64, vp]
+    lib.fa_compress_kv_workspace_bytes.restype = sz
+    lib.fa_compress_kv_workspace_bytes.argtypes = [i32] * 7
+    lib.fa_compress_kv.restype = i32
+    lib.fa_compress_kv.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32, i32, i32, vp, i32, vp, i32,
+                                   i32, i32, i32, i32, vp, vp, vp, i64, vp, i64, i32, vp, sz, vp]
+    lib.fa_compress_kv_timed.restype = i32
+    lib.fa_compress_kv_timed.argtypes = lib.fa_compress_kv.argtypes + [c.POINTER(c.c_float)]
     lib.fa_decode_mq.restype = i32
     lib.fa_decode_mq.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp, i32,
                                  i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, i32, i64,
@@ -257,4 +264,41 @@ def fa_decode_mq(q, ck, kmask, cv, vmask, M, T, t0, N, k_keep, v_keep, k_full, v
     if st != FA_OK:
         raise FourierAttnError(st, "fa_decode_mq")
     return out
+
+
+def compress_kv_workspace_bytes(B, H, N, D, Dkc, Dvc, M) -> int:
+    return int(lib.fa_compress_kv_workspace_bytes(B, H, N, D, Dkc, Dvc, M))
+
+
+def fa_compress_kv(k, v, kmask, vmask, Dkc, Dvc, M, T, t0=0, accumulate=False, ck=None, cv=None,
+                   k_keep=None, v_keep=None, keep_offset=0, workspace=None, stream=None, kernel_ms=None):
+    """Enqueue fa_compress_kv on `stream`: K and V segments [B,H,N,D] of the same tokens.  Returns
+    (ck, k_keep rows layout, cv, v_keep groups-of-8-tokens layout).  With `kernel_ms` (a list) the timed,
+    synchronous entry point is used and (projection, reduction) milliseconds appended."""
+    B, H, N, D = k.shape
+    assert v.shape == k.shape and v.stride() == k.stride() and v.dtype == k.dtype
+    dev = k.device
+    n_tok = keep_offset + N
+    if ck is None:
+        ck = torch.empty((B, H, M, Dkc), dtype=torch.float32, device=dev)
+    if cv is None:
+        cv = torch.empty((B, H, M, Dvc), dtype=torch.float32, device=dev)
+    if k_keep is None:
+        k_keep = torch.empty((B, H, n_tok, keep_rows_pitch(D - Dkc)), dtype=k.dtype, device=dev)
+    if v_keep is None:
+        v_keep = torch.zeros((B, H, tok8_numel(n_tok, D - Dvc)), dtype=k.dtype, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(compress_kv_workspace_bytes(B, H, N, D, Dkc, Dvc, M), 256), dtype=torch.uint8, device=dev)
+    args = (_ptr(k), _ptr(v), _dtype_code(k), k.stride(0), k.stride(1), k.stride(2), B, H, N, D,
+            _ptr(kmask), Dkc, _ptr(vmask), Dvc, M, T, t0, int(bool(accumulate)), _ptr(ck), _ptr(cv),
+            _ptr(k_keep), 0, _ptr(v_keep), 0, keep_offset, _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    if kernel_ms is None:
+        st = lib.fa_compress_kv(*args)
+    else:
+        ms = (ctypes.c_float * 2)()
+        st = lib.fa_compress_kv_timed(*args, ms)
+        kernel_ms.extend(ms)
+    if st != FA_OK:
+        raise FourierAttnError(st, "fa_compress_kv")
+    return ck, k_keep, cv, v_keep
 

@@ -475,9 +475,10 @@ __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) {   // (a.hi
 
 // KM selects the block step: 0 / 1 / 2 = the straight-line step with no kept dims to write /
 // kept dims as rows / kept dims in groups of 8 tokens (at most one 128-bit vector of kept dims
-// per thread and block); -1 = the general step (any number of kept dims, or nothing to project).
+// per thread and block); 3 = 1 or 2 by the call's layout (the K | V pair launch); -1 = the general
+// step (any number of kept dims, or nothing to project).
 template <int DT, int KM>
-__global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams p) {
+__device__ __forceinline__ void project_fast_body(const CompressParams& p, const int bh) {
   using T = bf16_t;
   constexpr int NW = kCBlock / 64;    // 8 waves
   constexpr int kThreads = kCBlock;
@@ -491,7 +492,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int q4 = lane >> 4, r16 = lane & 15;
   const int s = blockIdx.x, mc = blockIdx.y;
-  const int bh = blockIdx.z, b = bh / p.H, h = bh % p.H;
+  const int b = bh / p.H, h = bh % p.H;
   constexpr int D = 128;
   const int M = p.M, Du = p.Du, kp = p.keep_pitch;
   const int j0 = s * p.chunk, jend = min(p.N, j0 + p.chunk);
@@ -759,9 +760,9 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   // the shadow of the matrix instructions.  Ragged edges are handled by value: tokens past the
   // chunk are masked to zero, vectors past the end re-store the last valid one.
   const int dcl = min(rgw, DT - 1);   // column tile whose sums this wave forms (used if wave_dc)
-  auto fused_step = [&](Frag<T> (&xnext)[TOK], int blk, auto odd_c) {
+  auto fused_step = [&](Frag<T> (&xnext)[TOK], int blk, auto odd_c, auto mode_c) {
     constexpr int kOdd = decltype(odd_c)::value;   // second block of a pair: second basis set, no turn
-    constexpr int kMode = KM;   // kept dims: 0 none to write, 1 rows, 2 groups of 8 tokens
+    constexpr int kMode = decltype(mode_c)::value;   // kept dims: 0 none to write, 1 rows, 2 groups of 8 tokens
     const int js = j0 + blk * kFB;
     const unsigned char* cb = smem + (blk & 1) * bufb;
     unsigned char* fb = smem + ((blk & 1) ^ 1) * bufb;
@@ -772,14 +773,14 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
     // kept dims of block blk: out of the staging tile
     u32x4 kvv = {0u, 0u, 0u, 0u};
     T* kdst = keep;
-    if constexpr (kMode == 1) {
+    if (kMode == 1 || (kMode == 3 && rows_layout)) {   // (kMode 3: decided per launch half, a uniform branch)
       const int jt = max(min(kv_a, jend - js - 1), 0);
       const uint16_t* src = reinterpret_cast<const uint16_t*>(cb + ks_off) + (8 * kv_b) * kFP + jt;
 #pragma unroll
       for (int k = 0; k < 4; ++k)
         kvv[k] = static_cast<uint32_t>(src[(2 * k) * kFP]) | (static_cast<uint32_t>(src[(2 * k + 1) * kFP]) << 16);
       kdst = keep + (static_cast<int64_t>(p.keep_offset) + js + jt) * kp + 8 * kv_b;
-    } else if constexpr (kMode == 2) {
+    } else if (kMode == 2 || kMode == 3) {
       const int g = max(min(kv_a, (jend - js - 1) >> 3), 0);
       kvv = *reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(cb + ks_off) + kv_b * kFP + 8 * g);
       kdst = keep + ((((static_cast<int64_t>(p.keep_offset) + js) >> 3) + g) * Du + kv_b) * 8;
@@ -857,7 +858,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
   };
   auto two_slots = [&](Frag<T> (&xnext)[TOK], int blk, auto odd_c) {   // block blk; xnext holds block blk + 1
     if constexpr (KM >= 0) {
-      fused_step(xnext, blk, odd_c);
+      fused_step(xnext, blk, odd_c, std::integral_constant<int, KM>{});
     } else {
       multiply_block(blk, odd_c);
       if (blk + 1 < nb) scatter_block(xnext, blk + 1);
@@ -970,6 +971,52 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams 
       }
   }
   FA_CSTAMP(31);
+}
+
+template <int DT, int KM>
+__global__ __launch_bounds__(kCBlock) void compress_project_fast(CompressParams p) {
+  project_fast_body<DT, KM>(p, blockIdx.z);
+}
+
+// K and V of the same tokens in one launch: grid z covers the (sequence, head) pairs of K, then
+// those of V; each half runs with its own arguments
+struct CompressParamsKV {
+  CompressParams k, v;
+};
+template <int DT>
+__global__ __launch_bounds__(kCBlock) void compress_project_fast_kv(CompressParamsKV pp) {
+  const int BH = pp.k.B * pp.k.H;
+  const bool second = static_cast<int>(blockIdx.z) >= BH;
+  const CompressParams& p = second ? pp.v : pp.k;
+  project_fast_body<DT, 3>(p, static_cast<int>(blockIdx.z) - (second ? BH : 0));
+}
+
+// the chunk reduction of both tensors in one launch (grid y: 0 = K, 1 = V)
+struct ReducePair {
+  const float* part[2];
+  float* coeffs[2];
+  size_t total[2], stride[2];
+  int Sc, accumulate;
+};
+__global__ __launch_bounds__(256) void compress_reduce_kv(ReducePair r) {
+  const int y = blockIdx.y;
+  const float* part = y ? r.part[1] : r.part[0];
+  float* coeffs = y ? r.coeffs[1] : r.coeffs[0];
+  const size_t total = y ? r.total[1] : r.total[0], stride = y ? r.stride[1] : r.stride[0];
+  const size_t idx = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
+  if (idx >= total) return;
+  if (idx + 4 <= total) {
+    f32x4 v = r.accumulate ? *reinterpret_cast<const f32x4*>(coeffs + idx) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int s = 0; s < r.Sc; ++s) v += *reinterpret_cast<const f32x4*>(part + static_cast<size_t>(s) * stride + idx);
+    *reinterpret_cast<f32x4*>(coeffs + idx) = v;
+  } else {
+    for (size_t k = idx; k < total; ++k) {
+      float v = r.accumulate ? coeffs[k] : 0.0f;
+      for (int s = 0; s < r.Sc; ++s) v += part[static_cast<size_t>(s) * stride + k];
+      coeffs[k] = v;
+    }
+  }
 }
 
 // sum of the token-chunk partials (fixed order, so results are reproducible)
@@ -1092,7 +1139,8 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
                          int H, int N, int D, const uint8_t* dim_mask, int Dc, int M, int T, int t0,
                          int accumulate, float* coeffs, void* x_keep, int keep_layout,
                          int64_t keep_stride_bh, int keep_offset, void* workspace,
-                         size_t workspace_bytes, void* hip_stream, fa::KernelTimers* tm) {
+                         size_t workspace_bytes, void* hip_stream, fa::KernelTimers* tm,
+                         fa::CompressParams* only_params = nullptr, fa::CompressPlan* only_plan = nullptr) {
   using namespace fa;
   const int st = check_compress_shapes(dtype, B, H, N, D, Dc, M, T, t0);
   if (st != FA_OK) return st;
@@ -1141,6 +1189,11 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
                                          static_cast<size_t>(B) * H * pl.MC * pl.DCn * (pl.Sc > 0 ? pl.Sc : 1) * 8 * 32 * sizeof(long long));
 #endif
 
+  if (only_params) {   // the caller launches (the K | V pair entry)
+    *only_params = p;
+    *only_plan = pl;
+    return FA_OK;
+  }
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const size_t total = static_cast<size_t>(B) * H * M * Dc;
   if (pl.Sc > 0) {
@@ -1198,6 +1251,117 @@ int fa_compress(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx
   return compress_impl(x, dtype, sx_b, sx_h, sx_n, B, H, N, D, dim_mask, Dc, M, T, t0, accumulate,
                        coeffs, x_keep, keep_layout, keep_stride_bh, keep_offset, workspace,
                        workspace_bytes, hip_stream, nullptr);
+}
+
+size_t fa_compress_kv_workspace_bytes(int B, int H, int N, int D, int Dkc, int Dvc, int M) {
+  const size_t a = fa_compress_workspace_bytes(B, H, N, D, Dkc, M), b = fa_compress_workspace_bytes(B, H, N, D, Dvc, M);
+  if (a == 0 || b == 0) return 0;
+  return ((a + 255) & ~size_t(255)) + b;
+}
+
+// tm / tm2 (optional): event pairs for the timed entry point; tm2 is used only when the call falls
+// back to two projections
+static int compress_kv_impl(const void* k, const void* v, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n,
+                            int B, int H, int N, int D, const uint8_t* kmask, int Dkc, const uint8_t* vmask,
+                            int Dvc, int M, int T, int t0, int accumulate, float* ck, float* cv, void* k_keep,
+                            int64_t kk_stride_bh, void* v_keep, int64_t vk_stride_bh, int keep_offset,
+                            void* workspace, size_t workspace_bytes, void* hip_stream, fa::KernelTimers* tm,
+                            fa::KernelTimers* tm2) {
+  using namespace fa;
+  const size_t wk = (fa_compress_workspace_bytes(B, H, N, D, Dkc, M) + 255) & ~size_t(255);
+  const size_t wv = fa_compress_workspace_bytes(B, H, N, D, Dvc, M);
+  if (wk == 0 || wv == 0) return FA_ERR_SHAPE;
+  if (!workspace) return FA_ERR_NULL;
+  if (workspace_bytes < wk + wv || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return FA_ERR_WORKSPACE;
+  char* ws = static_cast<char*>(workspace);
+  CompressParams pk{}, pv{};
+  CompressPlan plk{}, plv{};
+  int rc = compress_impl(k, dtype, sx_b, sx_h, sx_n, B, H, N, D, kmask, Dkc, M, T, t0, accumulate, ck, k_keep,
+                         FA_KEEP_ROWS, kk_stride_bh, keep_offset, ws, wk, hip_stream, nullptr, &pk, &plk);
+  if (rc != FA_OK) return rc;
+  rc = compress_impl(v, dtype, sx_b, sx_h, sx_n, B, H, N, D, vmask, Dvc, M, T, t0, accumulate, cv, v_keep,
+                     FA_KEEP_TOK8, vk_stride_bh, keep_offset, ws + wk, wv, hip_stream, nullptr, &pv, &plv);
+  if (rc != FA_OK) return rc;
+  // One launch for both when each side takes the straight-line step with kept dims to write
+  // (bf16, head dim 128, at most one kept vector per thread and block) and they split the tokens
+  // alike; otherwise one call after the other.
+  auto nvec_of = [&](const CompressParams& p) {
+    return p.keep_layout == FA_KEEP_ROWS ? kFB * (p.keep_pitch / 8) : p.Du * (kFB / 8);
+  };
+  const unsigned lds_k = 2u * (kCols * kFP + static_cast<unsigned>(pk.keep_pitch) * kFP + 8u) * 2u;
+  const unsigned lds_v = 2u * (kCols * kFP + static_cast<unsigned>(pv.keep_pitch) * kFP + 8u) * 2u;
+  const unsigned lds = lds_k > lds_v ? lds_k : lds_v;
+  const bool pair = dtype == FA_BF16 && D == 128 && N > 0 && Dkc > 0 && Dvc > 0 && k_keep && v_keep &&
+                    pk.Du > 0 && pv.Du > 0 && nvec_of(pk) <= kCBlock && nvec_of(pv) <= kCBlock &&
+                    keep_offset % 8 == 0 && lds <= kMaxCLds && plk.Sc == plv.Sc && plk.chunk == plv.chunk &&
+                    plk.MC == plv.MC && plk.Sc > 0;
+  if (!pair) {
+    rc = compress_impl(k, dtype, sx_b, sx_h, sx_n, B, H, N, D, kmask, Dkc, M, T, t0, accumulate, ck, k_keep,
+                       FA_KEEP_ROWS, kk_stride_bh, keep_offset, ws, wk, hip_stream, tm);
+    if (rc != FA_OK) return rc;
+    return compress_impl(v, dtype, sx_b, sx_h, sx_n, B, H, N, D, vmask, Dvc, M, T, t0, accumulate, cv, v_keep,
+                         FA_KEEP_TOK8, vk_stride_bh, keep_offset, ws + wk, wv, hip_stream, tm2);
+  }
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  CompressParamsKV pp{pk, pv};
+  const bool narrow = (Dkc > Dvc ? Dkc : Dvc) <= 96;
+  static unsigned granted = 48 * 1024;
+  if (lds > granted) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(compress_project_fast_kv<6>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxCLds)) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(compress_project_fast_kv<8>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxCLds)) != hipSuccess)
+      return FA_ERR_HIP;
+    granted = kMaxCLds;
+  }
+  const dim3 grid(plk.Sc, plk.MC, 2 * B * H);
+  if (narrow) FA_LAUNCH_TIMED(tm, 0, compress_project_fast_kv<6>, grid, dim3(kCBlock), lds, stream, pp);
+  else FA_LAUNCH_TIMED(tm, 0, compress_project_fast_kv<8>, grid, dim3(kCBlock), lds, stream, pp);
+  if (plk.Sc > 1) {
+    ReducePair r{};
+    r.part[0] = pk.part; r.part[1] = pv.part;
+    r.coeffs[0] = ck; r.coeffs[1] = cv;
+    r.total[0] = static_cast<size_t>(B) * H * M * Dkc; r.total[1] = static_cast<size_t>(B) * H * M * Dvc;
+    r.stride[0] = pk.part_stride; r.stride[1] = pv.part_stride;
+    r.Sc = plk.Sc; r.accumulate = accumulate ? 1 : 0;
+    const size_t tmax = r.total[0] > r.total[1] ? r.total[0] : r.total[1];
+    FA_LAUNCH_TIMED(tm, 1, compress_reduce_kv, dim3(static_cast<unsigned>((tmax / 4 + 1 + 255) / 256), 2), dim3(256), 0, stream, r);
+  }
+  return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
+}
+
+int fa_compress_kv(const void* k, const void* v, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n,
+                   int B, int H, int N, int D, const uint8_t* kmask, int Dkc, const uint8_t* vmask,
+                   int Dvc, int M, int T, int t0, int accumulate, float* ck, float* cv, void* k_keep,
+                   int64_t kk_stride_bh, void* v_keep, int64_t vk_stride_bh, int keep_offset,
+                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return compress_kv_impl(k, v, dtype, sx_b, sx_h, sx_n, B, H, N, D, kmask, Dkc, vmask, Dvc, M, T, t0, accumulate,
+                          ck, cv, k_keep, kk_stride_bh, v_keep, vk_stride_bh, keep_offset, workspace,
+                          workspace_bytes, hip_stream, nullptr, nullptr);
+}
+
+int fa_compress_kv_timed(const void* k, const void* v, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n,
+                         int B, int H, int N, int D, const uint8_t* kmask, int Dkc, const uint8_t* vmask,
+                         int Dvc, int M, int T, int t0, int accumulate, float* ck, float* cv, void* k_keep,
+                         int64_t kk_stride_bh, void* v_keep, int64_t vk_stride_bh, int keep_offset,
+                         void* workspace, size_t workspace_bytes, void* hip_stream, float* kernel_ms) {
+  if (!kernel_ms) return FA_ERR_NULL;
+  fa::KernelTimers tm, tm2;
+  int st = tm.create();
+  if (st == FA_OK) st = tm2.create();
+  if (st == FA_OK)
+    st = compress_kv_impl(k, v, dtype, sx_b, sx_h, sx_n, B, H, N, D, kmask, Dkc, vmask, Dvc, M, T, t0, accumulate,
+                          ck, cv, k_keep, kk_stride_bh, v_keep, vk_stride_bh, keep_offset, workspace,
+                          workspace_bytes, hip_stream, &tm, &tm2);
+  float a[2] = {0.f, 0.f}, b[2] = {0.f, 0.f};
+  if (st == FA_OK) st = tm.read(2, a);
+  if (st == FA_OK) st = tm2.read(2, b);
+  if (st == FA_OK && hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)) != hipSuccess) st = FA_ERR_HIP;
+  kernel_ms[0] = a[0] + b[0];   // projection(s)
+  kernel_ms[1] = a[1] + b[1];   // chunk reduction(s)
+  tm.destroy();
+  tm2.destroy();
+  return st;
 }
 
 int fa_compress_timed(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n, int B,

@@ -22,7 +22,8 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(fa_[a-z_0-9]+)\s*\(", hdr))
     assert {"fa_compress", "fa_decode", "fa_compress_workspace_bytes",
             "fa_decode_workspace_bytes", "fa_decode_default_splits", "fa_status_string",
-            "fa_append", "fa_select_dims", "fa_select_workspace_bytes", "fa_decode_mq"} <= names
+            "fa_append", "fa_select_dims", "fa_select_workspace_bytes", "fa_decode_mq", "fa_compress_kv",
+            "fa_compress_kv_workspace_bytes"} <= names
     for n in names:
         assert hasattr(fa.lib, n), n
 
@@ -143,4 +144,22 @@ def test_decode_mq_rejects_bad_arguments_on_the_host():
     assert call(3, W=2) == -2            # more new tokens than full-width rows
     assert call(5) == -3                 # 5 tokens x 4 heads per KV head exceed the group limit
     assert call(4) == -4                 # legal, but the workspace is too small
+
+
+def test_compress_kv_rejects_bad_arguments_on_the_host():
+    fa = _fa()
+
+    def call(**kw):
+        d = dict(k=FAKE, v=FAKE, dtype=1, sn=128, N=2048, D=128, Dkc=96, Dvc=96, M=64, ws=FAKE, ws_bytes=1 << 30)
+        d.update(kw)
+        return fa.lib.fa_compress_kv(d["k"], d["v"], d["dtype"], 8 * d["N"] * d["sn"], d["N"] * d["sn"], d["sn"], 1, 8, d["N"],
+                                     d["D"], FAKE, d["Dkc"], FAKE, d["Dvc"], d["M"], d["N"], 0, 0, FAKE, FAKE, FAKE, 0, FAKE, 0, 0,
+                                     d["ws"], d["ws_bytes"], None)
+    assert call(M=0) == -2
+    assert call(Dvc=129) == -2
+    assert call(D=100, sn=100) in (-2, -3)
+    assert call(ws=None) == -1
+    assert call(ws_bytes=16) == -4
+    assert call(k=None) == -1
+    assert fa.compress_kv_workspace_bytes(1, 8, 31740, 128, 96, 96, 256) >= 2 * fa.compress_workspace_bytes(1, 8, 31740, 128, 96, 256)
 

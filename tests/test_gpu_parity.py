@@ -345,3 +345,44 @@ def test_decode_multi_query_with_one_token_is_fa_decode():
     torch.cuda.synchronize()
     assert torch.equal(a.view(-1), b.view(-1))                  # bit-identical: the same kernels, the same launch
 
+
+# --------------------------------------------------------------------------
+# K and V compressed by one call
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_bf16", "gqa8_oddM", "mha_ragged", "odd_dims", "middle_only", "m512",
+                                  "all_compress_bf16", "wide_d256"])
+def test_compress_kv_is_the_two_calls(name):
+    """Bit-identical to fa_compress(K, rows) + fa_compress(V, groups of 8 tokens): the same kernels' arithmetic,
+    whether the pair runs as one launch (bf16, D = 128, few kept dims) or falls back to two calls."""
+    fa = _fa()
+    cfg = next(c for c in SMALL if c.name == name)
+    print(f"[case] compress_kv {cfg}", flush=True)
+    ctx = cached_context(cfg)
+    k, v = to_dev(ctx["k_mid"], cfg), to_dev(ctx["v_mid"], cfg)
+    km, vm = to_dev(ctx["kmask"]), to_dev(ctx["vmask"])
+    ck0, kk0 = fa.fa_compress(k, km, cfg.Dkc, cfg.M, cfg.T, keep_layout=fa.FA_KEEP_ROWS)
+    cv0, vk0 = fa.fa_compress(v, vm, cfg.Dvc, cfg.M, cfg.T, keep_layout=fa.FA_KEEP_TOK8)
+    ck1, kk1, cv1, vk1 = fa.fa_compress_kv(k, v, km, vm, cfg.Dkc, cfg.Dvc, cfg.M, cfg.T)
+    torch.cuda.synchronize()
+    assert torch.equal(ck0, ck1) and torch.equal(cv0, cv1)
+    assert torch.equal(kk0.view(torch.int16) if kk0.dtype == torch.bfloat16 else kk0,
+                       kk1.view(torch.int16) if kk1.dtype == torch.bfloat16 else kk1)
+    assert torch.equal(vk0.view(torch.int16) if vk0.dtype == torch.bfloat16 else vk0,
+                       vk1.view(torch.int16) if vk1.dtype == torch.bfloat16 else vk1)
+
+
+def test_compress_kv_full_size():
+    fa = _fa()
+    cfg = CONFIGS[1]
+    print(f"[case] compress_kv full size {cfg}", flush=True)
+    ctx = cached_context(cfg)
+    k, v = to_dev(ctx["k_mid"], cfg), to_dev(ctx["v_mid"], cfg)
+    km, vm = to_dev(ctx["kmask"]), to_dev(ctx["vmask"])
+    ck0, kk0 = fa.fa_compress(k, km, cfg.Dkc, cfg.M, cfg.T, keep_layout=fa.FA_KEEP_ROWS)
+    cv0, vk0 = fa.fa_compress(v, vm, cfg.Dvc, cfg.M, cfg.T, keep_layout=fa.FA_KEEP_TOK8)
+    ck1, kk1, cv1, vk1 = fa.fa_compress_kv(k, v, km, vm, cfg.Dkc, cfg.Dvc, cfg.M, cfg.T)
+    torch.cuda.synchronize()
+    assert torch.equal(ck0, ck1) and torch.equal(cv0, cv1)
+    assert torch.equal(kk0.view(torch.int16), kk1.view(torch.int16)) and torch.equal(vk0.view(torch.int16), vk1.view(torch.int16))
+
