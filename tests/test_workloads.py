@@ -47,3 +47,15 @@ def test_config_table_matches_stated_sizes():
     assert abs(c5.decode_bytes() / 1e6 - 252.4) < 0.5
     assert abs(2 * c5.compress_flops(96) / 1e9 - 103.1) < 0.2
     assert len(CONFIGS) == 5
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's share only: any other count exits with a message, before touching a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and not r.stdout.strip()
