@@ -122,7 +122,11 @@ __device__ __forceinline__ void set_elem<float>(Frag<float>& f, int e, float x) 
 // 8-element vectors of X per thread and block (2 covers head dims up to 128, 4 up to 256)
 // kFast: the row vectors divide the workgroup evenly (head dim 64 / 128 / 256) and
 // kept dims are staged, so every thread routes the same 8 dims in every block.
-template <typename T, int DT, int kXR, bool kFast>
+// kSplit (bf16 only): the basis is held as a bf16 head plus a bf16 remainder (two products per
+// operand, 2^-17 relative instead of 2^-9).  Used for short segments, where the matrix work is
+// negligible and the rounding errors of a short period's few distinct basis values would not
+// average out.
+template <typename T, int DT, int kXR, bool kFast, bool kSplit>
 __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int16_t cpos[FA_MAX_HEAD_DIM];
@@ -199,6 +203,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
   const bool wave_live = project && rgw * 64 < rows_here && ndt > 0;
 
   Frag<T> ea[4][2];          // [m tile][32-token half]
+  Frag<T> el[kSplit ? 4 : 1][2];   // remainders of the split basis
   float twc[4][2], tws[4][2];   // cos/sin(omega_n * 64) of the two pairs a lane owns in every m tile
   const uint32_t ph_blk = fixed_phase(kTB, p.ph_scale);   // 64 positions, as a 2^-32-turn phase
   if (wave_live) {
@@ -226,7 +231,12 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
             sn = __builtin_amdgcn_sinf(x);
             c = __builtin_amdgcn_cosf(x);
           }
-          set_elem<T>(ea[mt][ksx], e, live ? ((rho & 1) ? sn : c) : 0.0f);
+          const float val = live ? ((rho & 1) ? sn : c) : 0.0f;
+          set_elem<T>(ea[mt][ksx], e, val);
+          if constexpr (kSplit) {
+            const float head = bf16_to_f32(f32_to_bf16(val));
+            set_elem<T>(el[mt][ksx], e, val - head);
+          }
         }
       }
 #pragma unroll
@@ -396,7 +406,10 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
             Frag<T> bx;
             bx.load(xcb + ((chw * DT + dt) * 16 + r16) * kLdX + 32 * ksx + 8 * q4);
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) mma_k32(acc[mt][dt], ea[mt][ksx], bx);
+            for (int mt = 0; mt < 4; ++mt) {
+              mma_k32(acc[mt][dt], ea[mt][ksx], bx);
+              if constexpr (kSplit) mma_k32(acc[mt][dt], el[mt][ksx], bx);
+            }
           }
         }
       }
@@ -462,6 +475,7 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
 // PAIR of blocks (256 tokens) in registers, so the frame moves once per 256 tokens.  The
 // constant function rides on the matrix cores as a row of ones, and all addressing is
 // decided before the loop.
+constexpr int kSplitTokens = 512;   // bf16 segments up to this length take the split basis
 constexpr int kFB = 128;            // tokens per block
 constexpr int kFP = kFB + 8;        // LDS pitch (elements) of a transposed column
 constexpr int kFK = kFB / 32;       // 32-token contraction steps per block
@@ -1109,9 +1123,9 @@ static int launch_project_fast(const CompressParams& p, const CompressPlan& pl, 
   return FA_OK;
 }
 
-template <typename T, int DT, int kXR, bool kFast>
+template <typename T, int DT, int kXR, bool kFast, bool kSplit>
 static int launch_project(const CompressParams& p, const CompressPlan& pl, hipStream_t st, KernelTimers* tm) {
-  auto kern = compress_project<T, DT, kXR, kFast>;
+  auto kern = compress_project<T, DT, kXR, kFast, kSplit>;
   static unsigned granted = 48 * 1024;
   if (pl.lds > granted) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1202,21 +1216,23 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
     const bool narrow = cols <= 96, small_d = D <= 128;
     // every thread routes fixed dims when the row vectors divide the workgroup and kept dims are staged
     const bool fast = (kCBlock % (D / 8)) == 0 && (pl.stage || Du == 0 || x_keep == nullptr);
-#define FA_LAUNCH_PROJECT2(T_, F_)                                                                  \
-  rc = narrow ? (small_d ? launch_project<T_, 3, 2, F_>(p, pl, stream, tm) : launch_project<T_, 3, 4, F_>(p, pl, stream, tm)) \
-              : (small_d ? launch_project<T_, 4, 2, F_>(p, pl, stream, tm) : launch_project<T_, 4, 4, F_>(p, pl, stream, tm))
-#define FA_LAUNCH_PROJECT(T_)       \
-  do {                              \
-    if (fast) {                     \
-      FA_LAUNCH_PROJECT2(T_, true); \
-    } else {                        \
-      FA_LAUNCH_PROJECT2(T_, false);\
-    }                               \
+#define FA_LAUNCH_PROJECT2(T_, F_, S_)                                                              \
+  rc = narrow ? (small_d ? launch_project<T_, 3, 2, F_, S_>(p, pl, stream, tm) : launch_project<T_, 3, 4, F_, S_>(p, pl, stream, tm)) \
+              : (small_d ? launch_project<T_, 4, 2, F_, S_>(p, pl, stream, tm) : launch_project<T_, 4, 4, F_, S_>(p, pl, stream, tm))
+#define FA_LAUNCH_PROJECT(T_, S_)       \
+  do {                                  \
+    if (fast) {                         \
+      FA_LAUNCH_PROJECT2(T_, true, S_); \
+    } else {                            \
+      FA_LAUNCH_PROJECT2(T_, false, S_);\
+    }                                   \
   } while (0)
+    // short bf16 segments: split basis in the generic kernel (see compress_project)
+    const bool short_seg = dtype == FA_BF16 && N <= kSplitTokens;
     // bf16 with head dim 128 and staged (or no) kept dims: the specialised kernel
     const unsigned fast_lds = 2u * (kCols * kFP + static_cast<unsigned>(keep_pitch) * kFP + 8u) * 2u;
     const bool staged_ok = x_keep == nullptr || Du == 0 || keep_layout == FA_KEEP_ROWS || keep_offset % 8 == 0;
-    if (dtype == FA_BF16 && D == 128 && staged_ok && fast_lds <= kMaxCLds) {
+    if (dtype == FA_BF16 && D == 128 && staged_ok && fast_lds <= kMaxCLds && !short_seg) {
       // straight-line block step when every thread has at most one vector of kept dims to store
       const int nvec = (x_keep == nullptr || Du == 0) ? 0 : (keep_layout == FA_KEEP_ROWS ? kFB * (keep_pitch / 8) : Du * (kFB / 8));
       const int km = (Dc == 0 || nvec > kCBlock) ? -1 : (nvec == 0 ? 0 : (keep_layout == FA_KEEP_ROWS ? 1 : 2));
@@ -1228,9 +1244,11 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
       else FA_LAUNCH_FAST(-1);
 #undef FA_LAUNCH_FAST
     } else if (dtype == FA_F32) {
-      FA_LAUNCH_PROJECT(float);
+      FA_LAUNCH_PROJECT(float, false);
+    } else if (short_seg) {
+      FA_LAUNCH_PROJECT(bf16_t, true);
     } else {
-      FA_LAUNCH_PROJECT(bf16_t);
+      FA_LAUNCH_PROJECT(bf16_t, false);
     }
 #undef FA_LAUNCH_PROJECT2
 #undef FA_LAUNCH_PROJECT
@@ -1291,7 +1309,7 @@ static int compress_kv_impl(const void* k, const void* v, int dtype, int64_t sx_
   const unsigned lds_k = 2u * (kCols * kFP + static_cast<unsigned>(pk.keep_pitch) * kFP + 8u) * 2u;
   const unsigned lds_v = 2u * (kCols * kFP + static_cast<unsigned>(pv.keep_pitch) * kFP + 8u) * 2u;
   const unsigned lds = lds_k > lds_v ? lds_k : lds_v;
-  const bool pair = dtype == FA_BF16 && D == 128 && N > 0 && Dkc > 0 && Dvc > 0 && k_keep && v_keep &&
+  const bool pair = dtype == FA_BF16 && D == 128 && N > kSplitTokens && Dkc > 0 && Dvc > 0 && k_keep && v_keep &&
                     pk.Du > 0 && pv.Du > 0 && nvec_of(pk) <= kCBlock && nvec_of(pv) <= kCBlock &&
                     keep_offset % 8 == 0 && lds <= kMaxCLds && plk.Sc == plv.Sc && plk.chunk == plv.chunk &&
                     plk.MC == plv.MC && plk.Sc > 0;
