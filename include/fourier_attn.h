@@ -93,7 +93,9 @@ enum { FA_KEEP_ROWS = 0, FA_KEEP_TOK8 = 1 };
  *               x_keep + (b*H+h)*keep_stride_bh elements and token j of x is
  *               stored at token index keep_offset + j of that slab.  May be
  *               NULL (nothing is written).  keep_stride_bh = 0 means dense.
- *   workspace   at least fa_compress_workspace_bytes(...) bytes, 256-byte aligned.
+ *   workspace   at least fa_compress_workspace_bytes(...) bytes, 256-byte aligned
+ *               (one figure that suffices for either element type; it holds the
+ *               per-token-chunk partial sums, which fp32 inputs need more of).
  *
  * N = 0 is legal (coeffs are zeroed unless accumulating).  Dc = 0 writes only
  * x_keep; Dc = D writes only coeffs.

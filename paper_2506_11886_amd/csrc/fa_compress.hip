@@ -475,7 +475,8 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
 // PAIR of blocks (256 tokens) in registers, so the frame moves once per 256 tokens.  The
 // constant function rides on the matrix cores as a row of ones, and all addressing is
 // decided before the loop.
-constexpr int kSplitTokens = 512;   // bf16 segments up to this length take the split basis
+constexpr int kSplitTokens = 512;      // bf16 segments up to this length take the split basis
+constexpr long kF32ChunkBlocks = 4;    // fp32 inputs: at most this many 128-token blocks per chunk
 constexpr int kFB = 128;            // tokens per block
 constexpr int kFP = kFB + 8;        // LDS pitch (elements) of a transposed column
 constexpr int kFK = kFB / 32;       // 32-token contraction steps per block
@@ -1005,6 +1006,33 @@ __global__ __launch_bounds__(kCBlock) void compress_project_fast_kv(CompressPara
   project_fast_body<DT, 3>(p, static_cast<int>(blockIdx.z) - (second ? BH : 0));
 }
 
+// Sum of the token-chunk partials of four consecutive coefficients, in chunk order (reproducible) and
+// in fp64: the partials of a slow out-of-band tone are individually large and cancel, and an fp32
+// running sum over many chunks would lose what the chunks themselves resolved.
+__device__ __forceinline__ void reduce_chunks(const float* part, float* coeffs, size_t total, size_t stride,
+                                              int Sc, int accumulate, size_t idx) {
+  if (idx + 4 <= total) {
+    double v0 = 0.0, v1 = 0.0, v2 = 0.0, v3 = 0.0;
+    if (accumulate) {
+      const f32x4 c = *reinterpret_cast<const f32x4*>(coeffs + idx);
+      v0 = c[0], v1 = c[1], v2 = c[2], v3 = c[3];
+    }
+#pragma unroll 8
+    for (int s = 0; s < Sc; ++s) {
+      const f32x4 t = *reinterpret_cast<const f32x4*>(part + static_cast<size_t>(s) * stride + idx);
+      v0 += t[0], v1 += t[1], v2 += t[2], v3 += t[3];
+    }
+    *reinterpret_cast<f32x4*>(coeffs + idx) =
+        f32x4{static_cast<float>(v0), static_cast<float>(v1), static_cast<float>(v2), static_cast<float>(v3)};
+  } else {
+    for (size_t k = idx; k < total; ++k) {
+      double v = accumulate ? coeffs[k] : 0.0f;
+      for (int s = 0; s < Sc; ++s) v += part[static_cast<size_t>(s) * stride + k];
+      coeffs[k] = static_cast<float>(v);
+    }
+  }
+}
+
 // the chunk reduction of both tensors in one launch (grid y: 0 = K, 1 = V)
 struct ReducePair {
   const float* part[2];
@@ -1019,37 +1047,15 @@ __global__ __launch_bounds__(256) void compress_reduce_kv(ReducePair r) {
   const size_t total = y ? r.total[1] : r.total[0], stride = y ? r.stride[1] : r.stride[0];
   const size_t idx = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
   if (idx >= total) return;
-  if (idx + 4 <= total) {
-    f32x4 v = r.accumulate ? *reinterpret_cast<const f32x4*>(coeffs + idx) : f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-    for (int s = 0; s < r.Sc; ++s) v += *reinterpret_cast<const f32x4*>(part + static_cast<size_t>(s) * stride + idx);
-    *reinterpret_cast<f32x4*>(coeffs + idx) = v;
-  } else {
-    for (size_t k = idx; k < total; ++k) {
-      float v = r.accumulate ? coeffs[k] : 0.0f;
-      for (int s = 0; s < r.Sc; ++s) v += part[static_cast<size_t>(s) * stride + k];
-      coeffs[k] = v;
-    }
-  }
+  reduce_chunks(part, coeffs, total, stride, r.Sc, r.accumulate, idx);
 }
 
-// sum of the token-chunk partials (fixed order, so results are reproducible)
+// the chunk reduction of one tensor
 __global__ __launch_bounds__(256) void compress_reduce(const float* part, float* coeffs, size_t total,
                                                        size_t stride, int Sc, int accumulate) {
   const size_t idx = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
   if (idx >= total) return;
-  if (idx + 4 <= total) {
-    f32x4 v = accumulate ? *reinterpret_cast<const f32x4*>(coeffs + idx) : f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-    for (int s = 0; s < Sc; ++s) v += *reinterpret_cast<const f32x4*>(part + static_cast<size_t>(s) * stride + idx);
-    *reinterpret_cast<f32x4*>(coeffs + idx) = v;
-  } else {
-    for (size_t k = idx; k < total; ++k) {
-      float v = accumulate ? coeffs[k] : 0.0f;
-      for (int s = 0; s < Sc; ++s) v += part[static_cast<size_t>(s) * stride + k];
-      coeffs[k] = v;
-    }
-  }
+  reduce_chunks(part, coeffs, total, stride, Sc, accumulate, idx);
 }
 
 struct CompressPlan {
@@ -1075,7 +1081,11 @@ static CompressPlan make_compress_plan(int dtype, int B, int H, int N, int D, in
   const long cap = nblocks / 8 > 0 ? nblocks / 8 : 1;     // but at least 1024 tokens per chunk: the
   if (want > cap) want = cap;                             // chunk partials cost memory traffic
   if (want < 1) want = 1;
-  const long per = N > 0 ? (nblocks + want - 1) / want : 1;
+  long per = N > 0 ? (nblocks + want - 1) / want : 1;
+  // fp32 inputs: an fp32 accumulator that runs over n tokens of a slow tone the band misses ends
+  // with an error of about 2^-24 * n / 11 of sqrt(N) * rms(x), the scale the 1e-5 parity bound is
+  // taken against; 512 tokens per chunk keep that three times below the bound for any N
+  if (dtype == FA_F32 && per > kF32ChunkBlocks) per = kF32ChunkBlocks;
   pl.chunk = static_cast<int>(per) * kFB;
   pl.Sc = N > 0 ? (N + pl.chunk - 1) / pl.chunk : 0;
   pl.total = (pl.Sc > 1 && Dc > 0)
@@ -1145,7 +1155,10 @@ extern "C" {
 
 size_t fa_compress_workspace_bytes(int B, int H, int N, int D, int Dc, int M) {
   if (fa::check_compress_shapes(FA_BF16, B, H, N, D, Dc, M, M > N ? M : N, 0) != FA_OK) return 0;
-  const size_t t = fa::make_compress_plan(FA_BF16, B, H, N, D, Dc, M, FA_KEEP_ROWS, 0).total;
+  // enough for either element type (fp32 inputs use shorter token chunks, hence more partials)
+  const size_t tb = fa::make_compress_plan(FA_BF16, B, H, N, D, Dc, M, FA_KEEP_ROWS, 0).total;
+  const size_t tf = fa::make_compress_plan(FA_F32, B, H, N, D, Dc, M, FA_KEEP_ROWS, 0).total;
+  const size_t t = tb > tf ? tb : tf;
   return t ? t : 256;
 }
 
