@@ -129,6 +129,12 @@ def small_variants():
                 Dkc=128, Dvc=192, M=16, dtype="f32"),
         replace(base, name="all_compress_bf16", index=24, B=2, Hq=4, Hkv=2, D=128, N=650, Lw=30,
                 Dkc=128, Dvc=128, M=33, dtype="bf16"),
+        # a short period with a tone next to the Nyquist order (the bf16 basis takes few distinct
+        # values) and a long fp32 segment whose band (the mean alone) misses every tone
+        replace(base, name="short_period", index=25, B=1, Hq=2, Hkv=2, D=128, N=80, Lw=12,
+                Dkc=96, Dvc=96, M=72, dtype="bf16"),
+        replace(base, name="f32_mean_only", index=26, B=2, Hq=3, Hkv=1, D=64, N=1878, Lw=113, Li=3,
+                Dkc=55, Dvc=23, M=1, dtype="f32"),
         replace(base, name="m512", index=23, B=1, Hq=4, Hkv=1, D=128, N=1500, Lw=40,
                 Dkc=112, Dvc=112, M=512, dtype="bf16"),
     )
