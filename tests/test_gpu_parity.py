@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 import torch
 
-from workloads import CONFIGS, rel_err, small_variants
+from workloads import CONFIGS, random_variants, rel_err, small_variants
 from fa_testlib import (cached_context, oracle_decode_heads, oracle_state, rows_pad8, rows_to_tok8,
                         sample_heads, to_dev)
 
@@ -98,6 +98,16 @@ def test_compress_small(cfg):
 def test_decode_small(cfg):
     print(f"[case] decode {cfg}", flush=True)
     _check_decode(cfg, sample_heads(cfg, None))
+
+
+@pytest.mark.parametrize("seed,count", [(7, 80), (3, 40)])
+def test_random_shapes(seed, count):
+    """Seeded random small shapes: compress, then decode, on up to three (sequence, head) pairs each."""
+    for i, cfg in enumerate(random_variants(seed, count)):
+        print(f"[case] random {cfg}", flush=True)
+        heads = sample_heads(cfg, 3, seed=i)
+        ctx, st = _check_compress(cfg, heads)
+        _check_decode(cfg, heads, ctx, st)
 
 
 @pytest.mark.parametrize("cfg", SMALL[:4], ids=[c.name for c in SMALL[:4]])

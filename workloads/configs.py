@@ -10,6 +10,8 @@ from __future__ import annotations
 
 from dataclasses import dataclass, replace
 
+import numpy as np
+
 
 @dataclass(frozen=True)
 class FAConfig:
@@ -138,3 +140,35 @@ def small_variants():
         replace(base, name="m512", index=23, B=1, Hq=4, Hkv=1, D=128, N=1500, Lw=40,
                 Dkc=112, Dvc=112, M=512, dtype="bf16"),
     )
+
+
+def random_variants(seed: int, count: int):
+    """`count` random small shapes (seeded): both element types, head dims 64 to 256, any
+    split of the head dims between kept and compressed, segment lengths 0 to 2600 with 1 <= M <= N,
+    sink and window lengths from zero up.  The parity tests run them next to the hand-picked
+    shapes above; they are what found the short-period and mean-only cases."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        D = int(rng.choice([64, 128, 128, 128, 192, 256]))
+        Hkv = int(rng.integers(1, 4))
+        G = int(rng.choice([1, 2, 3, 4, 8]))
+        B = int(rng.integers(1, 3))
+        N = int(rng.integers(1, 2600))
+        Li = int(rng.integers(0, 5))
+        Lw = int(rng.integers(0, 300))
+        if rng.random() < 0.1:
+            N = 0
+        if N + Li + Lw == 0:
+            Lw = 5
+        Dkc = int(rng.integers(0, D + 1))
+        Dvc = int(rng.integers(0, D + 1))
+        if rng.random() < 0.5:
+            Dkc, Dvc = (Dkc // 8) * 8, (Dvc // 8) * 8
+        if D - Dvc > 128:
+            Dvc = D - 128           # at most 128 kept V dims per head
+        Mmax = 512 if dtype == "bf16" else 256
+        M = int(rng.integers(1, min(Mmax, max(N, 1)) + 1)) if N > 0 else int(rng.integers(1, 64))
+        out.append(FAConfig(f"random{seed}_{i}", 500 + i, B, Hkv * G, Hkv, D, dtype, Li, Lw, N, Dkc, Dvc, M))
+    return tuple(out)
