@@ -645,7 +645,10 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
   constexpr unsigned kXsBytes = kWaves * kRB * 64 * 16;
   ES* pse = reinterpret_cast<ES*>(smem + kXsBytes);             // [kXN][16][4][8] probabilities, series type
   T* pte = reinterpret_cast<T*>(smem + kXsBytes + kXN * 16 * 4 * 8 * sizeof(ES));   // same, element type
-  float* alpha_s = reinterpret_cast<float*>(smem + kXsBytes + kXN * 16 * 4 * 8 * (sizeof(ES) + sizeof(T)));   // [16]
+  // what the element-type rounding of the probabilities dropped (16-bit element types only): the kept-V
+  // product takes both tiles, so a diffuse softmax does not see 2^-9 rounding noise in its output
+  T* ptl = reinterpret_cast<T*>(smem + kXsBytes + kXN * 16 * 4 * 8 * (sizeof(ES) + sizeof(T)));
+  float* alpha_s = reinterpret_cast<float*>(smem + kXsBytes + kXN * 16 * 4 * 8 * (sizeof(ES) + 2 * sizeof(T)));   // [16]
   float* st_m = alpha_s + 16;                                   // [16] column maxima (after the loop)
   float* st_l = st_m + 16;                                      // [16] column sums
   float* red_r = reinterpret_cast<float*>(smem);                // after the loop: [16][Mint + 4]
@@ -979,6 +982,13 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
         w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[0], pv[1]}, bf16x2));
         w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[2], pv[3]}, bf16x2));
         *reinterpret_cast<u32x2d*>(reinterpret_cast<uint16_t*>(pte) + slot) = w;
+        float lo[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          lo[v] = pv[v] - __builtin_bit_cast(float, ((w[v >> 1] >> (16 * (v & 1))) & 0xffffu) << 16);
+        w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo[0], lo[1]}, bf16x2));
+        w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo[2], lo[3]}, bf16x2));
+        *reinterpret_cast<u32x2d*>(reinterpret_cast<uint16_t*>(ptl) + slot) = w;
       }
       if (lane < 4) alpha_s[ocol] = alpha;
     }
@@ -1006,13 +1016,16 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
 
     if (traced) FA_STAMP(10);
     // -- (f) V side, own orders: r' += P^T E ------------------------------------------------------
-    Frag<T> pt[kXN];
+    Frag<T> pt[kXN], pl[kXN];
 #pragma unroll
     for (int x = 0; x < kXN; ++x) {
       Frag<ES> ps;
       ps.load(pse + ((x * 16 + r16) * 4 + q4) * 8);
       if constexpr (sizeof(ES) == 4) pt[x].load(reinterpret_cast<const T*>(pse) + ((x * 16 + r16) * 4 + q4) * 8);
-      else pt[x].load(pte + ((x * 16 + r16) * 4 + q4) * 8);
+      else {
+        pt[x].load(pte + ((x * 16 + r16) * 4 + q4) * 8);
+        if (DVT > 0) pl[x].load(ptl + ((x * 16 + r16) * 4 + q4) * 8);
+      }
 #pragma unroll
       for (int i = 0; i < CW; ++i) {
         mma_k32(racc[2 * i], ps, eB[i][0][x]);
@@ -1030,6 +1043,13 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
           const Frag<T> p1 = pt[1];
           if (vid & 1) ak = p1;
           if (col_k != (vid >> 1)) ak.zero();
+          Frag<T> al;
+          if constexpr (sizeof(ES) != 4) {
+            al = pl[0];
+            const Frag<T> l1 = pl[1];
+            if (vid & 1) al = l1;
+            if (col_k != (vid >> 1)) al.zero();
+          }
 #pragma unroll
           for (int dt = 0; dt < DVTM; ++dt) {
             if (dt < DVT) {
@@ -1038,6 +1058,7 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
               else bv.load(v_ptr(base, vid, dt));
               if (tail || vragged) fix_v(bv, base, vid, dt);
               mma_k32(oacc[dt], ak, bv);
+              if constexpr (sizeof(ES) != 4) mma_k32(oacc[dt], al, bv);
             }
           }
         }
