@@ -137,6 +137,10 @@ def small_variants():
                 Dkc=96, Dvc=96, M=72, dtype="bf16"),
         replace(base, name="f32_mean_only", index=26, B=2, Hq=3, Hkv=1, D=64, N=1878, Lw=113, Li=3,
                 Dkc=55, Dvc=23, M=1, dtype="f32"),
+        # a diffuse softmax (few compressed K dims, so small scores) over unstructured kept V dims:
+        # the output is a near-cancelling average and shows any rounding of the probabilities
+        replace(base, name="diffuse_kept_v", index=827, B=2, Hq=6, Hkv=3, D=64, N=2329, Lw=137, Li=2,
+                Dkc=6, Dvc=3, M=304, dtype="bf16"),
         replace(base, name="m512", index=23, B=1, Hq=4, Hkv=1, D=128, N=1500, Lw=40,
                 Dkc=112, Dvc=112, M=512, dtype="bf16"),
     )
