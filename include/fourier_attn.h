@@ -24,9 +24,10 @@
  *
  * Conventions shared by every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
- *     allocates nothing, keeps no global state and never synchronises: work
- *     is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
- *     default stream) and the call returns immediately.
+ *     allocates nothing and never synchronises: work is enqueued on
+ *     `hip_stream` (a hipStream_t passed as void*, NULL = the default stream)
+ *     and the call returns immediately.  The only state the library keeps
+ *     between calls is none that affects results.
  *   - Arguments are validated on the host before anything is launched; an
  *     invalid call launches nothing and returns a negative status.
  *   - Nothing throws, aborts or prints.
@@ -72,7 +73,9 @@ enum { FA_KEEP_ROWS = 0, FA_KEEP_TOK8 = 1 };
 #define FA_MAX_HEAD_DIM 256   /* D, must be a multiple of 8                     */
 #define FA_MAX_GROUP 16       /* query heads per KV head                         */
 #define FA_MAX_STATES 1024    /* M accepted by fa_compress                        */
-#define FA_MAX_DECODE_STATES 512 /* M accepted by fa_decode (256 for FA_F32)       */
+#define FA_MAX_DECODE_STATES 512 /* M accepted by fa_decode for FA_BF16              */
+#define FA_MAX_DECODE_STATES_F32 256 /* M accepted by fa_decode for FA_F32           */
+#define FA_MAX_KEPT_V_DIMS 128 /* D - Dvc accepted by fa_decode                     */
 #define FA_MAX_SPLITS 256     /* token-axis chunks of fa_decode                  */
 
 /*

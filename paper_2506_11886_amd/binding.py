@@ -11,8 +11,16 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfourier_attn.so")
 
 FA_OK = 0
+FA_ERR_NULL, FA_ERR_SHAPE, FA_ERR_UNSUPPORTED, FA_ERR_WORKSPACE, FA_ERR_HIP = -1, -2, -3, -4, -5
 FA_F32, FA_BF16 = 0, 1
 FA_KEEP_ROWS, FA_KEEP_TOK8 = 0, 1
+# compiled limits, as declared in include/fourier_attn.h
+FA_MAX_HEAD_DIM = 256
+FA_MAX_GROUP = 16
+FA_MAX_STATES = 1024
+FA_MAX_DECODE_STATES = 512
+FA_MAX_DECODE_STATES_F32 = 256
+FA_MAX_KEPT_V_DIMS = 128
 
 
 class FourierAttnError(RuntimeError):

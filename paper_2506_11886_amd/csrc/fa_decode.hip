@@ -1550,15 +1550,12 @@ static int check_decode_shapes(int dtype, int B, int Hq, int Hkv, int D, int Dkc
 template <typename T, int CW, int DVTM, bool KC1>
 static int launch_partial(const DecodeParams& p, unsigned lds, hipStream_t st, KernelTimers* tm) {
   auto kern = decode_partial<T, CW, DVTM, KC1>;
-  // raising the dynamic-LDS ceiling is a property of the loaded kernel: do it once
-  static unsigned granted = 48 * 1024;
-  if (lds > granted) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(kMaxDynLds)) != hipSuccess)
-      return FA_ERR_HIP;
-    granted = kMaxDynLds;
-  }
+  // the dynamic-LDS ceiling is a property of the kernel as loaded on the current device: raised
+  // whenever a launch needs it (a host-side table write, no stream operation)
+  if (lds > 48u * 1024u &&
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          static_cast<int>(kMaxDynLds)) != hipSuccess)
+    return FA_ERR_HIP;
   dim3 g2(p.Sw + p.Sm, p.B * p.Hkv);
   FA_LAUNCH_TIMED(tm, 1, kern, g2, dim3(kBlock), lds, st, p);
   return FA_OK;
@@ -1568,6 +1565,7 @@ static int launch_partial(const DecodeParams& p, unsigned lds, hipStream_t st, K
 template <typename T>
 static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_t st, KernelTimers* tm) {
   const int BH = p.B * p.Hkv;
+  const hipError_t prior = hipPeekAtLastError();
   if (p.Sm > 0) {
     if (static_cast<long>(BH) * ((p.Mint + 32) / 32) >= 512) {
       dim3 g1((p.Mint + 32) / 32, BH);
@@ -1602,7 +1600,9 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
   } else {
     FA_LAUNCH_TIMED(tm, 2, (decode_finish<T, 32>), dim3((p.D + 31) / 32, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
   }
-  return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
+  // only this call's launches are reported: an error some earlier, unrelated HIP call of the
+  // application left behind is neither returned nor cleared
+  return (hipPeekAtLastError() == hipSuccess || prior != hipSuccess) ? FA_OK : FA_ERR_HIP;
 }
 
 }  // namespace fa
@@ -1639,7 +1639,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   // Tq query tokens per sequence are Tq * Hq query heads to every kernel (group index = token * G +
   // head); only the full-width rows know about tokens: the last Tq rows are the new tokens, and
   // query t sees new tokens 0 .. t
-  if (Tq < 1 || (Tq > 1 && Tq > W) || Hq <= 0 || Hkv <= 0) return FA_ERR_SHAPE;
+  if (Tq < 1 || (Tq > 1 && Tq > W) || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return FA_ERR_SHAPE;
   const int Gq = Hq / Hkv;
   if (static_cast<long>(Hq) * Tq / Hkv > FA_MAX_GROUP) return FA_ERR_UNSUPPORTED;
   Hq *= Tq;

@@ -47,9 +47,9 @@ def oracle_state(cfg, ctx, heads=None):
     kk = np.zeros((B, H, N, D - cfg.Dkc), np.float32); vk = np.zeros((B, H, N, D - cfg.Dvc), np.float32)
     todo = heads if heads is not None else [(b, h) for b in range(B) for h in range(H)]
     for b, h in todo:
-        c, k = fk.compress_segment(ctx["k_mid"][b, h], ctx["kmask"][b, h], M, T, 0)
+        c, k = fk.compress_segment(ctx["k_mid"][b, h], ctx["kmask"][b, h], M, T, cfg.t0)
         ck[b, h], kk[b, h] = c, k
-        c, k = fk.compress_segment(ctx["v_mid"][b, h], ctx["vmask"][b, h], M, T, 0)
+        c, k = fk.compress_segment(ctx["v_mid"][b, h], ctx["vmask"][b, h], M, T, cfg.t0)
         cv[b, h], vk[b, h] = c, k
     return {"ck": ck, "cv": cv, "kk": kk, "vk": vk,
             "ck32": ck.astype(np.float32), "cv32": cv.astype(np.float32)}
@@ -64,7 +64,7 @@ def oracle_decode_heads(cfg, ctx, st, heads, from_f32_coeffs=True):
         cv = st["cv32"][b, h].astype(np.float64) if from_f32_coeffs else st["cv"][b, h]
         out[(b, h)] = fk.decode_head_group(
             ctx["q"][b, h * G:(h + 1) * G], ck, ctx["kmask"][b, h], cv, ctx["vmask"][b, h],
-            cfg.T, 0, cfg.N, st["kk"][b, h], st["vk"][b, h], ctx["k_full"][b, h], ctx["v_full"][b, h])
+            cfg.T, cfg.t0, cfg.N, st["kk"][b, h], st["vk"][b, h], ctx["k_full"][b, h], ctx["v_full"][b, h])
     return out
 
 

@@ -25,17 +25,38 @@ def _gpu_compress(cfg, ctx):
     fa = _fa()
     k_mid, v_mid = to_dev(ctx["k_mid"], cfg), to_dev(ctx["v_mid"], cfg)
     kmask, vmask = to_dev(ctx["kmask"]), to_dev(ctx["vmask"])
-    ck, kk = fa.fa_compress(k_mid, kmask, cfg.Dkc, cfg.M, cfg.T, keep_layout=fa.FA_KEEP_ROWS)
-    cv, vk = fa.fa_compress(v_mid, vmask, cfg.Dvc, cfg.M, cfg.T, keep_layout=fa.FA_KEEP_TOK8)
+    ck, kk = fa.fa_compress(k_mid, kmask, cfg.Dkc, cfg.M, cfg.T, t0=cfg.t0, keep_layout=fa.FA_KEEP_ROWS)
+    cv, vk = fa.fa_compress(v_mid, vmask, cfg.Dvc, cfg.M, cfg.T, t0=cfg.t0, keep_layout=fa.FA_KEEP_TOK8)
     torch.cuda.synchronize()
     return ck, kk, cv, vk, kmask, vmask
 
 
-def _check_compress(cfg, heads):
+def _compress_supported(cfg):
+    fa = _fa()
+    return cfg.M <= fa.FA_MAX_STATES
+
+
+def _decode_supported(cfg):
+    """The documented limits of fa_decode (include/fourier_attn.h); shapes beyond them must be refused."""
+    fa = _fa()
+    m_max = fa.FA_MAX_DECODE_STATES if cfg.dtype == "bf16" else fa.FA_MAX_DECODE_STATES_F32
+    return cfg.M <= m_max and cfg.D - cfg.Dvc <= fa.FA_MAX_KEPT_V_DIMS and cfg.G <= fa.FA_MAX_GROUP
+
+
+def _expect_unsupported(call, what):
+    fa = _fa()
+    with pytest.raises(fa.FourierAttnError) as e:
+        call()
+    assert e.value.status == fa.FA_ERR_UNSUPPORTED, (what, e.value.status)
+
+
+def _check_compress(cfg, heads, keep_gpu=False):
     fa = _fa()
     ctx = cached_context(cfg)
     st = oracle_state(cfg, ctx, heads)
     ck, kk, cv, vk, _, _ = _gpu_compress(cfg, ctx)
+    if keep_gpu:
+        st["gpu"] = (ck, kk, cv, vk)
     ck, cv = ck.cpu().numpy(), cv.cpu().numpy()
     kk = kk.float().cpu().numpy()
     Dku = cfg.D - cfg.Dkc
@@ -64,7 +85,7 @@ def _gpu_decode(cfg, ctx, ck, cv, kk_rows, vk_tok8, num_splits=None):
     fa = _fa()
     return fa.fa_decode(
         to_dev(ctx["q"], cfg), ck, to_dev(ctx["kmask"]), cv, to_dev(ctx["vmask"]),
-        cfg.M, cfg.T, 0, cfg.N, kk_rows, vk_tok8,
+        cfg.M, cfg.T, cfg.t0, cfg.N, kk_rows, vk_tok8,
         to_dev(ctx["k_full"], cfg), to_dev(ctx["v_full"], cfg),
         num_splits=cfg.num_splits if num_splits is None else num_splits)
 
@@ -102,12 +123,25 @@ def test_decode_small(cfg):
 
 @pytest.mark.parametrize("seed,count", [(7, 80), (3, 40)])
 def test_random_shapes(seed, count):
-    """Seeded random small shapes: compress, then decode, on up to three (sequence, head) pairs each."""
+    """Seeded random small shapes: compress, then decode, on up to three (sequence, head) pairs each.
+    The generator knows no kernel limit: a shape beyond the documented limits of an entry point must
+    be refused with FA_ERR_UNSUPPORTED (and nothing launched), every other shape must match the oracle."""
+    refused = 0
     for i, cfg in enumerate(random_variants(seed, count)):
         print(f"[case] random {cfg}", flush=True)
         heads = sample_heads(cfg, 3, seed=i)
+        if not _compress_supported(cfg):
+            _expect_unsupported(lambda: _gpu_compress(cfg, cached_context(cfg)), ("compress", cfg))
+            refused += 1
+            continue
         ctx, st = _check_compress(cfg, heads)
+        if not _decode_supported(cfg):
+            _expect_unsupported(lambda: _check_decode(cfg, heads, ctx, st), ("decode", cfg))
+            refused += 1
+            continue
         _check_decode(cfg, heads, ctx, st)
+    print(f"[case] random seed {seed}: {refused} of {count} shapes beyond the limits, refused", flush=True)
+    assert refused < count // 2
 
 
 @pytest.mark.parametrize("cfg", SMALL[:4], ids=[c.name for c in SMALL[:4]])
@@ -133,19 +167,41 @@ def test_decode_split_count_invariance(splits):
     _check_decode(cfg, sample_heads(cfg, None), num_splits=splits)
 
 
-FULL = {2: 3, 3: 6, 4: 2, 5: 8}   # config index -> number of (b, kv head) pairs the oracle checks
-
-
-@pytest.mark.parametrize("idx", sorted(FULL))
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
 def test_full_size_config(idx):
-    """BASELINE sizes in the launch configuration the benchmark times; the
-    oracle evaluates a sample of (sequence, KV head) pairs."""
+    """BASELINE sizes in the launch configuration the benchmark times.  EVERY (sequence, KV head) pair is
+    compared with the oracle three ways: fa_compress alone (coefficients within tolerance, kept dims
+    bit-exact), fa_decode alone (fed the oracle's coefficients and kept dims), and the two chained on the
+    GPU (GPU coefficients and kept dims into fa_decode), so that their errors are seen to compound."""
+    import oracle.fourier_kv as fk
     cfg = CONFIGS[idx - 1]
     print(f"[case] full-size {cfg}", flush=True)
-    heads = sample_heads(cfg, FULL[idx], seed=idx)
-    ctx, st = _check_compress(cfg, heads)
-    print("[case] full-size compress ok, decode next", flush=True)
-    _check_decode(cfg, heads, ctx, st)
+    heads = sample_heads(cfg, None)
+    ctx, st = _check_compress(cfg, heads, keep_gpu=True)
+    print("[case] full-size compress ok on every head, decode next", flush=True)
+    ck_g, kk_g, cv_g, vk_g = st["gpu"]
+    out_alone = _gpu_decode(cfg, ctx, to_dev(st["ck32"]), to_dev(st["cv32"]),
+                            to_dev(rows_pad8(st["kk"]), cfg), to_dev(rows_to_tok8(st["vk"]), cfg))
+    out_chain = _gpu_decode(cfg, ctx, ck_g, cv_g, kk_g, vk_g)
+    torch.cuda.synchronize()
+    out_alone, out_chain = out_alone.cpu().numpy(), out_chain.cpu().numpy()
+    assert np.isfinite(out_alone).all() and np.isfinite(out_chain).all()
+    G = cfg.G
+    worst = [0.0, 0.0]
+    for n, (b, h) in enumerate(heads):
+        # one oracle decode per head, from the fp64 coefficients (rounding them to fp32 first moves the
+        # result by ~1e-7 of its size, far inside the tolerance)
+        want = fk.decode_head_group(ctx["q"][b, h * G:(h + 1) * G], st["ck"][b, h], ctx["kmask"][b, h], st["cv"][b, h],
+                                    ctx["vmask"][b, h], cfg.T, cfg.t0, cfg.N, st["kk"][b, h], st["vk"][b, h],
+                                    ctx["k_full"][b, h], ctx["v_full"][b, h])
+        e0 = rel_err(out_alone[b, h * G:(h + 1) * G], want)
+        e1 = rel_err(out_chain[b, h * G:(h + 1) * G], want)
+        worst = [max(worst[0], e0), max(worst[1], e1)]
+        assert e0 <= cfg.tol, ("decode alone", b, h, e0)
+        assert e1 <= cfg.tol, ("compress -> decode", b, h, e1)
+        if n % 16 == 0:
+            print(f"[case] full-size head {n + 1}/{len(heads)} ok", flush=True)
+    print(f"[case] full-size cfg{idx}: worst error decode alone {worst[0]:.2e}, chained {worst[1]:.2e}", flush=True)
 
 
 def test_compress_streaming_update_matches_one_shot():
@@ -169,10 +225,40 @@ def test_compress_streaming_update_matches_one_shot():
     assert torch.equal(keep, keep_full)
 
 
+@pytest.mark.parametrize("name,a", [("gqa8_oddM", 501), ("tiny_bf16", 13), ("tiny", 100), ("mha_ragged", 1003)])
+def test_compress_tok8_append_at_unaligned_offset(name, a):
+    """V^mu in groups of eight tokens, written in two calls whose boundary is NOT a multiple of 8 (the
+    second call starts inside a group the first one left half full): the slab must equal the one-shot
+    slab bit for bit, the coefficients within tolerance."""
+    fa = _fa()
+    cfg = next(c for c in SMALL if c.name == name)
+    print(f"[case] TOK8 unaligned append {cfg} a={a}", flush=True)
+    ctx = cached_context(cfg)
+    x, mask = to_dev(ctx["v_mid"], cfg), to_dev(ctx["vmask"])
+    full, keep_full = fa.fa_compress(x, mask, cfg.Dvc, cfg.M, cfg.T, keep_layout=fa.FA_KEEP_TOK8)
+    keep = torch.zeros_like(keep_full)
+    slab = keep_full.stride(1)
+    c, _ = fa.fa_compress(x[:, :, :a], mask, cfg.Dvc, cfg.M, cfg.T, x_keep=keep, keep_layout=fa.FA_KEEP_TOK8,
+                          keep_stride_bh=slab)
+    fa.fa_compress(x[:, :, a:], mask, cfg.Dvc, cfg.M, cfg.T, t0=a, accumulate=True, coeffs=c, x_keep=keep,
+                   keep_layout=fa.FA_KEEP_TOK8, keep_offset=a, keep_stride_bh=slab)
+    torch.cuda.synchronize()
+    assert a % 8 != 0
+    view = (lambda t: t.view(torch.int16)) if keep.dtype == torch.bfloat16 else (lambda t: t)
+    assert torch.equal(view(keep), view(keep_full))
+    assert rel_err(c.cpu().numpy(), full.cpu().numpy()) <= cfg.tol
+    # and against the oracle's kept dims
+    st = oracle_state(cfg, ctx, [(0, 0)])
+    got = fa.keep_rows_from_tok8(keep, cfg.N, cfg.D - cfg.Dvc).float().cpu().numpy()
+    assert np.array_equal(got[0, 0], st["vk"][0, 0])
+
+
 @pytest.mark.parametrize("name", ["tiny", "gqa8_oddM", "odd_dims"])
 def test_append_steps_match_oracle(name):
-    """fa_append (Eq. 5 + window ring), several steps in a row, against oracle.append_token; then
-    one decode over the streamed state against the oracle's decode over its streamed state."""
+    """fa_append (Eq. 5 + window ring), several steps in a row, against oracle.append_token, with a
+    decode over the streamed state after the first, a middle and the last step (the segment then
+    covers only part of the period, as it does while a sequence is still growing) against the
+    oracle's decode over its streamed state."""
     import oracle.fourier_kv as fk
     fa = _fa()
     cfg = next(c for c in SMALL if c.name == name)
@@ -200,12 +286,16 @@ def test_append_steps_match_oracle(name):
     cv, _ = fa.fa_compress(v_mid, vmask, cfg.Dvc, M, T, x_keep=vk, keep_layout=fa.FA_KEEP_TOK8,
                            keep_stride_bh=vk.stride(1))
     k_full, v_full = to_dev(ctx["k_full"], cfg), to_dev(ctx["v_full"], cfg)
+    decode_at = (0, 4, steps - 1)      # decode after these steps: the segment is then shorter than the period
+    outs = {}
+    qd = to_dev(ctx["q"], cfg)
     for s in range(steps):
         slot = Li + s % ring
         fa.fa_append(new_k[s].cuda(), new_v[s].cuda(), k_full, v_full, slot, True, kmask, vmask, M, T, N0 + s,
                      ck, cv, kk, vk, kk_stride_bh=kk.stride(1), vk_stride_bh=vk.stride(1))
-    out = fa.fa_decode(to_dev(ctx["q"], cfg), ck, kmask, cv, vmask, M, T, 0, N0 + steps, kk, vk, k_full, v_full,
-                       kk_stride_bh=kk.stride(1), vk_stride_bh=vk.stride(1))
+        if s in decode_at:
+            outs[s] = fa.fa_decode(qd, ck, kmask, cv, vmask, M, T, 0, N0 + s + 1, kk, vk, k_full, v_full,
+                                   kk_stride_bh=kk.stride(1), vk_stride_bh=vk.stride(1)).cpu().numpy()
     torch.cuda.synchronize()
 
     # --- oracle, head by head ---
@@ -214,7 +304,6 @@ def test_append_steps_match_oracle(name):
     vk_g = fa.keep_rows_from_tok8(vk, cfg.N, Dvu).float().cpu().numpy()
     kf_g, vf_g = k_full.float().cpu().numpy(), v_full.float().cpu().numpy()
     nk, nv = new_k.float().numpy().astype(np.float64), new_v.float().numpy().astype(np.float64)
-    out = out.cpu().numpy()
     for b in range(B):
         for h in range(H):
             km, vm = ctx["kmask"][b, h], ctx["vmask"][b, h]
@@ -224,6 +313,11 @@ def test_append_steps_match_oracle(name):
             for s in range(steps):
                 Ck, Cv, kko, vko, kf, vf = fk.append_token(Ck, Cv, km, vm, kko, vko, kf, vf, Li + s % ring,
                                                            nk[s, b, h], nv[s, b, h], T, N0 + s, True)
+                if s in decode_at:
+                    want = fk.decode_head_group(ctx["q"][b, h * G:(h + 1) * G], Ck, km, Cv, vm, T, 0, N0 + s + 1,
+                                                kko, vko, kf, vf)
+                    got = outs[s][b, h * G:(h + 1) * G]
+                    assert rel_err(got, want) <= cfg.tol, ("out after step", s, b, h, rel_err(got, want))
             if cfg.Dkc:
                 fl = np.sqrt((N0 + steps) * np.mean(ctx["k_mid"][b, h][:, km == 1].astype(np.float64) ** 2))
                 assert rel_err(ck_g[b, h], Ck, fl) <= cfg.tol, ("ck", b, h)
@@ -233,10 +327,6 @@ def test_append_steps_match_oracle(name):
             assert np.array_equal(kk_g[b, h][:N0 + steps], kko), ("k_keep", b, h)
             assert np.array_equal(vk_g[b, h][:N0 + steps], vko), ("v_keep", b, h)
             assert np.array_equal(kf_g[b, h], kf) and np.array_equal(vf_g[b, h], vf), ("ring", b, h)
-            want = fk.decode_head_group(ctx["q"][b, h * G:(h + 1) * G], Ck, km, Cv, vm, T, 0, N0 + steps,
-                                        kko, vko, kf, vf)
-            got = out[b, h * G:(h + 1) * G]
-            assert rel_err(got, want) <= cfg.tol, ("out", b, h, rel_err(got, want))
 
 
 def test_append_without_eviction_only_writes_the_row():

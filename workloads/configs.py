@@ -29,6 +29,8 @@ class FAConfig:
     Dvc: int
     M: int
     num_splits: int = 0  # 0 = library chooses
+    period: int = 0      # basis period T; 0 = one period spans the compressed segment
+    t0: int = 0          # basis position of the first middle row
 
     @property
     def W(self) -> int:
@@ -40,9 +42,10 @@ class FAConfig:
 
     @property
     def T(self) -> int:
-        # One period spans the compressed segment (the only choice for which
-        # the basis is orthogonal on it); never shorter than the band.
-        return max(self.N, self.M)
+        # By default one period spans the compressed segment (the only choice
+        # for which the basis is orthogonal on it); never shorter than the band.
+        # The paper sets T to the maximum context length: `period` > N.
+        return self.period if self.period > 0 else max(self.N, self.M)
 
     @property
     def G(self) -> int:
@@ -143,14 +146,26 @@ def small_variants():
                 Dkc=6, Dvc=3, M=304, dtype="bf16"),
         replace(base, name="m512", index=23, B=1, Hq=4, Hkv=1, D=128, N=1500, Lw=40,
                 Dkc=112, Dvc=112, M=512, dtype="bf16"),
+        # the paper's regime: the period is the maximum context length, the segment covers part of it
+        replace(base, name="period_2n", index=27, B=1, Hq=4, Hkv=1, D=128, N=1111, Lw=70,
+                Dkc=96, Dvc=104, M=96, dtype="bf16", period=2222),
+        replace(base, name="period_n37_f32", index=28, B=2, Hq=4, Hkv=2, D=64, N=600, Lw=50,
+                Dkc=40, Dvc=48, M=48, dtype="f32", period=637),
+        # a segment that starts inside the period (what a chunked prefill hands over)
+        replace(base, name="t0_offset", index=29, B=1, Hq=8, Hkv=2, D=128, N=900, Lw=33,
+                Dkc=96, Dvc=88, M=130, dtype="bf16", period=4000, t0=1237),
+        replace(base, name="t0_offset_f32", index=30, B=1, Hq=2, Hkv=1, D=64, N=333, Lw=9,
+                Dkc=48, Dvc=32, M=31, dtype="f32", period=1000, t0=667),
     )
 
 
 def random_variants(seed: int, count: int):
     """`count` random small shapes (seeded): both element types, head dims 64 to 256, any
     split of the head dims between kept and compressed, segment lengths 0 to 2600 with 1 <= M <= N,
-    sink and window lengths from zero up.  The parity tests run them next to the hand-picked
-    shapes above; they are what found the short-period and mean-only cases."""
+    sink and window lengths from zero up, periods equal to or longer than the segment.  Nothing
+    here knows the limits of any implementation: callers decide what to do with a shape their
+    kernels do not cover.  The parity tests run them next to the hand-picked shapes above; they
+    are what found the short-period and mean-only cases."""
     rng = np.random.default_rng(seed)
     out = []
     for i in range(count):
@@ -170,9 +185,12 @@ def random_variants(seed: int, count: int):
         Dvc = int(rng.integers(0, D + 1))
         if rng.random() < 0.5:
             Dkc, Dvc = (Dkc // 8) * 8, (Dvc // 8) * 8
-        if D - Dvc > 128:
-            Dvc = D - 128           # at most 128 kept V dims per head
-        Mmax = 512 if dtype == "bf16" else 256
-        M = int(rng.integers(1, min(Mmax, max(N, 1)) + 1)) if N > 0 else int(rng.integers(1, 64))
-        out.append(FAConfig(f"random{seed}_{i}", 500 + i, B, Hkv * G, Hkv, D, dtype, Li, Lw, N, Dkc, Dvc, M))
+        m_hi = 1100 if rng.random() < 0.35 else 300      # mostly M << N, the regime the method is meant for
+        M = int(rng.integers(1, min(m_hi, max(N, 1)) + 1)) if N > 0 else int(rng.integers(1, 64))
+        period, t0 = 0, 0
+        if N > 0 and rng.random() < 0.3:      # a period longer than the segment, the segment anywhere inside it
+            period = N + int(rng.integers(1, 3 * N + 2))
+            t0 = int(rng.integers(0, period - N + 1))
+        out.append(FAConfig(f"random{seed}_{i}", 500 + i, B, Hkv * G, Hkv, D, dtype, Li, Lw, N, Dkc, Dvc, M,
+                            period=period, t0=t0))
     return tuple(out)
