@@ -27,7 +27,9 @@
  *     allocates nothing and never synchronises: work is enqueued on
  *     `hip_stream` (a hipStream_t passed as void*, NULL = the default stream)
  *     and the call returns immediately.  The only state the library keeps
- *     between calls is none that affects results.
+ *     between calls is per process: which kernels have had their dynamic-LDS
+ *     ceiling raised, and (fa_decode_static) the device address of its static
+ *     scratch array on each GPU; neither affects results.
  *   - Arguments are validated on the host before anything is launched; an
  *     invalid call launches nothing and returns a negative status.
  *   - Nothing throws, aborts or prints.
@@ -56,7 +58,8 @@ enum {
   FA_ERR_SHAPE = -2,       /* inconsistent or out-of-range sizes              */
   FA_ERR_UNSUPPORTED = -3, /* legal problem, but outside the compiled limits  */
   FA_ERR_WORKSPACE = -4,   /* workspace too small or misaligned               */
-  FA_ERR_HIP = -5          /* a HIP launch reported an error                  */
+  FA_ERR_HIP = -5,         /* a HIP launch reported an error                  */
+  FA_ERR_SCRATCH = -6      /* fa_decode_static: the sizes need more than FA_STATIC_SCRATCH_BYTES */
 };
 
 /* element type of q / K / V / kept-dimension tensors */
@@ -151,6 +154,32 @@ int fa_decode(const void* q, int dtype,
 
 size_t fa_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int Dkc, int Dvc,
                                  int M, int N, int W, int num_splits);
+
+/*
+ * fa_decode_static -- fa_decode for callers that cannot allocate or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ *
+ * Same arguments, kernels and results as fa_decode, without `workspace` / `workspace_bytes`: the
+ * split-K state lives in a static device array of FA_STATIC_SCRATCH_BYTES inside the library (one
+ * copy per GPU, held until the process ends; its device address is looked up on the first call on
+ * each device).  The call allocates and frees nothing.  Sizes whose state
+ * (fa_decode_workspace_bytes(...)) exceeds FA_STATIC_SCRATCH_BYTES return FA_ERR_SCRATCH and launch
+ * nothing; the five benchmark configurations need 1 - 3 MB.
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two streams,
+ * two threads) race.  Calls on one stream, or otherwise ordered, are safe; nothing has to be
+ * cleared between them.
+ */
+#define FA_STATIC_SCRATCH_BYTES (8u << 20)
+int fa_decode_static(const void* q, int dtype,
+                     int B, int Hq, int Hkv, int D,
+                     const float* ck, const uint8_t* kmask, int Dkc,
+                     const float* cv, const uint8_t* vmask, int Dvc,
+                     int M, int T, int t0, int N,
+                     const void* k_keep, int64_t kk_stride_bh,
+                     const void* v_keep, int64_t vk_stride_bh,
+                     const void* k_full, const void* v_full, int W, int64_t full_stride_bh,
+                     float scale, int num_splits,
+                     float* out, void* hip_stream);
 
 /*
  * fa_append -- one decode step of cache maintenance (Eq. 5 and the recent window of Eq. 1).

@@ -11,7 +11,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfourier_attn.so")
 
 FA_OK = 0
-FA_ERR_NULL, FA_ERR_SHAPE, FA_ERR_UNSUPPORTED, FA_ERR_WORKSPACE, FA_ERR_HIP = -1, -2, -3, -4, -5
+FA_ERR_NULL, FA_ERR_SHAPE, FA_ERR_UNSUPPORTED, FA_ERR_WORKSPACE, FA_ERR_HIP, FA_ERR_SCRATCH = -1, -2, -3, -4, -5, -6
+FA_STATIC_SCRATCH_BYTES = 8 << 20
 FA_F32, FA_BF16 = 0, 1
 FA_KEEP_ROWS, FA_KEEP_TOK8 = 0, 1
 # compiled limits, as declared in include/fourier_attn.h
@@ -54,6 +55,8 @@ def _load(path: str = _LIB_PATH):
                               f32, i32, vp, vp, sz, vp]
     lib.fa_decode_timed.restype = i32
     lib.fa_decode_timed.argtypes = lib.fa_decode.argtypes + [c.POINTER(c.c_float)]
+    lib.fa_decode_static.restype = i32
+    lib.fa_decode_static.argtypes = lib.fa_decode.argtypes[:27] + [vp]
     lib.fa_decode_workspace_bytes.restype = sz
     lib.fa_decode_workspace_bytes.argtypes = [i32] * 10
     lib.fa_decode_default_splits.restype = i32
@@ -207,6 +210,28 @@ def fa_decode(q, ck, kmask, cv, vmask, M, T, t0, N, k_keep, v_keep, k_full, v_fu
         kernel_ms.extend(ms)
     if st != FA_OK:
         raise FourierAttnError(st, "fa_decode")
+    return out
+
+
+def fa_decode_static(q, ck, kmask, cv, vmask, M, T, t0, N, k_keep, v_keep, k_full, v_full,
+                     scale=0.0, num_splits=0, out=None, stream=None,
+                     kk_stride_bh=0, vk_stride_bh=0, full_stride_bh=0):
+    """Enqueue fa_decode_static on `stream`: fa_decode with the split-K state in the library's
+    static device array (no workspace; the call itself allocates nothing when `out` is passed)."""
+    B, Hq, D = q.shape
+    Hkv = kmask.shape[1]
+    Dkc = ck.shape[-1] if ck is not None else 0
+    Dvc = cv.shape[-1] if cv is not None else 0
+    W = k_full.shape[2] if k_full is not None else 0
+    if out is None:
+        out = torch.empty((B, Hq, D), dtype=torch.float32, device=q.device)
+    st = lib.fa_decode_static(_ptr(q), _dtype_code(q), B, Hq, Hkv, D,
+                              _ptr(ck), _ptr(kmask), Dkc, _ptr(cv), _ptr(vmask), Dvc,
+                              M, T, t0, N, _ptr(k_keep), kk_stride_bh, _ptr(v_keep), vk_stride_bh,
+                              _ptr(k_full), _ptr(v_full), W, full_stride_bh,
+                              float(scale), num_splits, _ptr(out), _stream_ptr(stream))
+    if st != FA_OK:
+        raise FourierAttnError(st, "fa_decode_static")
     return out
 
 

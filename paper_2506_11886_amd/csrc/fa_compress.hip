@@ -1421,6 +1421,7 @@ const char* fa_status_string(int status) {
     case FA_ERR_UNSUPPORTED: return "outside the compiled limits";
     case FA_ERR_WORKSPACE: return "workspace too small or misaligned";
     case FA_ERR_HIP: return "HIP launch error";
+    case FA_ERR_SCRATCH: return "problem needs more split-K state than the library's static scratch array holds";
     default: return "unknown status";
   }
 }

@@ -33,6 +33,7 @@
 //      applies diag(w) C_v to r and normalises.
 
 #include <cstdlib>
+#include <mutex>
 
 #include "fa_common.hpp"
 #include "fa_mma.hpp"
@@ -1724,6 +1725,56 @@ int fa_decode_mq(const void* q, int dtype, int B, int Tq, int Hq, int Hkv, int D
   return decode_impl(q, dtype, B, Hq, Hkv, D, ck, kmask, Dkc, cv, vmask, Dvc, M, T, t0, N, k_keep,
                      kk_stride_bh, v_keep, vk_stride_bh, k_full, v_full, W, full_stride_bh, scale,
                      num_splits, out, workspace, workspace_bytes, hip_stream, nullptr, Tq);
+}
+
+// ---------------------------------------------------------------------------
+// fa_decode_static: fa_decode with the split-K state in a static device array
+// ---------------------------------------------------------------------------
+// One array per GPU (every device that loads this code object holds its own copy
+// at its own address).  In host code the array's name only stands for the symbol;
+// the device address is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[FA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on device i (nullptr: not asked yet)
+
+// address of the current device's copy of `scratch`, or nullptr
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    scratch_ptr[dev] = ptr;
+  }
+  return scratch_ptr[dev];
+}
+}  // namespace
+
+int fa_decode_static(const void* q, int dtype, int B, int Hq, int Hkv, int D, const float* ck,
+                     const uint8_t* kmask, int Dkc, const float* cv, const uint8_t* vmask, int Dvc,
+                     int M, int T, int t0, int N, const void* k_keep, int64_t kk_stride_bh,
+                     const void* v_keep, int64_t vk_stride_bh, const void* k_full, const void* v_full,
+                     int W, int64_t full_stride_bh, float scale, int num_splits, float* out,
+                     void* hip_stream) {
+  // sizes first: a problem whose split-K state does not fit the array is refused before anything else
+  if (Hq > 0 && Hkv > 0 && Hq % Hkv == 0 &&
+      fa::check_decode_shapes(dtype, B, Hq, Hkv, D, Dkc, Dvc, M, T, t0, N, W, num_splits) == FA_OK) {
+    fa::DecodePlan pl{};
+    if (fa::make_plan(pl, dtype, B, Hq, Hkv, D, Dkc, Dvc, M, N, W, num_splits) &&
+        pl.total > static_cast<size_t>(FA_STATIC_SCRATCH_BYTES))
+      return FA_ERR_SCRATCH;
+  }
+  void* ws = static_scratch();
+  if (!ws) return FA_ERR_HIP;
+  // every float of the state that a kernel reads is written by an earlier kernel of the same call,
+  // so nothing has to be cleared between calls
+  return decode_impl(q, dtype, B, Hq, Hkv, D, ck, kmask, Dkc, cv, vmask, Dvc, M, T, t0, N, k_keep,
+                     kk_stride_bh, v_keep, vk_stride_bh, k_full, v_full, W, full_stride_bh, scale,
+                     num_splits, out, ws, FA_STATIC_SCRATCH_BYTES, hip_stream, nullptr);
 }
 
 int fa_decode_timed(const void* q, int dtype, int B, int Hq, int Hkv, int D, const float* ck,

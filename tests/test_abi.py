@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     assert {"fa_compress", "fa_decode", "fa_compress_workspace_bytes",
             "fa_decode_workspace_bytes", "fa_decode_default_splits", "fa_status_string",
             "fa_append", "fa_select_dims", "fa_select_workspace_bytes", "fa_decode_mq", "fa_compress_kv",
-            "fa_compress_kv_workspace_bytes"} <= names
+            "fa_compress_kv_workspace_bytes", "fa_decode_static"} <= names
     for n in names:
         assert hasattr(fa.lib, n), n
 
@@ -163,3 +163,19 @@ def test_compress_kv_rejects_bad_arguments_on_the_host():
     assert call(k=None) == -1
     assert fa.compress_kv_workspace_bytes(1, 8, 31740, 128, 96, 96, 256) >= 2 * fa.compress_workspace_bytes(1, 8, 31740, 128, 96, 256)
 
+
+def test_static_scratch_refuses_sizes_beyond_the_array():
+    from workloads import CONFIGS
+    fa = _fa()
+    fake = FAKE                          # never dereferenced: the size check comes first
+    # 64 sequences x 32 query heads x 256 chunks of middle rows: far more records than 8 MiB hold
+    need = fa.decode_workspace_bytes(64, 32, 8, 128, 96, 96, 256, 1 << 20, 1028, 256)
+    assert need > fa.FA_STATIC_SCRATCH_BYTES
+    st = fa.lib.fa_decode_static(fake, 1, 64, 32, 8, 128, fake, fake, 96, fake, fake, 96, 256, 1 << 20, 0, 1 << 20,
+                                 fake, 0, fake, 0, fake, fake, 1028, 0, 0.0, 256, fake, None)
+    assert st == fa.FA_ERR_SCRATCH
+    assert "scratch" in fa.status_string(st)
+    # the benchmark configurations fit
+    for c in CONFIGS:
+        assert 0 < fa.decode_workspace_bytes(c.B, c.Hq, c.Hkv, c.D, c.Dkc, c.Dvc, c.M, c.N, c.W, c.num_splits) \
+            <= fa.FA_STATIC_SCRATCH_BYTES
