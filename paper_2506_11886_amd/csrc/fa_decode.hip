@@ -34,6 +34,7 @@
 
 #include <cstdlib>
 #include <mutex>
+#include <type_traits>
 
 #include "fa_common.hpp"
 #include "fa_mma.hpp"
@@ -1171,6 +1172,460 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
   FA_STAMP(15);
 }
 
+// ---------------------------------------------------------------------------
+// 2c. middle rows, specialised: bf16, groups of at most four query heads, at most 32 kept dims
+// ---------------------------------------------------------------------------
+// The same algorithm and the same LDS layouts as partial_middle_rows, with every shape that
+// decides control flow fixed at compile time (four tiles per step, CW series chunks per wave,
+// DVT column tiles of kept V dims, GP = 1 or 4 score columns per tile), so that a step is one
+// straight-line instruction stream: no branch sits between a load and its use, every wait
+// names the exact number of younger requests, and the loads of the step after next are
+// issued unconditionally (clamped into the chunk) right after a step.  The V-side table
+// slices are evaluated directly (a rotation recurrence along the eight consecutive rows a
+// lane holds) instead of being transposed through LDS, which takes the barriers out of the
+// prologue.  The wave-wide maximum of the softmax uses the half- and row-swap lane permutes.
+
+// max over the four 16-lane rows of a wave, per lane position, result in every lane
+__device__ __forceinline__ float cross_row_max(float v) {
+  auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float cross_row_sum(float v) {
+  auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+template <int CW, int DVT, int GP>
+__device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsigned char* smem) {
+  using T = bf16_t;
+  using ES = f16_t;
+  constexpr int Mint = kWaves * CW * 32;
+  constexpr int KT = 4, step = KT * kTJ;
+  static_assert(GP == 1 || GP == 4, "score columns per tile");
+  static_assert(DVT == 1 || DVT == 2, "kept V column tiles");
+
+  const int sm_idx = blockIdx.x, bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int G = p.G;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q4 = lane >> 4, r16 = lane & 15;
+  const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
+  const int c0 = sm_idx * p.chunk_m, c1 = min(p.N, c0 + p.chunk_m);
+  const int nsteps = (c1 - c0 + step - 1) / step;
+  const int col_k = r16 / GP, col_h = r16 % GP;
+  const bool col_live = col_k < KT && col_h < G;
+  const int hsafe = min(col_h, G - 1);
+  const int kpitch = (p.Dku + 7) & ~7;               // 8 .. 32
+  constexpr int Dkq = 32;                             // pitch of the packed query rows
+  const int Dvu = p.Dvu;
+  const T* kk = static_cast<const T*>(p.k_keep) + bh * p.kk_stride;
+  const T* vk = static_cast<const T*>(p.v_keep) + bh * p.vk_stride;
+  const int Nm1 = p.N - 1;
+
+  // ---- LDS carve-up (as partial_middle_rows) -------------------------------
+  f32x4* xs = reinterpret_cast<f32x4*>(smem);
+  constexpr unsigned kXsBytes = kWaves * kRB * 64 * 16;
+  ES* pse = reinterpret_cast<ES*>(smem + kXsBytes);
+  T* pte = reinterpret_cast<T*>(smem + kXsBytes + kXN * 16 * 4 * 8 * sizeof(ES));
+  T* ptl = reinterpret_cast<T*>(smem + kXsBytes + kXN * 16 * 4 * 8 * (sizeof(ES) + sizeof(T)));
+  float* alpha_s = reinterpret_cast<float*>(smem + kXsBytes + kXN * 16 * 4 * 8 * (sizeof(ES) + 2 * sizeof(T)));
+  float* st_m = alpha_s + 16;
+  float* st_l = st_m + 16;
+  float* red_r = reinterpret_cast<float*>(smem);
+  constexpr int pr = Mint + 4, po = 16 * DVT + 4;
+  float* red_o = red_r + 16 * pr;
+  constexpr int kPitchG = Mint + 32;
+  float* gs_s = reinterpret_cast<float*>(smem + p.lds_tab);
+  T* qk_s = reinterpret_cast<T*>(gs_s + G * kPitchG);
+
+  // this wave's kept operands of the step at `base`: the four row blocks and the two token
+  // blocks of tile `wave`.  Rows are clamped into the slab (rows past the chunk are masked at the
+  // softmax); K columns past the row pitch re-read the row's last 8 columns, where q is zero.
+  const int urow_lane = 8 * (r16 >> 2) + (r16 & 3);
+  const uint32_t kcol = static_cast<uint32_t>(min(8 * q4, kpitch - 8));
+  auto load_step = [&](Frag<T> (&kf)[4], Frag<T> (&vf)[2][DVT], int base) {
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+      const int u = 32 * (rb >> 1) + 4 * (rb & 1) + urow_lane;
+      const int j = min(base + wave * kTJ + u, Nm1);
+      kf[rb].load(kk + (static_cast<uint32_t>(j) * static_cast<uint32_t>(kpitch) + kcol));
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int tok0 = base + wave * kTJ + 32 * i + 8 * q4;
+      const uint32_t g8 = static_cast<uint32_t>(min(tok0, Nm1)) >> 3;
+#pragma unroll
+      for (int dt = 0; dt < DVT; ++dt) {
+        const int dim = min(16 * dt + r16, Dvu - 1);
+        vf[i][dt].load(vk + (g8 * static_cast<uint32_t>(Dvu) + static_cast<uint32_t>(dim)) * 8u);
+      }
+    }
+  };
+
+  // ---- (0) everything that comes from global memory is requested first ------------
+  constexpr int kGLoads = (Mint + kBlock - 1) / kBlock;   // G <= 4 heads of Mint floats, as float4
+  const int ng4 = G * Mint / 4;
+  f32x4 gv[kGLoads];
+#pragma unroll
+  for (int i = 0; i < kGLoads; ++i)
+    gv[i] = *reinterpret_cast<const f32x4*>(p.gs + hq0 * Mint + 4 * min(tid + i * kBlock, ng4 - 1));
+  const int ocol = 4 * wave + (lane & 3), orb = lane >> 4, oq4 = (lane >> 2) & 3;
+  const int ocol_k = ocol / GP, ocol_h = ocol % GP;
+  const bool olive = ocol_k < KT && ocol_h < G;
+  const float g0 = p.g0[hq0 + min(ocol_h, G - 1)];
+  // packed query at the kept K dims: G rows of 32 elements = at most 16 vectors of 8
+  Frag<T> qv;
+  qv.load(static_cast<const T*>(p.qkeep) + hq0 * Dkq + 8 * min(tid, G * 4 - 1));
+  Frag<T> kfA[4], kfB[4];
+  Frag<T> vfA[2][DVT], vfB[2][DVT];
+  load_step(kfA, vfA, c0);
+  load_step(kfB, vfB, c0 + min(1, nsteps - 1) * step);
+
+  // ---- this wave's slices of the E table, evaluated in registers -----------------------------
+  Frag<ES> eA[CW][kRB], eB[CW][2][kXN];
+  float tc[CW], ts[CW];
+  {
+    const int n_max = p.M / 2;
+    const float invT = 1.0f / static_cast<float>(p.T);
+    // K side: row u(rb, r16), slots = (cos, sin) of the 4 consecutive orders n0 .. n0 + 3; the first
+    // order is evaluated, the others follow by the angle-addition step of the row
+    float cd[kRB], sd[kRB];
+    int urow[kRB];
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) {
+      urow[rb] = 32 * (rb >> 1) + 4 * (rb & 1) + urow_lane;
+      table_cs<T>(1, urow[rb], p.T, invT, &cd[rb], &sd[rb]);
+    }
+#pragma unroll
+    for (int i = 0; i < CW; ++i) {
+      const int n0 = 16 * (wave * CW + i) + 4 * q4 + 1;
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb) {
+        float vals[8];
+        table_cs<T>(n0, urow[rb], p.T, invT, &vals[0], &vals[1]);
+#pragma unroll
+        for (int hp = 1; hp < 4; ++hp) {
+          vals[2 * hp] = vals[2 * hp - 2] * cd[rb] - vals[2 * hp - 1] * sd[rb];
+          vals[2 * hp + 1] = vals[2 * hp - 1] * cd[rb] + vals[2 * hp - 2] * sd[rb];
+        }
+#pragma unroll
+        for (int hp = 0; hp < 4; ++hp)
+          if (n0 + hp > n_max) vals[2 * hp] = vals[2 * hp + 1] = 0.0f;
+        pack8(eA[i][rb], vals);
+      }
+    }
+    // V side: order n = 16 c + r16 + 1 at the 8 consecutive rows 32 x + 8 q4 + e: the first row is
+    // evaluated, the others follow by the angle-addition step of the order
+#pragma unroll
+    for (int i = 0; i < CW; ++i) {
+      const int n = 16 * (wave * CW + i) + r16 + 1;
+      float cn, sn;
+      table_cs<T>(n, 1, p.T, invT, &cn, &sn);
+#pragma unroll
+      for (int x = 0; x < kXN; ++x) {
+        float cs[8], ss[8];
+        table_cs<T>(n, 32 * x + 8 * q4, p.T, invT, &cs[0], &ss[0]);
+#pragma unroll
+        for (int e = 1; e < 8; ++e) {
+          cs[e] = cs[e - 1] * cn - ss[e - 1] * sn;
+          ss[e] = ss[e - 1] * cn + cs[e - 1] * sn;
+        }
+        if (n > n_max) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) cs[e] = ss[e] = 0.0f;
+        }
+        pack8(eB[i][0][x], cs);
+        pack8(eB[i][1][x], ss);
+      }
+    }
+    // the V-side accumulators live in a frame that moves with the steps
+    const uint32_t ph_step = phase_of(step, p.ph_scale);
+#pragma unroll
+    for (int i = 0; i < CW; ++i)
+      phase_cs<T>(static_cast<uint32_t>(16 * (wave * CW + i) + r16 + 1) * ph_step, &tc[i], &ts[i]);
+  }
+
+  // ---- series coefficients and packed query into LDS ---------------------------------------------
+#pragma unroll
+  for (int i = 0; i < kGLoads; ++i) {
+    const int v4 = tid + i * kBlock;
+    if (v4 < ng4) *reinterpret_cast<f32x4*>(gs_s + (4 * v4 / Mint) * kPitchG + (4 * v4) % Mint) = gv[i];
+  }
+  if (tid < G * 4) *reinterpret_cast<Frag<T>*>(qk_s + 8 * tid) = qv;
+  __syncthreads();
+  // this lane's B operand of the kept-K products: q of its column's head, only in the columns of tile `wave`
+  Frag<T> bq;
+  bq.load(qk_s + hsafe * Dkq + 8 * q4);
+  if (col_k != wave || !col_live) bq.zero();
+
+  f32x4 racc[2 * CW];
+  f32x4 oacc[DVT];
+#pragma unroll
+  for (int t = 0; t < 2 * CW; ++t) racc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int t = 0; t < DVT; ++t) oacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.0f;
+
+  auto do_step = [&](Frag<T> (&kf)[4], Frag<T> (&vf)[2][DVT], int base, auto tail_tag) {
+    constexpr bool kTail = decltype(tail_tag)::value;
+    f32x4 sacc[kRB];
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // -- (a) series on the K side, own orders: S += E g'(tile origin) -----------------
+    const uint32_t ph_k = phase_of(p.t0 + base + col_k * kTJ, p.ph_scale);
+#pragma unroll
+    for (int i = 0; i < CW; ++i) {
+      const uint32_t n0 = 16 * (wave * CW + i) + 4 * q4 + 1;
+      float csv[4], snv[4];
+      if constexpr (GP >= 4) {          // the 4 lanes of a quad share (tile, q4): one evaluation each
+        float cs, sn;
+        phase_cs<T>((n0 + (lane & 3)) * ph_k, &cs, &sn);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          csv[j] = quad_bcast(cs, j);
+          snv[j] = quad_bcast(sn, j);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) phase_cs<T>((n0 + j) * ph_k, &csv[j], &snv[j]);
+      }
+      const float* gl = gs_s + hsafe * kPitchG + 32 * (wave * CW + i) + 8 * q4;
+      const f32x4 ga = *reinterpret_cast<const f32x4*>(gl), gb = *reinterpret_cast<const f32x4*>(gl + 4);
+      float gp[8];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float gc = (j < 2) ? ga[2 * (j & 1)] : gb[2 * (j & 1)];
+        const float gsn = (j < 2) ? ga[2 * (j & 1) + 1] : gb[2 * (j & 1) + 1];
+        gp[2 * j] = gc * csv[j] + gsn * snv[j];
+        gp[2 * j + 1] = gsn * csv[j] - gc * snv[j];
+      }
+      Frag<ES> bg;
+      pack8(bg, gp);
+      if (!col_live) bg.zero();
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], eA[i][rb], bg);
+    }
+    // -- (b) kept K dims of tile `wave`: A = K^mu rows, B = q masked to the tile's columns --
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], kf[rb], bq);
+
+    // -- (c) the partial scores of the four waves meet; this wave sums its four columns --------
+    {
+      f32x4* xw = xs + (wave * kRB) * 64 + lane;
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb) xw[rb * 64] = sacc[rb];
+    }
+    __syncthreads();
+    f32x4 sv;
+    {
+      const f32x4* xr = xs + orb * 64 + oq4 * 16 + ocol;
+      sv = ((xr[0 * kRB * 64] + xr[1 * kRB * 64]) + xr[2 * kRB * 64]) + xr[3 * kRB * 64];
+    }
+    // -- (d) online softmax of the own columns: lane holds rows u = 32x + 8 oq4 + 4y + v (orb = 2x + y)
+    float pv[4];
+    float m_tile = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      float sc = (sv[v] + g0) * p.scale;
+      if constexpr (kTail) {
+        const int u = 32 * (orb >> 1) + 8 * oq4 + 4 * (orb & 1) + v;
+        if (base + ocol_k * kTJ + u >= c1) sc = -INFINITY;
+      }
+      if (!olive) sc = -INFINITY;
+      pv[v] = sc;
+      m_tile = fmaxf(m_tile, sc);
+    }
+    m_tile = row_stride_max(m_tile, 4);                      // the 16 lanes of a column are 4 apart
+    m_tile = cross_row_max(m_tile);
+    const float m_new = fmaxf(m_run, m_tile);
+    const float m_ref = (m_new == -INFINITY) ? 0.0f : m_new;
+    const float alpha = __expf(m_run - m_ref);   // m_run = -inf -> 0
+    float l_add = 0.0f;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      pv[v] = __expf(pv[v] - m_ref);
+      l_add += pv[v];
+    }
+    l_run = l_run * alpha + l_add;
+    m_run = m_new;
+    {
+      const int slot = (((orb >> 1) * 16 + ocol) * 4 + oq4) * 8 + 4 * (orb & 1);
+      u32x2d w;
+      w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[0], pv[1]}, f16x2));
+      w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[2], pv[3]}, f16x2));
+      *reinterpret_cast<u32x2d*>(reinterpret_cast<uint16_t*>(pse) + slot) = w;
+      w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[0], pv[1]}, bf16x2));
+      w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[2], pv[3]}, bf16x2));
+      *reinterpret_cast<u32x2d*>(reinterpret_cast<uint16_t*>(pte) + slot) = w;
+      float lo[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        lo[v] = pv[v] - __builtin_bit_cast(float, ((w[v >> 1] >> (16 * (v & 1))) & 0xffffu) << 16);
+      w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo[0], lo[1]}, bf16x2));
+      w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo[2], lo[3]}, bf16x2));
+      *reinterpret_cast<u32x2d*>(reinterpret_cast<uint16_t*>(ptl) + slot) = w;
+      if (lane < 4) alpha_s[ocol] = alpha;
+    }
+    __syncthreads();
+    // -- (e) bring the accumulators into this step's frame (the first step scales zeros by zero) --
+    {
+      const f32x4 al = *reinterpret_cast<const f32x4*>(alpha_s + 4 * q4);
+#pragma unroll
+      for (int t = 0; t < DVT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) oacc[t][v] *= al[v];
+#pragma unroll
+      for (int i = 0; i < CW; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float rc = racc[2 * i][v], rs = racc[2 * i + 1][v];
+          racc[2 * i][v] = al[v] * (tc[i] * rc + ts[i] * rs);
+          racc[2 * i + 1][v] = al[v] * (tc[i] * rs - ts[i] * rc);
+        }
+    }
+    // -- (f) V side, own orders: r' += P^T E;  (g) kept V dims of tile `wave`: O += P^T V^mu -------
+#pragma unroll
+    for (int x = 0; x < kXN; ++x) {
+      Frag<ES> ps;
+      Frag<T> pt, pl;
+      ps.load(pse + ((x * 16 + r16) * 4 + q4) * 8);
+      pt.load(pte + ((x * 16 + r16) * 4 + q4) * 8);
+      pl.load(ptl + ((x * 16 + r16) * 4 + q4) * 8);
+#pragma unroll
+      for (int i = 0; i < CW; ++i) {
+        mma_k32(racc[2 * i], ps, eB[i][0][x]);
+        mma_k32(racc[2 * i + 1], ps, eB[i][1][x]);
+      }
+      if (col_k != wave) {   // this wave's token blocks belong to tile `wave`: other columns contribute nothing
+        pt.zero();
+        pl.zero();
+      }
+#pragma unroll
+      for (int dt = 0; dt < DVT; ++dt) {
+        Frag<T> bv = vf[x][dt];
+        if (16 * dt + r16 >= Dvu) bv.zero();
+        if constexpr (kTail) {
+          const int tok0 = base + wave * kTJ + 32 * x + 8 * q4;
+          if (tok0 + 8 > c1) mask_tail(bv, c1 - tok0);
+        }
+        mma_k32(oacc[dt], pt, bv);
+        mma_k32(oacc[dt], pl, bv);
+      }
+    }
+  };
+
+  // two steps per trip: the operands of a step are requested two steps ahead, clamped into the chunk
+  const int last_base = c0 + (nsteps - 1) * step;
+  {
+    int s = 0;
+    for (; s + 2 < nsteps; s += 2) {
+      const int base = c0 + s * step;
+      do_step(kfA, vfA, base, std::false_type{});
+      load_step(kfA, vfA, min(base + 2 * step, last_base));
+      do_step(kfB, vfB, base + step, std::false_type{});
+      load_step(kfB, vfB, min(base + 3 * step, last_base));
+    }
+    const int base = c0 + s * step;
+    if (nsteps - s == 2) {
+      do_step(kfA, vfA, base, std::false_type{});
+      do_step(kfB, vfB, base + step, std::true_type{});
+    } else {
+      do_step(kfA, vfA, base, std::true_type{});
+    }
+  }
+
+  // ---- merge the tiles of a head --------------------------------------------------------------
+  l_run = row_stride_sum(l_run, 4);
+  l_run = cross_row_sum(l_run);
+  if (lane < 4) {
+    st_m[ocol] = m_run;
+    st_l[ocol] = l_run;
+  }
+  __syncthreads();
+  const float mc = col_live ? st_m[r16] : -INFINITY;
+  const float lcol = st_l[r16];
+  const float mstar = row_stride_max(mc, GP);   // the columns of one head are GP lanes apart
+  const float fc = (mc != -INFINITY) ? __expf(mc - mstar) : 0.0f;
+  const float lstar = row_stride_sum(col_live ? lcol * fc : 0.0f, GP);
+  __syncthreads();   // every wave is done with the exchange regions: they are reused below
+
+  {
+    float f[4];
+    uint32_t phr[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int row = 4 * q4 + v;
+      f[v] = __shfl(fc, row, kWave);
+      phr[v] = phase_of(p.t0 + last_base + (row / GP) * kTJ, p.ph_scale);
+    }
+#pragma unroll
+    for (int i = 0; i < CW; ++i) {
+      const int c = wave * CW + i;
+      const uint32_t n = 16 * c + r16 + 1;
+      float cs[4], sn[4];
+      phase_cs<T>(n * phr[0], &cs[0], &sn[0]);
+      if constexpr (GP >= 4) {   // rows 4*q4 .. 4*q4+3 belong to one tile
+#pragma unroll
+        for (int v = 1; v < 4; ++v) {
+          cs[v] = cs[0];
+          sn[v] = sn[0];
+        }
+      } else {
+#pragma unroll
+        for (int v = 1; v < 4; ++v) phase_cs<T>(n * phr[v], &cs[v], &sn[v]);
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const float rc = racc[2 * i][v], rs = racc[2 * i + 1][v];
+        float* dst = red_r + (4 * q4 + v) * pr + 32 * c + r16;
+        dst[0] = f[v] * (cs[v] * rc - sn[v] * rs);
+        dst[16] = f[v] * (sn[v] * rc + cs[v] * rs);
+      }
+    }
+    float* ro = red_o + wave * 16 * po;
+#pragma unroll
+    for (int dt = 0; dt < DVT; ++dt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) ro[(4 * q4 + v) * po + 16 * dt + r16] = f[v] * oacc[dt][v];
+  }
+  __syncthreads();
+
+  // record of head h: [max, sum, -, -, acc over the kept dims (16 DVT), r (Mint, V-side order)]
+  const size_t rec_h = static_cast<size_t>(p.Sm) * p.recm;
+  float* rec0 = p.part_m + (hq0 * p.Sm + sm_idx) * p.recm;
+  if (wave == 0 && lane < G) {
+    rec0[lane * rec_h + 0] = mstar;
+    rec0[lane * rec_h + 1] = lstar;
+  }
+  constexpr int no4 = 4 * DVT, nr4 = Mint / 4, per = no4 + nr4;
+  for (int it = tid; it < G * per; it += kBlock) {
+    const int h = it / per, x4 = it - h * per;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (x4 < no4) {
+      // kept dims of tile k were accumulated by wave k alone
+#pragma unroll
+      for (int k = 0; k < KT; ++k) v += *reinterpret_cast<const f32x4*>(red_o + ((k * 16 + k * GP + h) * po + 4 * x4));
+    } else {
+      const int y = x4 - no4;
+#pragma unroll
+      for (int k = 0; k < KT; ++k) v += *reinterpret_cast<const f32x4*>(red_r + ((k * GP + h) * pr + 4 * y));
+    }
+    *reinterpret_cast<f32x4*>(rec0 + h * rec_h + 4 + 4 * x4) = v;
+  }
+}
+
+template <int CW, int DVT, int GP>
+__global__ __launch_bounds__(kBlock, CW <= 2 ? 2 : 1) void decode_partial_fast(DecodeParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  if (static_cast<int>(blockIdx.x) < p.Sm) partial_middle_fast<CW, DVT, GP>(p, smem);
+  else partial_full_rows<bf16_t>(p, smem);
+}
+
 template <typename T, int CW, int DVTM, bool KC1>
 __global__ __launch_bounds__(kBlock, (CW <= 2 && sizeof(T) == 2) ? 2 : 1) void decode_partial(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -1562,6 +2017,45 @@ static int launch_partial(const DecodeParams& p, unsigned lds, hipStream_t st, K
   return FA_OK;
 }
 
+template <typename T>
+static int launch_finish(const DecodeParams& p, hipStream_t st, KernelTimers* tm, hipError_t prior) {
+  if (static_cast<long>(p.B) * p.Hq >= 256) {
+    FA_LAUNCH_TIMED(tm, 2, (decode_finish<T, 64>), dim3((p.D + 63) / 64, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
+  } else {
+    FA_LAUNCH_TIMED(tm, 2, (decode_finish<T, 32>), dim3((p.D + 31) / 32, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
+  }
+  // only this call's launches are reported: an error some earlier, unrelated HIP call of the
+  // application left behind is neither returned nor cleared
+  return (hipPeekAtLastError() == hipSuccess || prior != hipSuccess) ? FA_OK : FA_ERR_HIP;
+}
+
+template <int CW, int DVT, int GP>
+static int launch_partial_fast_one(const DecodeParams& p, unsigned lds, hipStream_t st, KernelTimers* tm) {
+  auto kern = decode_partial_fast<CW, DVT, GP>;
+  if (lds > 48u * 1024u &&
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          static_cast<int>(kMaxDynLds)) != hipSuccess)
+    return FA_ERR_HIP;
+  dim3 g2(p.Sw + p.Sm, p.B * p.Hkv);
+  FA_LAUNCH_TIMED(tm, 1, kern, g2, dim3(kBlock), lds, st, p);
+  return FA_OK;
+}
+
+static int launch_partial_fast(const DecodeParams& p, const DecodePlan& pl, hipStream_t st, KernelTimers* tm) {
+  const bool one_tile = p.Dvu <= 16, one_head = p.G == 1;
+#define FA_FAST(CW_)                                                                              \
+  return one_tile ? (one_head ? launch_partial_fast_one<CW_, 1, 1>(p, pl.lds_total, st, tm)        \
+                              : launch_partial_fast_one<CW_, 1, 4>(p, pl.lds_total, st, tm))       \
+                  : (one_head ? launch_partial_fast_one<CW_, 2, 1>(p, pl.lds_total, st, tm)        \
+                              : launch_partial_fast_one<CW_, 2, 4>(p, pl.lds_total, st, tm))
+  switch (pl.cw) {
+    case 1: FA_FAST(1);
+    case 2: FA_FAST(2);
+    default: FA_FAST(4);
+  }
+#undef FA_FAST
+}
+
 // tm (optional): per-kernel event pairs, for fa_decode_timed
 template <typename T>
 static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_t st, KernelTimers* tm) {
@@ -1577,6 +2071,14 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
     }
   }
   int rc;
+  if constexpr (sizeof(T) == 2) {
+    // the specialised kernel: groups of at most four query heads, 1 .. 32 kept dims on both sides
+    if (p.Sm > 0 && p.G <= 4 && p.Dku > 0 && p.Dku <= 32 && p.Dvu > 0 && p.Dvu <= 32) {
+      rc = launch_partial_fast(p, pl, st, tm);
+      if (rc != FA_OK) return rc;
+      return launch_finish<T>(p, st, tm, prior);
+    }
+  }
   const bool narrow = p.Dvu <= 32;   // kept V dims fit two MFMA column tiles
   const bool kc1 = p.Dku <= 32;      // kept K dims fit one MFMA step
 #define FA_LAUNCH_PARTIAL(CW_)                                                                      \
@@ -1596,14 +2098,7 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
   }
 #undef FA_LAUNCH_PARTIAL
   if (rc != FA_OK) return rc;
-  if (static_cast<long>(p.B) * p.Hq >= 256) {
-    FA_LAUNCH_TIMED(tm, 2, (decode_finish<T, 64>), dim3((p.D + 63) / 64, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
-  } else {
-    FA_LAUNCH_TIMED(tm, 2, (decode_finish<T, 32>), dim3((p.D + 31) / 32, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
-  }
-  // only this call's launches are reported: an error some earlier, unrelated HIP call of the
-  // application left behind is neither returned nor cleared
-  return (hipPeekAtLastError() == hipSuccess || prior != hipSuccess) ? FA_OK : FA_ERR_HIP;
+  return launch_finish<T>(p, st, tm, prior);
 }
 
 }  // namespace fa
