@@ -367,6 +367,93 @@ __global__ __launch_bounds__(kBlock) void decode_prepare(DecodeParams p) {
 }
 
 // ---------------------------------------------------------------------------
+// 1b. g = diag(w) C_k q_c for compressed counts that are a multiple of 4: the streaming form
+// ---------------------------------------------------------------------------
+// TPR threads share a row of C_k and read it as interleaved 128-bit vectors, all requested
+// before anything else happens (rows are independent of the mask); the group's queries at the
+// compressed dims go through LDS once, each thread forms its share of the G dot products from
+// registers, and the TPR shares meet by lane rotation.  256 / TPR rows per workgroup: 64 when
+// the (sequence, head) pairs alone fill the chip, 16 when there are few of them.
+template <typename T, int TPR>
+__global__ __launch_bounds__(kBlock) void decode_prepare2(DecodeParams p) {
+  constexpr int kRows = kBlock / TPR;
+  constexpr int kV4 = (FA_MAX_HEAD_DIM / 4 + TPR - 1) / TPR;
+  __shared__ __attribute__((aligned(16))) float qc[kMaxG * FA_MAX_HEAD_DIM];   // [G][Dkc] query at the compressed dims
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int Dkc = p.Dkc, D = p.D, G = p.G;
+  const int row = tid / TPR, seg = tid % TPR;
+  const int m = blockIdx.x * kRows + row;            // basis function of this thread's row (0 .. Mint)
+  const int c4n = Dkc / 4;
+
+  // C_k row, the mask row and q of the group: all requested up front, clamped, never predicated
+  const float* ck = p.ck + static_cast<size_t>(bh) * p.M * Dkc + static_cast<size_t>(min(m, p.M - 1)) * Dkc;
+  f32x4 cv4[kV4];
+#pragma unroll
+  for (int i = 0; i < kV4; ++i)
+    if (i * TPR < c4n) cv4[i] = *reinterpret_cast<const f32x4*>(ck + 4 * min(seg + i * TPR, c4n - 1));
+  uint64_t kbal[4];
+  mask_ballots(p.kmask + static_cast<size_t>(bh) * D, D, lane, kbal);
+  const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
+  const T* q = static_cast<const T*>(p.q) + hq0 * D;
+  constexpr int kQElems = kMaxG * FA_MAX_HEAD_DIM / kBlock;
+  const int nqe = G * D;
+  T qe[kQElems];
+#pragma unroll
+  for (int i = 0; i < kQElems; ++i)
+    if (i * kBlock < nqe) qe[i] = q[min(tid + i * kBlock, nqe - 1)];
+
+  // q splits into its compressed dims (fp32, for the products below) and its kept dims (packed and
+  // zero padded for the K^mu products of decode_partial; written by the first workgroup of the row)
+  const int kpitch = (p.Dku + 7) & ~7;
+  const int Dkq = (kpitch + 31) / 32 * 32;
+  T* qkeep = static_cast<T*>(p.qkeep) + hq0 * Dkq;
+#pragma unroll
+  for (int i = 0; i < kQElems; ++i) {
+    const int it = tid + i * kBlock;
+    if (it < nqe) {
+      const int h = it / D, d = it % D;
+      const int r = dim_rank(kbal, d);
+      if (r < 0) qc[h * Dkc + (-r - 1)] = to_f32(qe[i]);
+      else if (blockIdx.x == 0) qkeep[h * Dkq + r] = qe[i];
+    }
+  }
+  if (blockIdx.x == 0) {
+    const int npad = Dkq - p.Dku;
+    for (int it = tid; it < G * npad; it += kBlock) qkeep[(it / npad) * Dkq + p.Dku + it % npad] = T{};
+  }
+  __syncthreads();
+
+  const float w = (m < p.M) ? basis_weight((m + 1) / 2, p.T) : 0.0f;
+  for (int h = 0; h < G; ++h) {
+    const float* qh = qc + h * Dkc;
+    float acc = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kV4; ++i) {
+      if (i * TPR < c4n) {
+        const int c4 = seg + i * TPR;
+        const f32x4 qv = *reinterpret_cast<const f32x4*>(qh + 4 * min(c4, c4n - 1));
+        const float d4 = (cv4[i][0] * qv[0] + cv4[i][1] * qv[1]) + (cv4[i][2] * qv[2] + cv4[i][3] * qv[3]);
+        acc += (c4 < c4n) ? d4 : 0.0f;
+      }
+    }
+    if constexpr (TPR == 16) {
+      acc = row_stride_sum(acc, 1);
+    } else {
+      static_assert(TPR == 4, "threads per row");
+      acc += __shfl_xor(acc, 1, kWave);
+      acc += __shfl_xor(acc, 2, kWave);
+    }
+    if (seg == 0 && m <= p.Mint) {
+      const float g = acc * w;
+      if (m == 0) p.g0[hq0 + h] = g;
+      else p.gs[(hq0 + h) * p.Mint + (m - 1)] = g;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // 2a. full-width sink/window rows: plain single-query attention partial
 // ---------------------------------------------------------------------------
 // A workgroup takes 256 rows, 64 per wave.  A wave multiplies its rows with q on the matrix
@@ -1902,6 +1989,263 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
 }
 
 // ---------------------------------------------------------------------------
+// 3b. merge partials, apply diag(w) C_v, normalise: the pipelined form
+// ---------------------------------------------------------------------------
+// Same arithmetic as decode_finish, organised so that a workgroup's large reads depend on
+// nothing but the kernel arguments: a query head is shared by NS workgroups that divide the
+// output dims by RANK (compressed dims cb0 .. cb0 + cbw - 1 and kept dims kb0 .. kb0 + kbw - 1 in
+// mask order) instead of by position, so the band of C_v columns and the kept-dim columns of the
+// records are known before the mask row arrives; only the few full-row records are read after
+// it.  Every load is issued in batches of independent requests (no load waits for another one's
+// data), and the workgroups of one KV head are numbered so that they run on one XCD and share
+// its L2 (workgroup ids go round the eight XCDs).  Needs Dvc to be a multiple of 4.
+constexpr int kFin2Batch = 4;    // independent requests per batch: narrow columns (kept dims, full-row records)
+// kFin2Wide: independent 128-bit requests per batch of the series sums and of the C_v band: 16 when a
+// launch has few workgroups (long record lists, registers to spare), 8 with four workgroups per unit
+template <int kFin2Wide>
+__global__ __launch_bounds__(kFinBlock, kFin2Wide == 16 ? 2 : 4) void decode_finish2(DecodeParams p, int NS) {
+  constexpr int kNW = kFinBlock / 64;
+  constexpr int kSP = kMaxPartials / kFinBlock;
+  __shared__ float es[kMaxPartials];
+  __shared__ f32x4 red4[kFinBlock];                 // series sums per record group, then C_v partial sums per row group
+  __shared__ float redk[2 * kFinBlock];             // kept-dim and full-row partial sums per record group
+  __shared__ float rr[FA_MAX_DECODE_STATES + 4];
+  __shared__ int dim_of[FA_MAX_HEAD_DIM];           // output dim of each rank of this slice
+  __shared__ float wmax[kNW], wsum[kNW], wsum_m[kNW];
+
+  // workgroup -> (KV head, query head of the group, slice): the G * NS workgroups of a KV head share an XCD
+  const int per_kv = p.G * NS;
+  const int L = blockIdx.x, xcd = L & 7, slot = L >> 3;
+  const int bh = (slot / per_kv) * 8 + xcd;
+  if (bh >= p.B * p.Hkv) return;
+  const int within = slot % per_kv, g = within / NS, sl = within % NS;
+  const int b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int hq = b * p.Hq + hkv * p.G + g;
+
+  const int D = p.D, M = p.M, Sm = p.Sm, Sw = p.Sw, S = Sm + Sw, Dvc = p.Dvc, Dvu = p.Dvu, Mint = p.Mint;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int Dva = 16 * ((Dvu + 15) / 16);
+  const int recm = p.recm, recw = p.recw;
+  const float* pm = p.part_m + static_cast<size_t>(hq) * Sm * recm;
+  const float* pw = p.part_w + static_cast<size_t>(hq) * Sw * recw;
+  const bool do_cv = Sm > 0 && Dvc > 0;
+  // this slice's ranks
+  const int cbw = (((Dvc + NS - 1) / NS) + 3) & ~3, cb0 = sl * cbw, cbn = max(0, min(cbw, Dvc - cb0));
+  const int kbw = (Dvu + NS - 1) / NS, kb0 = sl * kbw, kbn = max(0, min(kbw, Dvu - kb0));
+
+  // ---- loads that depend on nothing ------------------------------------------------------------
+  uint8_t vmb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) vmb[i] = p.vmask[static_cast<size_t>(bh) * D + min(lane + 64 * i, D - 1)];
+  float ms[kSP], ls[kSP];
+#pragma unroll
+  for (int i = 0; i < kSP; ++i) {
+    if (i * kFinBlock < S) {
+      const int s = min(tid + i * kFinBlock, S - 1);
+      const float* r = (s < Sm) ? pm + static_cast<size_t>(s) * recm : pw + static_cast<size_t>(s - Sm) * recw;
+      ms[i] = r[0];
+      ls[i] = r[1];
+    }
+  }
+  // first batch of the series sums: thread (4 slots c4r, record group gr)
+  const int cr4 = Mint / 4, ngr = max(kFinBlock / cr4, 1);
+  const int c4r = tid % cr4, gr = tid / cr4;
+  const bool r_on = do_cv && tid < cr4 * ngr;
+  const float* pr = pm + 4 + Dva + 4 * c4r;
+  f32x4 rv[kFin2Wide];
+  if (do_cv) {
+#pragma unroll
+    for (int u = 0; u < kFin2Wide; ++u)
+      if (u * ngr < Sm) rv[u] = *reinterpret_cast<const f32x4*>(pr + static_cast<size_t>(min(gr + u * ngr, Sm - 1)) * recm);
+  }
+  // first batch of the C_v band: thread (column quad cqv, row group rgv)
+  const int nq = max(cbn / 4, 1), ngrp = kFinBlock / nq;
+  const int cqv = tid % nq, rgv = tid / nq;
+  const bool cv_on = do_cv && cbn > 0 && tid < nq * ngrp;
+  const float* cvb = p.cv + static_cast<size_t>(bh) * M * Dvc + cb0 + 4 * cqv;
+  f32x4 cv4[kFin2Wide];
+  if (do_cv && cbn > 0) {
+#pragma unroll
+    for (int u = 0; u < kFin2Wide; ++u)
+      if (u * ngrp < M) cv4[u] = *reinterpret_cast<const f32x4*>(cvb + static_cast<size_t>(min(rgv + u * ngrp, M - 1)) * Dvc);
+  }
+  // kept-dim accumulators of the middle records: thread (kept rank kc, record group kg)
+  const int kcn = max(kbn, 1), nkg = kFinBlock / kcn;
+  const int kc = tid % kcn, kg = tid / kcn;
+  const bool k_on = Sm > 0 && kbn > 0 && tid < kcn * nkg;
+  const float* pk = pm + 4 + kb0 + kc;
+  float kv[kFin2Batch];
+  if (Sm > 0 && kbn > 0) {
+#pragma unroll
+    for (int u = 0; u < kFin2Batch; ++u)
+      if (u * nkg < Sm) kv[u] = pk[static_cast<size_t>(min(kg + u * nkg, Sm - 1)) * recm];
+  }
+
+  // ---- which dims this slice writes (needs the mask row) ---------------------------------------
+  uint64_t vbal[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) vbal[i] = __ballot(vmb[i] != 0 && lane + 64 * i < D);
+  if (tid < D) {
+    const int rk = dim_rank(vbal, tid);
+    if (rk < 0) {
+      const int c = -rk - 1 - cb0;
+      if (c >= 0 && c < cbn) dim_of[c] = tid;
+    } else {
+      const int k = rk - kb0;
+      if (k >= 0 && k < kbn) dim_of[cbw + k] = tid;
+    }
+  }
+
+  // ---- global max, per-record factors, normaliser ---------------------------------------------
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < kSP; ++i)
+    if (tid + i * kFinBlock < S) m = fmaxf(m, ms[i]);
+  m = wave_max_fast(m);
+  if (lane == 0) wmax[wave] = m;
+  __syncthreads();   // also publishes dim_of
+  m = wmax[0];
+#pragma unroll
+  for (int w = 1; w < kNW; ++w) m = fmaxf(m, wmax[w]);
+  float l = 0.0f, lm = 0.0f;
+#pragma unroll
+  for (int i = 0; i < kSP; ++i) {
+    const int s = tid + i * kFinBlock;
+    if (s < S) {
+      const float e = (ms[i] == -INFINITY) ? 0.0f : __expf(ms[i] - m);
+      es[s] = e;
+      l += e * ls[i];
+      if (s < Sm) lm += e * ls[i];
+    }
+  }
+  // the full-row records at this slice's dims: thread (rank j of the slice, record group)
+  const int nj = cbw + kbw, njn = max(nj, 1), nwg = kFinBlock / njn;
+  const int wj = tid % njn, wg = tid / njn;
+  const bool wj_live = (wj < cbn) || (wj >= cbw && wj < cbw + kbn);
+  const bool w_on = Sw > 0 && nj > 0 && tid < njn * nwg && wj_live;
+  const int wdim = wj_live && nj > 0 ? dim_of[wj] : 0;
+  float wv[kFin2Batch];
+  if (Sw > 0) {
+#pragma unroll
+    for (int u = 0; u < kFin2Batch; ++u)
+      if (u * nwg < Sw) wv[u] = pw[static_cast<size_t>(min(wg + u * nwg, Sw - 1)) * recw + 4 + wdim];
+  }
+  l = wave_sum_fast(l);
+  lm = wave_sum_fast(lm);
+  if (lane == 0) {
+    wsum[wave] = l;
+    wsum_m[wave] = lm;
+  }
+  __syncthreads();
+  float Lsum = 0.0f, Lm = 0.0f;
+#pragma unroll
+  for (int w = 0; w < kNW; ++w) {
+    Lsum += wsum[w];
+    Lm += wsum_m[w];
+  }
+
+  // ---- kept dims of the slice and the full-row records: per-thread partial sums ------------------
+  {
+    float o = 0.0f;
+    if (k_on) {
+#pragma unroll
+      for (int u = 0; u < kFin2Batch; ++u) {
+        const int s = kg + u * nkg;
+        if (s < Sm) o += es[s] * kv[u];
+      }
+      for (int s = kg + kFin2Batch * nkg; s < Sm; s += nkg) o += es[s] * pk[static_cast<size_t>(s) * recm];
+    }
+    redk[tid] = o;
+    float ow = 0.0f;
+    if (w_on) {
+#pragma unroll
+      for (int u = 0; u < kFin2Batch; ++u) {
+        const int s = wg + u * nwg;
+        if (s < Sw) ow += es[Sm + s] * wv[u];
+      }
+      for (int s = wg + kFin2Batch * nwg; s < Sw; s += nwg) ow += es[Sm + s] * pw[static_cast<size_t>(s) * recw + 4 + wdim];
+    }
+    redk[kFinBlock + tid] = ow;
+  }
+  // ---- r in basis order, weighted by the inverse squared norms ---------------------------------
+  if (do_cv) {
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    if (r_on) {
+#pragma unroll
+      for (int u = 0; u < kFin2Wide; ++u) {
+        const int s = gr + u * ngr;
+        if (s < Sm) a += es[s] * rv[u];
+      }
+      for (int s0 = kFin2Wide * ngr; s0 < Sm; s0 += kFin2Wide * ngr) {   // further batches: requests first, sums after
+        f32x4 t[kFin2Wide];
+#pragma unroll
+        for (int u = 0; u < kFin2Wide; ++u)
+          t[u] = *reinterpret_cast<const f32x4*>(pr + static_cast<size_t>(min(s0 + gr + u * ngr, Sm - 1)) * recm);
+#pragma unroll
+        for (int u = 0; u < kFin2Wide; ++u) {
+          const int s = s0 + gr + u * ngr;
+          if (s < Sm) a += es[s] * t[u];
+        }
+      }
+    }
+    red4[tid] = a;
+  }
+  __syncthreads();
+  if (do_cv) {
+    for (int ig = tid; ig < Mint; ig += kFinBlock) {   // record order: 32 * chunk + 16 * (cos | sin) + order
+      const float* src = reinterpret_cast<const float*>(red4) + ig;
+      float v = 0.0f;
+      for (int gi = 0; gi < ngr; ++gi) v += src[gi * Mint];
+      const int n = 16 * (ig >> 5) + (ig & 15) + 1, cs = (ig >> 4) & 1;
+      const int mm = 2 * n - 1 + cs;
+      if (mm < M) rr[mm] = v * basis_weight(n, p.T);
+    }
+    if (tid == kFinBlock - 1) rr[0] = Lm * basis_weight(0, p.T);
+  }
+  __syncthreads();
+
+  // ---- compressed dims of the slice: sum_m rr[m] C_v[m, rank] -----------------------------------
+  {
+    f32x4 o4 = {0.f, 0.f, 0.f, 0.f};
+    if (cv_on) {
+#pragma unroll
+      for (int u = 0; u < kFin2Wide; ++u) {
+        const int mm = rgv + u * ngrp;
+        if (mm < M) o4 += rr[mm] * cv4[u];
+      }
+      for (int m0 = kFin2Wide * ngrp; m0 < M; m0 += kFin2Wide * ngrp) {
+        f32x4 t[kFin2Wide];
+#pragma unroll
+        for (int u = 0; u < kFin2Wide; ++u)
+          t[u] = *reinterpret_cast<const f32x4*>(cvb + static_cast<size_t>(min(m0 + rgv + u * ngrp, M - 1)) * Dvc);
+#pragma unroll
+        for (int u = 0; u < kFin2Wide; ++u) {
+          const int mm = m0 + rgv + u * ngrp;
+          if (mm < M) o4 += rr[mm] * t[u];
+        }
+      }
+    }
+    red4[tid] = o4;   // [row group][column quad]
+  }
+  __syncthreads();
+  if (tid < nj) {
+    const bool live = (tid < cbn) || (tid >= cbw && tid < cbw + kbn);
+    if (live) {
+      float v = 0.0f;
+      if (do_cv && tid < cbn) {
+        const float* src = reinterpret_cast<const float*>(red4) + tid;   // band column tid = quad tid / 4, element tid % 4
+        for (int gi = 0; gi < ngrp; ++gi) v += src[4 * gi * nq];
+      }
+      if (tid >= cbw && Sm > 0)
+        for (int gi = 0; gi < nkg; ++gi) v += redk[gi * kcn + (tid - cbw)];
+      if (Sw > 0)
+        for (int gi = 0; gi < nwg; ++gi) v += redk[kFinBlock + gi * njn + tid];
+      p.out[static_cast<size_t>(hq) * D + dim_of[tid]] = v / Lsum;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 struct DecodePlan {
@@ -2019,7 +2363,16 @@ static int launch_partial(const DecodeParams& p, unsigned lds, hipStream_t st, K
 
 template <typename T>
 static int launch_finish(const DecodeParams& p, hipStream_t st, KernelTimers* tm, hipError_t prior) {
-  if (static_cast<long>(p.B) * p.Hq >= 256) {
+  if ((p.Dvc & 3) == 0) {
+    // slices per query head: as many as keep the launch within one round of resident workgroups
+    const int BH = p.B * p.Hkv;
+    const long heads = static_cast<long>(p.B) * p.Hq;
+    int NS = p.D <= 32 ? 1 : (p.D <= 64 ? 2 : (p.D <= 128 ? 4 : 8));
+    while (NS > 1 && heads * NS > 1024) NS /= 2;
+    const dim3 grid((BH + 7) / 8 * 8 * p.G * NS);
+    if (heads * NS <= 512) FA_LAUNCH_TIMED(tm, 2, decode_finish2<16>, grid, dim3(kFinBlock), 0, st, p, NS);
+    else FA_LAUNCH_TIMED(tm, 2, decode_finish2<8>, grid, dim3(kFinBlock), 0, st, p, NS);
+  } else if (static_cast<long>(p.B) * p.Hq >= 256) {
     FA_LAUNCH_TIMED(tm, 2, (decode_finish<T, 64>), dim3((p.D + 63) / 64, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
   } else {
     FA_LAUNCH_TIMED(tm, 2, (decode_finish<T, 32>), dim3((p.D + 31) / 32, p.B * p.Hq), dim3(kFinBlock), 0, st, p);
@@ -2061,7 +2414,13 @@ template <typename T>
 static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_t st, KernelTimers* tm) {
   const int BH = p.B * p.Hkv;
   const hipError_t prior = hipPeekAtLastError();
-  if (p.Sm > 0) {
+  if (p.Sm > 0 && p.Dkc > 0 && (p.Dkc & 3) == 0) {
+    if (static_cast<long>(BH) * (p.Mint / 64 + 1) >= 256) {
+      FA_LAUNCH_TIMED(tm, 0, (decode_prepare2<T, 4>), dim3(p.Mint / 64 + 1, BH), dim3(kBlock), 0, st, p);
+    } else {
+      FA_LAUNCH_TIMED(tm, 0, (decode_prepare2<T, 16>), dim3(p.Mint / 16 + 1, BH), dim3(kBlock), 0, st, p);
+    }
+  } else if (p.Sm > 0) {
     if (static_cast<long>(BH) * ((p.Mint + 32) / 32) >= 512) {
       dim3 g1((p.Mint + 32) / 32, BH);
       FA_LAUNCH_TIMED(tm, 0, (decode_prepare<T, 32>), g1, dim3(kBlock), prep_lds_bytes(32, p.G, p.Dkc), st, p);
