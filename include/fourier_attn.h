@@ -76,7 +76,7 @@ enum { FA_KEEP_ROWS = 0, FA_KEEP_TOK8 = 1 };
 #define FA_MAX_HEAD_DIM 256   /* D, must be a multiple of 8                     */
 #define FA_MAX_GROUP 16       /* query heads per KV head                         */
 #define FA_MAX_STATES 1024    /* M accepted by fa_compress                        */
-#define FA_MAX_DECODE_STATES 512 /* M accepted by fa_decode for FA_BF16              */
+#define FA_MAX_DECODE_STATES 1024 /* M accepted by fa_decode for FA_BF16 (the paper's 2k = 1024) */
 #define FA_MAX_DECODE_STATES_F32 256 /* M accepted by fa_decode for FA_F32           */
 #define FA_MAX_KEPT_V_DIMS 128 /* D - Dvc accepted by fa_decode                     */
 #define FA_MAX_SPLITS 256     /* token-axis chunks of fa_decode                  */
@@ -99,9 +99,9 @@ enum { FA_KEEP_ROWS = 0, FA_KEEP_TOK8 = 1 };
  *               x_keep + (b*H+h)*keep_stride_bh elements and token j of x is
  *               stored at token index keep_offset + j of that slab.  May be
  *               NULL (nothing is written).  keep_stride_bh = 0 means dense.
- *   workspace   at least fa_compress_workspace_bytes(...) bytes, 256-byte aligned
- *               (one figure that suffices for either element type; it holds the
- *               per-token-chunk partial sums, which fp32 inputs need more of).
+ *   workspace   at least fa_compress_workspace_bytes_for(dtype, ...) bytes, 256-byte
+ *               aligned (fa_compress_workspace_bytes(...) suffices for either
+ *               element type); it holds the per-token-chunk partial sums.
  *
  * N = 0 is legal (coeffs are zeroed unless accumulating).  Dc = 0 writes only
  * x_keep; Dc = D writes only coeffs.
@@ -116,6 +116,10 @@ int fa_compress(const void* x, int dtype,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 size_t fa_compress_workspace_bytes(int B, int H, int N, int D, int Dc, int M);
+/* The same for one element type: what a call with that `dtype` actually needs.  On long bf16
+ * segments this is several times smaller than the figure above (fp32 inputs use shorter token
+ * chunks, hence more partial sums); fa_compress accepts either. */
+size_t fa_compress_workspace_bytes_for(int dtype, int B, int H, int N, int D, int Dc, int M);
 
 /*
  * fa_decode -- Eq. 6 for one new query token per sequence.
@@ -221,10 +225,11 @@ int fa_append(const void* k_new, const void* v_new, int dtype,
  * projection kernel (bf16, D = 128, at most 32 kept dims each, keep_offset a
  * multiple of 8) the two projections run as ONE launch and the two chunk
  * reductions as one: two kernel launches per call instead of four.
- * workspace: >= fa_compress_kv_workspace_bytes(B, H, N, D, Dkc, Dvc, M), 256-byte
- * aligned.  Everything else (argument meaning, errors, asynchrony) as fa_compress.
+ * workspace: >= fa_compress_kv_workspace_bytes_for(dtype, B, H, N, D, Dkc, Dvc, M)
+ * (fa_compress_kv_workspace_bytes(...) covers either element type), 256-byte aligned.  Everything else (argument meaning, errors, asynchrony) as fa_compress.
  */
 size_t fa_compress_kv_workspace_bytes(int B, int H, int N, int D, int Dkc, int Dvc, int M);
+size_t fa_compress_kv_workspace_bytes_for(int dtype, int B, int H, int N, int D, int Dkc, int Dvc, int M);
 int fa_compress_kv(const void* k, const void* v, int dtype,
                    int64_t sx_b, int64_t sx_h, int64_t sx_n,
                    int B, int H, int N, int D,

@@ -19,7 +19,7 @@ FA_KEEP_ROWS, FA_KEEP_TOK8 = 0, 1
 FA_MAX_HEAD_DIM = 256
 FA_MAX_GROUP = 16
 FA_MAX_STATES = 1024
-FA_MAX_DECODE_STATES = 512
+FA_MAX_DECODE_STATES = 1024
 FA_MAX_DECODE_STATES_F32 = 256
 FA_MAX_KEPT_V_DIMS = 128
 
@@ -49,6 +49,10 @@ def _load(path: str = _LIB_PATH):
     lib.fa_compress_timed.argtypes = lib.fa_compress.argtypes + [c.POINTER(c.c_float)]
     lib.fa_compress_workspace_bytes.restype = sz
     lib.fa_compress_workspace_bytes.argtypes = [i32] * 6
+    lib.fa_compress_workspace_bytes_for.restype = sz
+    lib.fa_compress_workspace_bytes_for.argtypes = [i32] * 7
+    lib.fa_compress_kv_workspace_bytes_for.restype = sz
+    lib.fa_compress_kv_workspace_bytes_for.argtypes = [i32] * 8
     lib.fa_decode.restype = i32
     lib.fa_decode.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp, i32,
                               i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, i32, i64,
@@ -109,8 +113,13 @@ def _stream_ptr(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-def compress_workspace_bytes(B, H, N, D, Dc, M) -> int:
-    return int(lib.fa_compress_workspace_bytes(B, H, N, D, Dc, M))
+def compress_workspace_bytes(B, H, N, D, Dc, M, dtype=None) -> int:
+    """Workspace of fa_compress: for one element type (a torch dtype or FA_* code) when given, else
+    the figure that covers either."""
+    if dtype is None:
+        return int(lib.fa_compress_workspace_bytes(B, H, N, D, Dc, M))
+    code = dtype if isinstance(dtype, int) else (FA_F32 if dtype == torch.float32 else FA_BF16)
+    return int(lib.fa_compress_workspace_bytes_for(code, B, H, N, D, Dc, M))
 
 
 def decode_workspace_bytes(B, Hq, Hkv, D, Dkc, Dvc, M, N, W, num_splits=0) -> int:
@@ -161,7 +170,7 @@ def fa_compress(x, dim_mask, Dc, M, T, t0=0, accumulate=False, coeffs=None, x_ke
             x_keep = torch.empty((B, H, n_tok, keep_rows_pitch(Du)), dtype=x.dtype, device=dev)
         else:
             x_keep = torch.zeros((B, H, tok8_numel(n_tok, Du)), dtype=x.dtype, device=dev)
-    need = compress_workspace_bytes(B, H, N, D, Dc, M)
+    need = compress_workspace_bytes(B, H, N, D, Dc, M, x.dtype)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     args = (_ptr(x), _dtype_code(x), x.stride(0), x.stride(1), x.stride(2),
@@ -299,8 +308,11 @@ def fa_decode_mq(q, ck, kmask, cv, vmask, M, T, t0, N, k_keep, v_keep, k_full, v
     return out
 
 
-def compress_kv_workspace_bytes(B, H, N, D, Dkc, Dvc, M) -> int:
-    return int(lib.fa_compress_kv_workspace_bytes(B, H, N, D, Dkc, Dvc, M))
+def compress_kv_workspace_bytes(B, H, N, D, Dkc, Dvc, M, dtype=None) -> int:
+    if dtype is None:
+        return int(lib.fa_compress_kv_workspace_bytes(B, H, N, D, Dkc, Dvc, M))
+    code = dtype if isinstance(dtype, int) else (FA_F32 if dtype == torch.float32 else FA_BF16)
+    return int(lib.fa_compress_kv_workspace_bytes_for(code, B, H, N, D, Dkc, Dvc, M))
 
 
 def fa_compress_kv(k, v, kmask, vmask, Dkc, Dvc, M, T, t0=0, accumulate=False, ck=None, cv=None,
@@ -321,7 +333,8 @@ def fa_compress_kv(k, v, kmask, vmask, Dkc, Dvc, M, T, t0=0, accumulate=False, c
     if v_keep is None:
         v_keep = torch.zeros((B, H, tok8_numel(n_tok, D - Dvc)), dtype=k.dtype, device=dev)
     if workspace is None:
-        workspace = torch.empty(max(compress_kv_workspace_bytes(B, H, N, D, Dkc, Dvc, M), 256), dtype=torch.uint8, device=dev)
+        workspace = torch.empty(max(compress_kv_workspace_bytes(B, H, N, D, Dkc, Dvc, M, k.dtype), 256), dtype=torch.uint8,
+                                device=dev)
     args = (_ptr(k), _ptr(v), _dtype_code(k), k.stride(0), k.stride(1), k.stride(2), B, H, N, D,
             _ptr(kmask), Dkc, _ptr(vmask), Dvc, M, T, t0, int(bool(accumulate)), _ptr(ck), _ptr(cv),
             _ptr(k_keep), 0, _ptr(v_keep), 0, keep_offset, _ptr(workspace), workspace.numel(), _stream_ptr(stream))

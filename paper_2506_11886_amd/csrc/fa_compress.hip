@@ -34,26 +34,6 @@ constexpr int kPairs = 128;      // harmonics per workgroup (256 basis rows)
 constexpr int kCols = 128;       // compressed columns per workgroup
 constexpr unsigned kMaxCLds = 160 * 1024 - 8192;
 
-// Developer aid (compiled out unless FA_TRACE is defined): per-wave cycle stamps.
-#ifdef FA_TRACE
-#ifdef FA_TRACE_PRO
-#define FA_STAMP_OK(i) ((i) < 3 || (i) > 29)
-#define FA_PSTAMP(i) FA_CSTAMP(100 + (i))
-#else
-#define FA_STAMP_OK(i) true
-#define FA_PSTAMP(i) do {} while (0)
-#endif
-#define FA_CSTAMP(i_)                                                                         \
-  do {                                                                                        \
-    const int i = (i_) >= 100 ? (i_) - 100 : (i_);                                            \
-    if ((threadIdx.x & 63) == 0 && (i) < 32 && ((i_) >= 100 || FA_STAMP_OK(i)))                                                \
-      p.trace[(((static_cast<size_t>(blockIdx.z) * gridDim.y + blockIdx.y) * gridDim.x +      \
-                blockIdx.x) * 8 + (threadIdx.x >> 6)) * 32 + (i)] = clock64();                \
-  } while (0)
-#else
-#define FA_CSTAMP(i) do {} while (0)
-#define FA_PSTAMP(i) do {} while (0)
-#endif
 
 typedef float f32x2c __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2c __attribute__((ext_vector_type(2)));
@@ -79,9 +59,6 @@ struct CompressParams {
   double ph_scale;  // 2^32 / T
   float* part;      // [Sc][part_stride] when Sc > 1, chunk s holds [B*H][M][Dc]
   size_t part_stride;   // B*H*M*Dc rounded up to 4 floats
-#ifdef FA_TRACE
-  long long* trace;
-#endif
 };
 
 __device__ __forceinline__ void load8(const bf16_t* p, Frag<bf16_t>& f) { f.load(p); }
@@ -166,7 +143,6 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
       }
     }
   };
-  FA_CSTAMP(0);
   load_x(0);
 
   // ---- dimension ranks: >= 0 index among kept dims, < 0: -(1 + index among compressed) ------
@@ -282,7 +258,6 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
     }
   }
 
-  FA_CSTAMP(1);
   for (int blk = 0; blk < nb; ++blk) {
     const int buf = blk & 1;
     const int js = j0 + blk * kTB;
@@ -340,11 +315,9 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
         if (j < jend) keep[(static_cast<int64_t>(p.keep_offset) + j) * kp + Du + it % npad] = zero_elem(keep);
       }
     }
-    FA_CSTAMP(2 + 4 * blk);
     // -- the next block travels while this one is multiplied
     if (blk + 1 < nb) load_x(blk + 1);
     __syncthreads();
-    FA_CSTAMP(3 + 4 * blk);
 
     // -- kept dims: staging tile -> 128-bit stores
     if (stage) {
@@ -381,7 +354,6 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
         for (int e = 0; e < 8; ++e) dcs += tof(felem(f, e));
       }
     }
-    FA_CSTAMP(4 + 4 * blk);
     // -- harmonics: move the frame to this block, then accumulate E * X_blk
     if (wave_live) {
       if (blk > 0) {
@@ -414,10 +386,8 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
         }
       }
     }
-    FA_CSTAMP(5 + 4 * blk);
   }
 
-  FA_CSTAMP(30);
   // ---- epilogue -----------------------------------------------------------------------------
   if (!project) return;
   float* dst = (p.Sc == 1) ? p.coeffs + static_cast<size_t>(bh) * M * p.Dc
@@ -461,7 +431,6 @@ __global__ __launch_bounds__(kCBlock) void compress_project(CompressParams p) {
         }
       }
   }
-  FA_CSTAMP(31);
 }
 
 // ---------------------------------------------------------------------------
@@ -537,14 +506,12 @@ __device__ __forceinline__ void project_fast_body(const CompressParams& p, const
 #pragma unroll
     for (int i = 0; i < TOK; ++i) xr[i].load(xthr + static_cast<int64_t>(min(js + i, p.N - 1)) * p.sx_n);
   };
-  FA_CSTAMP(0);
   // the mask row first (it is waited for first), then the first two X blocks
   uint8_t mb[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) mb[j] = p.mask[static_cast<size_t>(bh) * D + lane + 64 * j];
   load_x(xra, 0);
   load_x(xrb, 1);
-  FA_PSTAMP(23);
 
   // ---- per-wave constants: E fragments (A operand) and frame twiddles -------------------
   const int rows_here = 2 * min(kPairs, p.nmax - mc * kPairs);   // live basis rows of this row block
@@ -605,7 +572,6 @@ __device__ __forceinline__ void project_fast_body(const CompressParams& p, const
       }
     }
   }
-  FA_PSTAMP(24);
   // ---- dimension ranks, wave-local (no LDS, no barrier): the mask bits of all 128 dims sit in two
   // ballots; a lane's 8 dims are consecutive, so one byte of a ballot holds their bits and the
   // rank of its first dim is a population count below it
@@ -625,7 +591,6 @@ __device__ __forceinline__ void project_fast_body(const CompressParams& p, const
       else sc_off[e] = ks_off + static_cast<uint32_t>(kp) * kFP * 2;   // spare slot: the value is not needed
     }
   }
-  FA_PSTAMP(25);
   // The pad rows of the kept-dim staging tiles (dims Du .. kp-1, which leave as the zero pad of the
   // rows layout) are zero for the whole kernel.  Nothing else needs clearing: every token of a used
   // column is written before it is read, and columns past Dc only feed accumulator columns that
@@ -649,7 +614,6 @@ __device__ __forceinline__ void project_fast_body(const CompressParams& p, const
   f32x4 acc_dc = {0.f, 0.f, 0.f, 0.f};   // rows are identical: the column sums of tile rgw
 
   T* keep = static_cast<T*>(p.keep) + static_cast<int64_t>(bh) * p.keep_stride;
-  FA_PSTAMP(26);
   // (no barrier here: the first scatter touches no pad row, and the barrier after it also orders
   // the zero fill before the first read of the staging tile)
   // ---- kept dims leave the staging tile as 128-bit stores: one or more vectors per thread ------
@@ -666,7 +630,6 @@ __device__ __forceinline__ void project_fast_body(const CompressParams& p, const
   else kv_a = kv_0 / kv_d;
   const int kv_b = kv_0 - kv_a * kv_d;                           // 8-dim group (rows) or dim (tok8)
 
-  FA_CSTAMP(1);
   auto scatter_block = [&](Frag<T> (&xr)[TOK], int blk) {   // this thread's 4 tokens x 8 dims of block blk -> LDS
     const int js = j0 + blk * kFB;
     unsigned char* bb = smem + (blk & 1) * bufb;
@@ -859,8 +822,6 @@ __device__ __forceinline__ void project_fast_body(const CompressParams& p, const
         __builtin_amdgcn_sched_group_barrier(0x300, 1, 0);   // one LDS access
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (dt == 0) FA_CSTAMP(3 + 4 * blk);
-      if (dt == DT - 1) FA_CSTAMP(6 + 4 * blk);
     }
     {
       Frag<T> (&dcx)[kFK] = (DT & 1) ? bxb : bxa;
@@ -879,9 +840,7 @@ __device__ __forceinline__ void project_fast_body(const CompressParams& p, const
       if (blk + 1 < nb) scatter_block(xnext, blk + 1);
       if (write_keep) keep_out(blk);
     }
-    FA_CSTAMP(4 + 4 * blk);
     __syncthreads();
-    FA_CSTAMP(5 + 4 * blk);
   };
   // Loads are issued where every wave passes, never under a condition (the result would have to be
   // merged with the other path, i.e. waited for at once): as soon as a register set has been
@@ -889,7 +848,6 @@ __device__ __forceinline__ void project_fast_body(const CompressParams& p, const
   scatter_block(xra, 0);
   load_x(xra, 2);
   __syncthreads();
-  FA_CSTAMP(2);
   if constexpr (KM >= 0) {
     // blocks go in pairs without a branch in between; an odd chunk ends with a block of zeros
     // (the scatter past the chunk writes zeros), which only turns the frame once more
@@ -906,7 +864,6 @@ __device__ __forceinline__ void project_fast_body(const CompressParams& p, const
     }
   }
 
-  FA_CSTAMP(30);
   // ---- epilogue -----------------------------------------------------------------------------
   if (!project) return;
   float* dst = (p.Sc == 1) ? p.coeffs + static_cast<size_t>(bh) * M * p.Dc
@@ -957,7 +914,6 @@ __device__ __forceinline__ void project_fast_body(const CompressParams& p, const
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_wave_barrier();
       }
-      FA_CSTAMP(31);
       return;
     }
 #pragma unroll
@@ -985,7 +941,6 @@ __device__ __forceinline__ void project_fast_body(const CompressParams& p, const
         }
       }
   }
-  FA_CSTAMP(31);
 }
 
 template <int DT, int KM>
@@ -1092,9 +1047,6 @@ static CompressPlan make_compress_plan(int dtype, int B, int H, int N, int D, in
                  ? align_up(static_cast<size_t>(pl.Sc) * ((static_cast<size_t>(B) * H * M * Dc + 3) & ~size_t(3)) *
                                 sizeof(float), 256)
                  : 0;
-#ifdef FA_TRACE
-  pl.total = align_up(pl.total, 256) + static_cast<size_t>(B) * H * pl.MC * pl.DCn * (pl.Sc > 0 ? pl.Sc : 1) * 8 * 32 * sizeof(long long);
-#endif
   const unsigned es = dtype == FA_F32 ? 4 : 2;
   const int Du = D - Dc, kp = (Du + 7) & ~7;
   const unsigned rows_elems = kTB * (kp + 8), tok8_elems = static_cast<unsigned>(Du) * kLdX;
@@ -1120,14 +1072,12 @@ template <int DT, int KM>
 static int launch_project_fast(const CompressParams& p, const CompressPlan& pl, unsigned lds, hipStream_t st,
                                KernelTimers* tm) {
   auto kern = compress_project_fast<DT, KM>;
-  static unsigned granted = 48 * 1024;
-  if (lds > granted) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(kMaxCLds)) != hipSuccess)
-      return FA_ERR_HIP;
-    granted = kMaxCLds;
-  }
+  // the dynamic-LDS ceiling belongs to the kernel as loaded on the current device: raised whenever a
+  // launch needs it (a host-side table write, no stream operation)
+  if (lds > 48u * 1024u &&
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          static_cast<int>(kMaxCLds)) != hipSuccess)
+    return FA_ERR_HIP;
   dim3 grid(pl.Sc, pl.MC, p.B * p.H);
   FA_LAUNCH_TIMED(tm, 0, kern, grid, dim3(kCBlock), lds, st, p);
   return FA_OK;
@@ -1136,14 +1086,10 @@ static int launch_project_fast(const CompressParams& p, const CompressPlan& pl, 
 template <typename T, int DT, int kXR, bool kFast, bool kSplit>
 static int launch_project(const CompressParams& p, const CompressPlan& pl, hipStream_t st, KernelTimers* tm) {
   auto kern = compress_project<T, DT, kXR, kFast, kSplit>;
-  static unsigned granted = 48 * 1024;
-  if (pl.lds > granted) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(kMaxCLds)) != hipSuccess)
-      return FA_ERR_HIP;
-    granted = kMaxCLds;
-  }
+  if (pl.lds > 48u * 1024u &&
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          static_cast<int>(kMaxCLds)) != hipSuccess)
+    return FA_ERR_HIP;
   dim3 grid(pl.Sc, pl.MC * pl.DCn, p.B * p.H);
   FA_LAUNCH_TIMED(tm, 0, kern, grid, dim3(kCBlock), pl.lds, st, p);
   return FA_OK;
@@ -1153,13 +1099,18 @@ static int launch_project(const CompressParams& p, const CompressPlan& pl, hipSt
 
 extern "C" {
 
-size_t fa_compress_workspace_bytes(int B, int H, int N, int D, int Dc, int M) {
-  if (fa::check_compress_shapes(FA_BF16, B, H, N, D, Dc, M, M > N ? M : N, 0) != FA_OK) return 0;
-  // enough for either element type (fp32 inputs use shorter token chunks, hence more partials)
-  const size_t tb = fa::make_compress_plan(FA_BF16, B, H, N, D, Dc, M, FA_KEEP_ROWS, 0).total;
-  const size_t tf = fa::make_compress_plan(FA_F32, B, H, N, D, Dc, M, FA_KEEP_ROWS, 0).total;
-  const size_t t = tb > tf ? tb : tf;
+size_t fa_compress_workspace_bytes_for(int dtype, int B, int H, int N, int D, int Dc, int M) {
+  if (dtype != FA_F32 && dtype != FA_BF16) return 0;
+  if (fa::check_compress_shapes(dtype, B, H, N, D, Dc, M, M > N ? M : N, 0) != FA_OK) return 0;
+  const size_t t = fa::make_compress_plan(dtype, B, H, N, D, Dc, M, FA_KEEP_ROWS, 0).total;
   return t ? t : 256;
+}
+
+size_t fa_compress_workspace_bytes(int B, int H, int N, int D, int Dc, int M) {
+  // enough for either element type (fp32 inputs use shorter token chunks, hence more partials)
+  const size_t tb = fa_compress_workspace_bytes_for(FA_BF16, B, H, N, D, Dc, M);
+  const size_t tf = fa_compress_workspace_bytes_for(FA_F32, B, H, N, D, Dc, M);
+  return tb > tf ? tb : tf;
 }
 
 static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n, int B,
@@ -1211,10 +1162,6 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
   p.ph_scale = 4294967296.0 / static_cast<double>(T);
   p.part = static_cast<float*>(workspace);
   p.part_stride = (static_cast<size_t>(B) * H * M * Dc + 3) & ~size_t(3);
-#ifdef FA_TRACE
-  p.trace = reinterpret_cast<long long*>(static_cast<char*>(workspace) + pl.total -
-                                         static_cast<size_t>(B) * H * pl.MC * pl.DCn * (pl.Sc > 0 ? pl.Sc : 1) * 8 * 32 * sizeof(long long));
-#endif
 
   if (only_params) {   // the caller launches (the K | V pair entry)
     *only_params = p;
@@ -1284,10 +1231,17 @@ int fa_compress(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx
                        workspace_bytes, hip_stream, nullptr);
 }
 
-size_t fa_compress_kv_workspace_bytes(int B, int H, int N, int D, int Dkc, int Dvc, int M) {
-  const size_t a = fa_compress_workspace_bytes(B, H, N, D, Dkc, M), b = fa_compress_workspace_bytes(B, H, N, D, Dvc, M);
+size_t fa_compress_kv_workspace_bytes_for(int dtype, int B, int H, int N, int D, int Dkc, int Dvc, int M) {
+  const size_t a = fa_compress_workspace_bytes_for(dtype, B, H, N, D, Dkc, M);
+  const size_t b = fa_compress_workspace_bytes_for(dtype, B, H, N, D, Dvc, M);
   if (a == 0 || b == 0) return 0;
   return ((a + 255) & ~size_t(255)) + b;
+}
+
+size_t fa_compress_kv_workspace_bytes(int B, int H, int N, int D, int Dkc, int Dvc, int M) {
+  const size_t tb = fa_compress_kv_workspace_bytes_for(FA_BF16, B, H, N, D, Dkc, Dvc, M);
+  const size_t tf = fa_compress_kv_workspace_bytes_for(FA_F32, B, H, N, D, Dkc, Dvc, M);
+  return tb > tf ? tb : tf;
 }
 
 // tm / tm2 (optional): event pairs for the timed entry point; tm2 is used only when the call falls
@@ -1299,8 +1253,9 @@ static int compress_kv_impl(const void* k, const void* v, int dtype, int64_t sx_
                             void* workspace, size_t workspace_bytes, void* hip_stream, fa::KernelTimers* tm,
                             fa::KernelTimers* tm2) {
   using namespace fa;
-  const size_t wk = (fa_compress_workspace_bytes(B, H, N, D, Dkc, M) + 255) & ~size_t(255);
-  const size_t wv = fa_compress_workspace_bytes(B, H, N, D, Dvc, M);
+  if (dtype != FA_F32 && dtype != FA_BF16) return FA_ERR_UNSUPPORTED;
+  const size_t wk = (fa_compress_workspace_bytes_for(dtype, B, H, N, D, Dkc, M) + 255) & ~size_t(255);
+  const size_t wv = fa_compress_workspace_bytes_for(dtype, B, H, N, D, Dvc, M);
   if (wk == 0 || wv == 0) return FA_ERR_SHAPE;
   if (!workspace) return FA_ERR_NULL;
   if (workspace_bytes < wk + wv || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return FA_ERR_WORKSPACE;
@@ -1336,15 +1291,11 @@ static int compress_kv_impl(const void* k, const void* v, int dtype, int64_t sx_
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   CompressParamsKV pp{pk, pv};
   const bool narrow = (Dkc > Dvc ? Dkc : Dvc) <= 96;
-  static unsigned granted = 48 * 1024;
-  if (lds > granted) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(compress_project_fast_kv<6>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxCLds)) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(compress_project_fast_kv<8>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxCLds)) != hipSuccess)
-      return FA_ERR_HIP;
-    granted = kMaxCLds;
-  }
+  if (lds > 48u * 1024u &&
+      hipFuncSetAttribute(narrow ? reinterpret_cast<const void*>(compress_project_fast_kv<6>)
+                                 : reinterpret_cast<const void*>(compress_project_fast_kv<8>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxCLds)) != hipSuccess)
+    return FA_ERR_HIP;
   const dim3 grid(plk.Sc, plk.MC, 2 * B * H);
   if (narrow) FA_LAUNCH_TIMED(tm, 0, compress_project_fast_kv<6>, grid, dim3(kCBlock), lds, stream, pp);
   else FA_LAUNCH_TIMED(tm, 0, compress_project_fast_kv<8>, grid, dim3(kCBlock), lds, stream, pp);

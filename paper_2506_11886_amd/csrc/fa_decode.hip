@@ -59,26 +59,6 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x2d __attribute__((ext_vector_type(2)));
 
-// Developer aid (compiled out unless FA_TRACE is defined): per-wave cycle stamps
-// at phase boundaries, written behind the partial records of the workspace.
-#ifdef FA_TRACE
-#define FA_STAMP(i)                                                                          \
-  do {                                                                                       \
-    if ((threadIdx.x & 63) == 0)                                                             \
-      p.trace[((static_cast<size_t>(blockIdx.y) * gridDim.x + blockIdx.x) * 4 +              \
-               (threadIdx.x >> 6)) * 16 + (i)] = clock64();                                  \
-  } while (0)
-// stamps of decode_finish live behind those of decode_partial
-#define FA_FSTAMP(i)                                                                         \
-  do {                                                                                       \
-    if ((threadIdx.x & 63) == 0)                                                             \
-      p.trace[(static_cast<size_t>(p.B) * p.Hkv * (p.Sw + p.Sm) * 4 +                        \
-               (static_cast<size_t>(blockIdx.y) * gridDim.x + blockIdx.x) * 4 + (threadIdx.x >> 6)) * 16 + (i)] = clock64(); \
-  } while (0)
-#else
-#define FA_STAMP(i) do {} while (0)
-#define FA_FSTAMP(i) do {} while (0)
-#endif
 
 struct DecodeParams {
   const void* q;
@@ -107,10 +87,6 @@ struct DecodeParams {
   float* part_m;    // [B,Hq,Sm,recm]
   float* part_w;    // [B,Hq,Sw,recw]
   float* out;       // [B,Hq,D]
-#ifdef FA_TRACE
-  long long* trace;
-  int trace_step;   // which step of a chunk carries the fine stamps
-#endif
 };
 
 // ---------------------------------------------------------------------------
@@ -482,7 +458,6 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
   float* red = reinterpret_cast<float*>(smem + 16 * FA_MAX_HEAD_DIM * sizeof(T)) + kWaves * kWRows * kMaxG;
   __shared__ float wm[kWaves][kMaxG], wl[kWaves][kMaxG];
 
-  FA_STAMP(0);
   // ---- global operands: q of the group, this wave's K rows (rows past the end re-read the last) --
   constexpr int kQLoads = kMaxG * FA_MAX_HEAD_DIM / 8 / kBlock;
   const T* q = static_cast<const T*>(p.q) + hq0 * D;
@@ -502,7 +477,6 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) ka[cc][rb].load(krow[rb] + min(cc * 32 + 8 * q4, D - 8));
 
-  FA_STAMP(1);
   // ---- q into LDS (rows >= G zero) ---------------------------------------------------
   {
     const int nz = (16 - G) * D * static_cast<int>(sizeof(T)) / 16;
@@ -515,7 +489,6 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
   }
   __syncthreads();
 
-  FA_STAMP(2);
   // ---- scores of the wave's 64 rows: lane (head r16, q4) gets rows 16 rb + 4 q4 + v ----------------
   f32x4 sacc[kRB];
 #pragma unroll
@@ -549,7 +522,6 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
 #pragma unroll
   for (int i = 0; i < kWBatch; ++i) vf0[i].load(vlane + static_cast<int64_t>(min(jw + rg + i * nrg, jlast)) * D);
 
-  FA_STAMP(3);
   // ---- softmax over the wave's rows, per head -----------------------------------------------------
   float m_w = -INFINITY;
 #pragma unroll
@@ -580,7 +552,6 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
     wl[wave][r16] = l_w;
   }
   __syncthreads();   // statistics of all waves (and this wave's p tile) are visible
-  FA_STAMP(4);
 
   // record of head h: [max, sum, -, -, acc[D]]
   float* part = p.part_w + (hq0 * p.Sw + s) * p.recw;
@@ -661,7 +632,6 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
       }
     }
   }
-  FA_STAMP(5);
 }
 
 // ---------------------------------------------------------------------------
@@ -793,7 +763,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
     }
   };
 
-  FA_STAMP(0);
   // ---- (0) everything that comes from global memory is requested first ------------
   // series coefficients of the group: G * Mint contiguous floats
   constexpr int kGLoads = kMaxG * Mint / 4 / kBlock;
@@ -818,7 +787,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
   Frag<T> vfA[kVU][kVR], vfB[kVU][kVR];
   load_step(kfA, vfA, c0);
 
-  FA_STAMP(1);
   // ---- this wave's slices of the E table ------------------------------------------------------
   // K side, A operand of (own chunk i, row block rb): row u(rb, r16), slots 8 q4 .. 8 q4 + 7 of the
   // chunk = (cos, sin) of 4 consecutive orders.  V side, B operand of (own chunk i, cos | sin,
@@ -910,7 +878,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
     for (int i = 0; i < CW; ++i)
       phase_cs<T>(static_cast<uint32_t>(16 * (wave * CW + i) + r16 + 1) * ph_step, &tc[i], &ts[i]);
   }
-  FA_STAMP(2);
 
   // ---- series coefficients and packed query into LDS ---------------------------------------------
 #pragma unroll
@@ -927,7 +894,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
   // the second step's operands are requested only now: a wave that asks for more than the memory
   // pipeline holds stalls at the request, and the table above is better built before that
   if (c0 + step < c1) load_step(kfB, vfB, c0 + step);
-  FA_STAMP(3);
 
   f32x4 racc[2 * CW];           // r' = P^T E (own orders), frame of the current step
   f32x4 oacc[DVTM];             // sum_j p_j V^mu[j,:] over this wave's token blocks
@@ -942,11 +908,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
 
   auto do_step = [&](Frag<T> (&kf)[kMaxKT], Frag<T> (&vf)[kVU][kVR], int base) {
     const bool tail = base + step > c1;
-#ifdef FA_TRACE
-    const bool traced = base == c0 + p.trace_step * step;   // developer trace: the step that carries the fine stamps
-#else
-    constexpr bool traced = false;
-#endif
     f32x4 sacc[kRB];
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -986,7 +947,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
       for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], eA[i][rb], bg);
     }
 
-    if (traced) FA_STAMP(4);
     // -- (b) kept K dims, own row blocks: A = K^mu rows, B = q masked to the tile's columns --
     if (kchunks > 0) {
 #pragma unroll
@@ -1017,22 +977,18 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
       }
     }
 
-    if (traced) FA_STAMP(5);
     // -- (c) the partial scores of the four waves meet; this wave sums its four columns --------
     {
       f32x4* xw = xs + (wave * kRB) * 64 + lane;
 #pragma unroll
       for (int rb = 0; rb < kRB; ++rb) xw[rb * 64] = sacc[rb];
     }
-    if (traced) FA_STAMP(6);
     __syncthreads();
-    if (traced) FA_STAMP(7);
     f32x4 sv;
     {
       const f32x4* xr = xs + orb * 64 + oq4 * 16 + ocol;
       sv = ((xr[0 * kRB * 64] + xr[1 * kRB * 64]) + xr[2 * kRB * 64]) + xr[3 * kRB * 64];
     }
-    if (traced) FA_STAMP(8);
     // -- (d) online softmax of the own columns: lane holds rows u = 32x + 8 oq4 + 4y + v (orb = 2x + y)
     float pv[4];
     float m_tile = -INFINITY;
@@ -1082,7 +1038,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
       if (lane < 4) alpha_s[ocol] = alpha;
     }
     __syncthreads();
-    if (traced) FA_STAMP(9);
     // -- (e) bring the accumulators into this step's frame --------------------------------
     if (!first) {
       // accumulator rows are S columns 4*q4 + v
@@ -1103,7 +1058,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
     first = false;
     last_base = base;
 
-    if (traced) FA_STAMP(10);
     // -- (f) V side, own orders: r' += P^T E ------------------------------------------------------
     Frag<T> pt[kXN], pl[kXN];
 #pragma unroll
@@ -1121,7 +1075,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
         mma_k32(racc[2 * i + 1], ps, eB[i][1][x]);
       }
     }
-    if (traced) FA_STAMP(11);
     // -- (g) kept V dims, own token blocks: O += P^T V^mu -----------------------------------------
     if (DVT > 0) {
 #pragma unroll
@@ -1153,7 +1106,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
         }
       }
     }
-    if (traced) FA_STAMP(12);
   };
 
   // two steps per trip: the operands of a step are requested while the step before it runs
@@ -1166,7 +1118,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
     }
   }
 
-  FA_STAMP(13);
   // ---- merge the tiles of a head --------------------------------------------------------------
   // the owners publish the statistics of their columns; then every lane takes those of its S column
   l_run = row_stride_sum(l_run, 4);
@@ -1227,7 +1178,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
         for (int v = 0; v < 4; ++v) ro[(4 * q4 + v) * po + 16 * dt + r16] = f[v] * oacc[dt][v];
   }
   __syncthreads();
-  FA_STAMP(14);
 
   // record of head h: [max, sum, -, -, acc over the kept dims (16 DVT), r (Mint, V-side order)]
   const size_t rec_h = static_cast<size_t>(p.Sm) * p.recm;
@@ -1256,7 +1206,6 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
       *reinterpret_cast<f32x4*>(rec0 + h * rec_h + 4 + 4 * x4) = v;
     }
   }
-  FA_STAMP(15);
 }
 
 // ---------------------------------------------------------------------------
@@ -1755,7 +1704,6 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
   const bool do_cv = Sm > 0 && Dvc > 0;
   const int d0 = kFinDims * sl;
 
-  FA_FSTAMP(0);
   // ---- global operands, in the order they are needed -----------------------------------------
   // (0) the mask row: it decides which columns of C_v and of the accumulators this slice reads
   uint8_t vmb[4];
@@ -1770,7 +1718,6 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
     ms[i] = r[0];
     ls[i] = r[1];
   }
-  FA_FSTAMP(10);
   // (2) series sums of the middle records: thread (4 columns, group of records)
   const int cr4 = p.Mint / 4, ngr = kFinBlock / cr4;
   const int c4r = tid % cr4, gr = tid / cr4;
@@ -1783,7 +1730,6 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
       if (u * ngr < Sm)             // at once); rounds no lane needs are skipped by the whole workgroup
         rv[u] = *reinterpret_cast<const f32x4*>(pr + static_cast<size_t>(min(gr + u * ngr, Sm - 1)) * recm);
   }
-  FA_FSTAMP(11);
   // (3) this slice's columns of the full-row records: thread (4 columns, group of records)
   constexpr int kW4 = kFinDims / 4, kWG = kFinBlock / kW4;
   const int c4w = tid % kW4, gw = tid / kW4;
@@ -1797,7 +1743,6 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
       if (u * kWG < Sw)
         wv[u] = *reinterpret_cast<const f32x4*>(pw + static_cast<size_t>(min(gw + u * kWG, Sw - 1)) * recw + 4 + dw);
   }
-  FA_FSTAMP(12);
   // ranks of this slice's dims (needs only the mask)
   uint64_t vbal[4];
 #pragma unroll
@@ -1806,7 +1751,6 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
   const int dme = d0 + col;
   const int rk = (dme < D) ? dim_rank(vbal, dme) : 0;
   const bool is_c = dme < D && rk < 0, is_k = dme < D && rk >= 0;
-  FA_FSTAMP(13);
   // (4) C_v.  The compressed dims of a slice have consecutive ranks r0 .. r0 + nc - 1, i.e. the slice
   // needs a contiguous band of C_v's columns.  With Dvc a multiple of 4 the band is read as 128-bit
   // vectors: thread (column quad cq, row group rg) takes rows rg, rg + ngrp, ...  Otherwise every
@@ -1842,7 +1786,6 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
     for (int u = 0; u < kUc; ++u)
       if (u * kCG < M) cvv[u] = cvc[static_cast<size_t>(min(cg + u * kCG, M - 1)) * Dvc];
   }
-  FA_FSTAMP(14);
   const float* pk = pm + 4 + (is_k ? rk : 0);
   float kv[kUk];
   if (Sm > 0) {
@@ -1851,7 +1794,6 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
       if (u * kCG < Sm) kv[u] = pk[static_cast<size_t>(min(cg + u * kCG, Sm - 1)) * recm];
   }
 
-  FA_FSTAMP(1);
   // ---- global max, per-record factors, normaliser ---------------------------------------------
   float m = -INFINITY;
 #pragma unroll
@@ -1887,7 +1829,6 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
     L += wsum[w];
     Lm += wsum_m[w];
   }
-  FA_FSTAMP(2);
 
   // ---- r in basis order, weighted by the inverse squared norms ---------------------------------
   if (do_cv) {
@@ -1936,7 +1877,6 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
     if (tid == kFinBlock - 1) rr[0] = Lm * basis_weight(0, p.T);   // constant function: sum of p over the middle rows
   }
   __syncthreads();
-  FA_FSTAMP(3);
 
   // ---- per dim: sum_m rr[m] C_v[m, i] (compressed) or the merged accumulator (kept) ------------
   if (vec_cv) {   // band of C_v: partial sums per (row group, column quad); red4 is free again
@@ -1985,7 +1925,6 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
     }
     p.out[static_cast<size_t>(hq) * D + d0 + tid] = v / L;
   }
-  FA_FSTAMP(4);
 }
 
 // ---------------------------------------------------------------------------
@@ -2251,14 +2190,14 @@ __global__ __launch_bounds__(kFinBlock, kFin2Wide == 16 ? 2 : 4) void decode_fin
 struct DecodePlan {
   int Gp, KT, Mint, cw, Sw, Sm, chunk_m, recm, recw;
   unsigned lds_tab, lds_total;
-  size_t off_gs, off_g0, off_qk, off_pm, off_pw, off_trace, total;
+  size_t off_gs, off_g0, off_qk, off_pm, off_pw, total;
 };
 
 static int round_up(int x, int a) { return (x + a - 1) / a * a; }
 
-static int series_chunks_per_wave(int M) {   // compiled series lengths: 128, 256, 512 slots
+static int series_chunks_per_wave(int M) {   // compiled series lengths: 128, 256, 512, 1024 slots
   const int slots = 2 * (M / 2);
-  for (int cw : {1, 2, 4})
+  for (int cw : {1, 2, 4, 8})
     if (slots <= kWaves * cw * 32) return cw;
   return 0;
 }
@@ -2322,11 +2261,7 @@ static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, 
   pl.off_qk = pl.off_g0 + align_up(BHq * sizeof(float), 256);
   pl.off_pm = pl.off_qk + align_up(BHq * Dkq * 4 + 16, 256);   // sized for fp32: the size query has no dtype
   pl.off_pw = pl.off_pm + align_up(BHq * pl.Sm * pl.recm * sizeof(float) + 16, 256);
-  pl.off_trace = pl.off_pw + align_up(BHq * pl.Sw * pl.recw * sizeof(float) + 16, 256);
-  pl.total = pl.off_trace;
-#ifdef FA_TRACE
-  pl.total += (static_cast<size_t>(B) * Hkv * (pl.Sw + pl.Sm) * 4 + BHq * 16) * 16 * sizeof(long long);
-#endif
+  pl.total = pl.off_pw + align_up(BHq * pl.Sw * pl.recw * sizeof(float) + 16, 256);
   return true;
 }
 
@@ -2341,7 +2276,7 @@ static int check_decode_shapes(int dtype, int B, int Hq, int Hkv, int D, int Dkc
   if (D % 8 != 0 || D > FA_MAX_HEAD_DIM) return FA_ERR_UNSUPPORTED;
   if (Hq / Hkv > FA_MAX_GROUP || M > FA_MAX_DECODE_STATES || num_splits > FA_MAX_SPLITS)
     return FA_ERR_UNSUPPORTED;
-  if (dtype == FA_F32 && M > FA_MAX_DECODE_STATES / 2) return FA_ERR_UNSUPPORTED;
+  if (dtype == FA_F32 && M > FA_MAX_DECODE_STATES_F32) return FA_ERR_UNSUPPORTED;
   if (D - Dvc > 16 * kMaxDvTiles) return FA_ERR_UNSUPPORTED;
   if (static_cast<long>(B) * Hkv > 65535) return FA_ERR_UNSUPPORTED;
   return FA_OK;
@@ -2432,7 +2367,7 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
   int rc;
   if constexpr (sizeof(T) == 2) {
     // the specialised kernel: groups of at most four query heads, 1 .. 32 kept dims on both sides
-    if (p.Sm > 0 && p.G <= 4 && p.Dku > 0 && p.Dku <= 32 && p.Dvu > 0 && p.Dvu <= 32) {
+    if (p.Sm > 0 && pl.cw <= 4 && p.G <= 4 && p.Dku > 0 && p.Dku <= 32 && p.Dvu > 0 && p.Dvu <= 32) {
       rc = launch_partial_fast(p, pl, st, tm);
       if (rc != FA_OK) return rc;
       return launch_finish<T>(p, st, tm, prior);
@@ -2448,8 +2383,9 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
     case 1: FA_LAUNCH_PARTIAL(1); break;
     case 2: FA_LAUNCH_PARTIAL(2); break;
     default:
-      if constexpr (sizeof(T) == 2) {
-        FA_LAUNCH_PARTIAL(4);
+      if constexpr (sizeof(T) == 2) {   // fp32 inputs stop at 256 states (two chunks per wave)
+        if (pl.cw == 4) FA_LAUNCH_PARTIAL(4);
+        else FA_LAUNCH_PARTIAL(8);
       } else {
         rc = FA_ERR_UNSUPPORTED;
       }
@@ -2550,10 +2486,6 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   p.part_m = reinterpret_cast<float*>(ws + pl.off_pm);
   p.part_w = reinterpret_cast<float*>(ws + pl.off_pw);
   p.out = out;
-#ifdef FA_TRACE
-  p.trace_step = getenv("FA_TRACE_STEP") ? atoi(getenv("FA_TRACE_STEP")) : 1;
-  p.trace = reinterpret_cast<long long*>(ws + pl.off_trace);
-#endif
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   return dtype == FA_F32 ? launch_decode<float>(p, pl, stream, tm)
                          : launch_decode<bf16_t>(p, pl, stream, tm);

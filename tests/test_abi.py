@@ -23,7 +23,8 @@ def test_library_exports_every_declared_symbol():
     assert {"fa_compress", "fa_decode", "fa_compress_workspace_bytes",
             "fa_decode_workspace_bytes", "fa_decode_default_splits", "fa_status_string",
             "fa_append", "fa_select_dims", "fa_select_workspace_bytes", "fa_decode_mq", "fa_compress_kv",
-            "fa_compress_kv_workspace_bytes", "fa_decode_static"} <= names
+            "fa_compress_kv_workspace_bytes", "fa_decode_static", "fa_compress_workspace_bytes_for",
+            "fa_compress_kv_workspace_bytes_for"} <= names
     for n in names:
         assert hasattr(fa.lib, n), n
 
@@ -89,6 +90,14 @@ def test_workspace_queries():
     assert fa.decode_workspace_bytes(1, 7, 2, 128, 96, 96, 256, 100, 10, 0) == 0
     assert fa.compress_workspace_bytes(8, 32, 4096, 128, 96, 256) >= 256
     assert fa.decode_default_splits(1, 32, 8, 256, 31740, 1028) >= 1
+    # the element-type-aware query: never more than the one that covers both, far less for long bf16 segments
+    both = fa.compress_workspace_bytes(1, 8, 129020, 128, 112, 512)
+    bf16 = fa.compress_workspace_bytes(1, 8, 129020, 128, 112, 512, fa.FA_BF16)
+    f32 = fa.compress_workspace_bytes(1, 8, 129020, 128, 112, 512, fa.FA_F32)
+    assert 0 < bf16 <= f32 == both and bf16 * 4 < both
+    assert fa.compress_kv_workspace_bytes(1, 8, 129020, 128, 112, 112, 512, fa.FA_BF16) < \
+        fa.compress_kv_workspace_bytes(1, 8, 129020, 128, 112, 112, 512)
+    assert fa.lib.fa_compress_workspace_bytes_for(7, 1, 8, 1000, 128, 96, 64) == 0
 
 
 def test_append_rejects_bad_arguments_on_the_host():

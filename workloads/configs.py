@@ -95,6 +95,12 @@ CONFIGS = (
 )
 
 
+# The setting the paper ran (Section 4.1: L_init 4, L_local 1024, k = 512, 32K context) on two KV heads
+# of a LLaMA-3-8B-shaped layer: not a benchmark line, a full-size parity case.
+PAPER_SETTING = FAConfig("paper_k512_32k", 6, B=1, Hq=8, Hkv=2, D=128, dtype="bf16", Li=4, Lw=1024,
+                         N=31740, Dkc=96, Dvc=96, M=1023)
+
+
 def get_config(key) -> FAConfig:
     """Look a config up by 1-based index or by name."""
     for c in CONFIGS:
@@ -146,6 +152,12 @@ def small_variants():
                 Dkc=6, Dvc=3, M=304, dtype="bf16"),
         replace(base, name="m512", index=23, B=1, Hq=4, Hkv=1, D=128, N=1500, Lw=40,
                 Dkc=112, Dvc=112, M=512, dtype="bf16"),
+        # the paper's own state size: k = 512 complex orders = 1023 live real functions (1024 with the
+        # unpaired cosine), Section 4.1
+        replace(base, name="m1023_paper", index=31, B=1, Hq=4, Hkv=1, D=128, N=3000, Lw=64,
+                Dkc=96, Dvc=96, M=1023, dtype="bf16"),
+        replace(base, name="m1024_g2", index=32, B=1, Hq=4, Hkv=2, D=128, N=2500, Lw=10,
+                Dkc=112, Dvc=104, M=1024, dtype="bf16"),
         # the paper's regime: the period is the maximum context length, the segment covers part of it
         replace(base, name="period_2n", index=27, B=1, Hq=4, Hkv=1, D=128, N=1111, Lw=70,
                 Dkc=96, Dvc=104, M=96, dtype="bf16", period=2222),
