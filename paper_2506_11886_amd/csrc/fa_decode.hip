@@ -76,6 +76,7 @@ struct DecodeParams {
   int Gp, KT;       // group size padded to a power of two, tiles per wave step
   int Mint;         // series length: 2 * (M/2) padded to a compiled size
   int Sw, Sm;       // chunks of full-width rows / of middle rows (middle chunks come first)
+  int cpw, Smw;     // middle chunks per workgroup and middle workgroups per (sequence, KV head): Sm unless cpw > 1
   int chunk_m;      // middle rows per chunk (multiple of the workgroup step)
   int recm, recw;   // floats per partial record: 4 + 16 ceil(Dvu/16) + Mint (middle), 4 + D (full rows)
   unsigned lds_tab; // bytes of the exchange / reduction region of a middle-row workgroup
@@ -441,7 +442,7 @@ constexpr int kWBatch = 8;      // V rows a lane has in flight
 
 template <typename T>
 __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigned char* smem) {
-  const int s = blockIdx.x - p.Sm, bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int s = blockIdx.x - p.Smw, bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
   const int G = p.G, D = p.D;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1235,6 +1236,159 @@ __device__ __forceinline__ float cross_row_sum(float v) {
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
+// ---------------------------------------------------------------------------
+// 2a'. full-width rows, specialised: bf16, head dim 128, at most four query columns
+// ---------------------------------------------------------------------------
+// Same arithmetic as partial_full_rows (256 rows per workgroup, 64 per wave).  Everything a wave
+// needs from global memory - its 64 K rows, its 64 V rows and the queries, which go straight into
+// B operands - is requested at the start, the softmax of a wave stays inside the wave, and the
+// waves meet once, at the end.
+template <typename T>
+__device__ __forceinline__ void partial_full_fast(const DecodeParams& p, unsigned char* smem) {
+  static_assert(sizeof(T) == 2, "16-bit elements");
+  constexpr int D = 128, kH = 4;                        // head dim, query columns
+  const int s = blockIdx.x - p.Smw, bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int G = p.G;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q4 = lane >> 4, r16 = lane & 15;
+  const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
+  const int jw = s * kWChunk + wave * kWRows;
+  const int nw = max(0, min(kWRows, p.W - jw));
+  const int jlast = p.W - 1;
+  const int jvis = p.W - p.Tq + r16 / p.Gq;             // last row the query token of column r16 may see
+
+  float* pw = reinterpret_cast<float*>(smem) + wave * kWRows * kH;          // [64 rows][4 columns] probabilities
+  float* red = reinterpret_cast<float*>(smem) + kWaves * kWRows * kH;      // [waves][4 columns][128 dims]
+  float* wm = red + kWaves * kH * D;                                        // [waves][4] maxima
+  float* wl = wm + kWaves * kH;                                             // [waves][4] sums
+
+  // ---- global operands ------------------------------------------------------------------------
+  const T* kbase = static_cast<const T*>(p.k_full) + bh * p.full_stride;
+  const T* vbase = static_cast<const T*>(p.v_full) + bh * p.full_stride;
+  Frag<T> ka[4][kRB];
+#pragma unroll
+  for (int rb = 0; rb < kRB; ++rb) {
+    const T* krow = kbase + static_cast<int64_t>(min(jw + 16 * rb + r16, jlast)) * D + 8 * q4;
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) ka[cc][rb].load(krow + cc * 32);
+  }
+  Frag<T> qb[4];
+  {
+    const T* q = static_cast<const T*>(p.q) + (hq0 + min(r16, G - 1)) * D + 8 * q4;
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) qb[cc].load(q + cc * 32);
+  }
+  // V rows of this lane: 8 dims (dc) of rows rg, rg + 4, ...
+  const int dc = lane & 15, rg = lane >> 4;
+  Frag<T> vf[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) vf[i].load(vbase + static_cast<int64_t>(min(jw + rg + 4 * i, jlast)) * D + dc * 8);
+
+  // ---- scores of the wave's 64 rows: lane (column r16, q4) gets rows 16 rb + 4 q4 + v -----------
+  if (r16 >= G) {
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) qb[cc].zero();
+  }
+  f32x4 sacc[kRB];
+#pragma unroll
+  for (int rb = 0; rb < kRB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], ka[cc][rb], qb[cc]);
+
+  // ---- softmax over the wave's rows, per column ---------------------------------------------------
+  float m_w = -INFINITY;
+#pragma unroll
+  for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int r = 16 * rb + 4 * q4 + v;
+      const float sv = (r < nw && r16 < G && jw + r <= jvis) ? sacc[rb][v] * p.scale : -INFINITY;
+      sacc[rb][v] = sv;
+      m_w = fmaxf(m_w, sv);
+    }
+  m_w = cross_row_max(m_w);
+  const float m_ref = (m_w == -INFINITY) ? 0.0f : m_w;
+  float l_w = 0.0f;
+#pragma unroll
+  for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float e = __expf(sacc[rb][v] - m_ref);   // masked rows hold -inf -> 0
+      l_w += e;
+      if (r16 < kH) pw[(16 * rb + 4 * q4 + v) * kH + r16] = e;
+    }
+  l_w = cross_row_sum(l_w);
+  if (lane < kH) {
+    wm[wave * kH + lane] = m_w;
+    wl[wave * kH + lane] = l_w;
+  }
+  // the probabilities were written by this wave and are read by this wave: no barrier, the LDS
+  // operations of a wave complete in order
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  // ---- sum_j p_j V[j,:] over this lane's rows ---------------------------------------------------
+  float acc[kH][8];
+#pragma unroll
+  for (int h = 0; h < kH; ++h)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int r = rg + 4 * i;
+    const f32x4 p4 = *reinterpret_cast<const f32x4*>(pw + r * kH);   // rows past the end hold zeros
+    float x[8];
+    unpack8(vf[i], x);
+#pragma unroll
+    for (int h = 0; h < kH; ++h)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[h][e] += p4[h] * x[e];
+  }
+  // the four row groups of the wave meet in its first 16 lanes
+#pragma unroll
+  for (int h = 0; h < kH; ++h)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[h][e] = cross_row_sum(acc[h][e]);
+  if (rg == 0) {
+#pragma unroll
+    for (int h = 0; h < kH; ++h) {
+      float* dst = red + (wave * kH + h) * D + dc * 8;
+      *reinterpret_cast<f32x4*>(dst) = f32x4{acc[h][0], acc[h][1], acc[h][2], acc[h][3]};
+      *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[h][4], acc[h][5], acc[h][6], acc[h][7]};
+    }
+  }
+  __syncthreads();
+
+  // ---- the waves meet: record of column h = [max, sum, -, -, acc[128]] ---------------------------
+  if (tid < kH * (D / 4)) {
+    const int h = tid / (D / 4), d4 = tid % (D / 4);
+    if (h < G) {
+      float ms = wm[h];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) ms = fmaxf(ms, wm[w * kH + h]);
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      float l = 0.0f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float mw = wm[w * kH + h];
+        const float f = (mw == -INFINITY) ? 0.0f : __expf(mw - ms);
+        l += f * wl[w * kH + h];
+        v += f * *reinterpret_cast<const f32x4*>(red + (w * kH + h) * D + 4 * d4);
+      }
+      float* rec = p.part_w + ((hq0 + h) * p.Sw + s) * p.recw;
+      *reinterpret_cast<f32x4*>(rec + 4 + 4 * d4) = v;
+      if (d4 == 0) {
+        rec[0] = ms;
+        rec[1] = l;
+      }
+    }
+  }
+}
+
 template <int CW, int DVT, int GP>
 __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsigned char* smem) {
   using T = bf16_t;
@@ -1658,14 +1812,476 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsig
 template <int CW, int DVT, int GP>
 __global__ __launch_bounds__(kBlock, CW <= 2 ? 2 : 1) void decode_partial_fast(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  if (static_cast<int>(blockIdx.x) < p.Sm) partial_middle_fast<CW, DVT, GP>(p, smem);
+  if (static_cast<int>(blockIdx.x) < p.Smw) partial_middle_fast<CW, DVT, GP>(p, smem);
+  else if (p.D == 128) partial_full_fast<bf16_t>(p, smem);
   else partial_full_rows<bf16_t>(p, smem);
+}
+
+// ---------------------------------------------------------------------------
+// 2d. middle rows, specialised, eight waves: the long series (up to 512 slots) at two waves per SIMD
+// ---------------------------------------------------------------------------
+// With 512 series slots the table slices of a four-wave workgroup fill its registers (one wave
+// per SIMD, nothing to overlap a wait with).  Here eight waves split the harmonics (CW chunks of
+// 32 slots each: CW = 2 for 512 slots), so a wave's slices take 64 registers and two waves share
+// a SIMD.  A step is still four tiles of 64 rows; of its kept operands a wave takes two row blocks
+// of K^mu and one token block of V^mu (tile wave / 2); of the softmax it owns two score columns,
+// two rows per lane.  The score exchange is padded so that the eight-byte reads of the owners
+// fall in distinct LDS banks.
+constexpr int kWaves8 = 8;
+constexpr int kBlock8 = 64 * kWaves8;
+constexpr int kXs8Q4 = 18;                    // f32x4 cells per (row block, lane / 16): 16 columns + 2 pad cells
+constexpr int kXs8Rb = 4 * kXs8Q4;            // per row block
+constexpr int kXs8Wave = kRB * kXs8Rb;        // per wave
+constexpr unsigned kXs8Bytes = kWaves8 * kXs8Wave * 16;
+
+template <int CW, int DVT, int GP>
+__device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsigned char* smem) {
+  using T = bf16_t;
+  using ES = f16_t;
+  constexpr int Mint = kWaves8 * CW * 32;
+  constexpr int KT = 4, step = KT * kTJ;
+  static_assert(GP == 1 || GP == 4, "score columns per tile");
+  static_assert(DVT == 1 || DVT == 2, "kept V column tiles");
+
+  const int sm_idx = blockIdx.x, bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int G = p.G;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q4 = lane >> 4, r16 = lane & 15;
+  const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
+  // the workgroup walks p.cpw consecutive chunks of its head (one record each): its rows are
+  // [w0, w1), its steps are counted through all of them, a chunk ends every spc steps
+  const int w0 = sm_idx * p.cpw * p.chunk_m, w1 = min(p.N, w0 + p.cpw * p.chunk_m);
+  const int total = (w1 - w0 + step - 1) / step;
+  const int spc = p.chunk_m / step;
+  const int c1 = w1;                                  // rows at or past it are masked (only the last step can hold any)
+  const int col_k = r16 / GP, col_h = r16 % GP;
+  const bool col_live = col_k < KT && col_h < G;
+  const int hsafe = min(col_h, G - 1);
+  const int kpitch = (p.Dku + 7) & ~7;
+  constexpr int Dkq = 32;
+  const int Dvu = p.Dvu;
+  const T* kk = static_cast<const T*>(p.k_keep) + bh * p.kk_stride;
+  const T* vk = static_cast<const T*>(p.v_keep) + bh * p.vk_stride;
+  const int Nm1 = p.N - 1;
+  const int my_tile = wave >> 1, my_half = wave & 1;   // kept operands: tile, and which half of it
+
+  // ---- LDS carve-up ----------------------------------------------------------------------------
+  f32x4* xs = reinterpret_cast<f32x4*>(smem);                   // [8 waves][4 rb][4][18] partial scores
+  ES* pse = reinterpret_cast<ES*>(smem + kXs8Bytes);
+  T* pte = reinterpret_cast<T*>(smem + kXs8Bytes + kXN * 16 * 4 * 8 * sizeof(ES));
+  T* ptl = reinterpret_cast<T*>(smem + kXs8Bytes + kXN * 16 * 4 * 8 * (sizeof(ES) + sizeof(T)));
+  float* alpha_s = reinterpret_cast<float*>(smem + kXs8Bytes + kXN * 16 * 4 * 8 * (sizeof(ES) + 2 * sizeof(T)));
+  float* st_m = alpha_s + 16;
+  float* st_l = st_m + 16;
+  float* red_r = reinterpret_cast<float*>(smem);                // after the loop: [16][Mint + 4]
+  constexpr int pr = Mint + 4, po = 16 * DVT + 4;
+  float* red_o = red_r + 16 * pr;                               // [8 waves][16][16 DVT + 4]
+  constexpr int kPitchG = Mint + 32;
+  float* gs_s = reinterpret_cast<float*>(smem + p.lds_tab);
+  T* qk_s = reinterpret_cast<T*>(gs_s + G * kPitchG);
+
+  const int urow_lane = 8 * (r16 >> 2) + (r16 & 3);
+  const uint32_t kcol = static_cast<uint32_t>(min(8 * q4, kpitch - 8));
+  // this wave's kept operands of the step at `base`: row blocks 2 my_half, 2 my_half + 1 and token block
+  // my_half of tile my_tile
+  auto load_step = [&](Frag<T> (&kf)[2], Frag<T> (&vf)[DVT], int base) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int rb = 2 * my_half + i;
+      const int u = 32 * (rb >> 1) + 4 * (rb & 1) + urow_lane;
+      const int j = min(base + my_tile * kTJ + u, Nm1);
+      kf[i].load(kk + (static_cast<uint32_t>(j) * static_cast<uint32_t>(kpitch) + kcol));
+    }
+    const int tok0 = base + my_tile * kTJ + 32 * my_half + 8 * q4;
+    const uint32_t g8 = static_cast<uint32_t>(min(tok0, Nm1)) >> 3;
+#pragma unroll
+    for (int dt = 0; dt < DVT; ++dt) {
+      const int dim = min(16 * dt + r16, Dvu - 1);
+      vf[dt].load(vk + (g8 * static_cast<uint32_t>(Dvu) + static_cast<uint32_t>(dim)) * 8u);
+    }
+  };
+
+  // ---- (0) everything that comes from global memory is requested first ------------
+  constexpr int kGLoads = (Mint + kBlock8 - 1) / kBlock8;   // G <= 4 heads of Mint floats, as float4
+  const int ng4 = G * Mint / 4;
+  f32x4 gv[kGLoads];
+#pragma unroll
+  for (int i = 0; i < kGLoads; ++i)
+    gv[i] = *reinterpret_cast<const f32x4*>(p.gs + hq0 * Mint + 4 * min(tid + i * kBlock8, ng4 - 1));
+  // this lane's share of the softmax: column ocol, rows 32 x + 8 oq4 + 4 y + 2 ohalf + {0, 1} (orb = 2 x + y)
+  const int ocol = 2 * wave + (lane & 1), ohalf = (lane >> 1) & 1, oq4 = (lane >> 2) & 3, orb = lane >> 4;
+  const int ocol_k = ocol / GP, ocol_h = ocol % GP;
+  const bool olive = ocol_k < KT && ocol_h < G;
+  const float g0 = p.g0[hq0 + min(ocol_h, G - 1)];
+  Frag<T> qv;
+  qv.load(static_cast<const T*>(p.qkeep) + hq0 * Dkq + 8 * min(tid, G * 4 - 1));
+  Frag<T> kfA[2], kfB[2];
+  Frag<T> vfA[DVT], vfB[DVT];
+  load_step(kfA, vfA, w0);
+  load_step(kfB, vfB, w0 + min(1, total - 1) * step);
+
+  // ---- this wave's slices of the E table, evaluated in registers -----------------------------
+  Frag<ES> eA[CW][kRB], eB[CW][2][kXN];
+  float tc[CW], ts[CW];
+  {
+    const int n_max = p.M / 2;
+    const float invT = 1.0f / static_cast<float>(p.T);
+    float cd[kRB], sd[kRB];
+    int urow[kRB];
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) {
+      urow[rb] = 32 * (rb >> 1) + 4 * (rb & 1) + urow_lane;
+      table_cs<T>(1, urow[rb], p.T, invT, &cd[rb], &sd[rb]);
+    }
+#pragma unroll
+    for (int i = 0; i < CW; ++i) {
+      const int n0 = 16 * (wave * CW + i) + 4 * q4 + 1;
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb) {
+        float vals[8];
+        table_cs<T>(n0, urow[rb], p.T, invT, &vals[0], &vals[1]);
+#pragma unroll
+        for (int hp = 1; hp < 4; ++hp) {
+          vals[2 * hp] = vals[2 * hp - 2] * cd[rb] - vals[2 * hp - 1] * sd[rb];
+          vals[2 * hp + 1] = vals[2 * hp - 1] * cd[rb] + vals[2 * hp - 2] * sd[rb];
+        }
+#pragma unroll
+        for (int hp = 0; hp < 4; ++hp)
+          if (n0 + hp > n_max) vals[2 * hp] = vals[2 * hp + 1] = 0.0f;
+        pack8(eA[i][rb], vals);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < CW; ++i) {
+      const int n = 16 * (wave * CW + i) + r16 + 1;
+      float cn, sn;
+      table_cs<T>(n, 1, p.T, invT, &cn, &sn);
+#pragma unroll
+      for (int x = 0; x < kXN; ++x) {
+        float cs[8], ss[8];
+        table_cs<T>(n, 32 * x + 8 * q4, p.T, invT, &cs[0], &ss[0]);
+#pragma unroll
+        for (int e = 1; e < 8; ++e) {
+          cs[e] = cs[e - 1] * cn - ss[e - 1] * sn;
+          ss[e] = ss[e - 1] * cn + cs[e - 1] * sn;
+        }
+        if (n > n_max) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) cs[e] = ss[e] = 0.0f;
+        }
+        pack8(eB[i][0][x], cs);
+        pack8(eB[i][1][x], ss);
+      }
+    }
+    const uint32_t ph_step = phase_of(step, p.ph_scale);
+#pragma unroll
+    for (int i = 0; i < CW; ++i)
+      phase_cs<T>(static_cast<uint32_t>(16 * (wave * CW + i) + r16 + 1) * ph_step, &tc[i], &ts[i]);
+  }
+
+  // ---- series coefficients and packed query into LDS ---------------------------------------------
+#pragma unroll
+  for (int i = 0; i < kGLoads; ++i) {
+    const int v4 = tid + i * kBlock8;
+    if (v4 < ng4) *reinterpret_cast<f32x4*>(gs_s + (4 * v4 / Mint) * kPitchG + (4 * v4) % Mint) = gv[i];
+  }
+  if (tid < G * 4) *reinterpret_cast<Frag<T>*>(qk_s + 8 * tid) = qv;
+  __syncthreads();
+  Frag<T> bq;
+  bq.load(qk_s + hsafe * Dkq + 8 * q4);
+  if (col_k != my_tile || !col_live) bq.zero();
+
+  f32x4 racc[2 * CW];
+  f32x4 oacc[DVT];
+  float m_run, l_run;
+  auto reset_chunk = [&]() {
+#pragma unroll
+    for (int t = 0; t < 2 * CW; ++t) racc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < DVT; ++t) oacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    m_run = -INFINITY;
+    l_run = 0.0f;
+  };
+  reset_chunk();
+
+  auto do_step = [&](Frag<T> (&kf)[2], Frag<T> (&vf)[DVT], int base, auto tail_tag) {
+    constexpr bool kTail = decltype(tail_tag)::value;
+    f32x4 sacc[kRB];
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // -- (a) series on the K side, own orders -----------------------------------------
+    const uint32_t ph_k = phase_of(p.t0 + base + col_k * kTJ, p.ph_scale);
+#pragma unroll
+    for (int i = 0; i < CW; ++i) {
+      const uint32_t n0 = 16 * (wave * CW + i) + 4 * q4 + 1;
+      float csv[4], snv[4];
+      if constexpr (GP >= 4) {
+        float cs, sn;
+        phase_cs<T>((n0 + (lane & 3)) * ph_k, &cs, &sn);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          csv[j] = quad_bcast(cs, j);
+          snv[j] = quad_bcast(sn, j);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) phase_cs<T>((n0 + j) * ph_k, &csv[j], &snv[j]);
+      }
+      const float* gl = gs_s + hsafe * kPitchG + 32 * (wave * CW + i) + 8 * q4;
+      const f32x4 ga = *reinterpret_cast<const f32x4*>(gl), gb = *reinterpret_cast<const f32x4*>(gl + 4);
+      float gp[8];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float gc = (j < 2) ? ga[2 * (j & 1)] : gb[2 * (j & 1)];
+        const float gsn = (j < 2) ? ga[2 * (j & 1) + 1] : gb[2 * (j & 1) + 1];
+        gp[2 * j] = gc * csv[j] + gsn * snv[j];
+        gp[2 * j + 1] = gsn * csv[j] - gc * snv[j];
+      }
+      Frag<ES> bg;
+      pack8(bg, gp);
+      if (!col_live) bg.zero();
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], eA[i][rb], bg);
+    }
+    // -- (b) kept K dims: two row blocks of tile my_tile --------------------------------------------
+    if (my_half == 0) {
+      mma_k32(sacc[0], kf[0], bq);
+      mma_k32(sacc[1], kf[1], bq);
+    } else {
+      mma_k32(sacc[2], kf[0], bq);
+      mma_k32(sacc[3], kf[1], bq);
+    }
+
+    // -- (c) the partial scores of the eight waves meet; this wave sums its two columns --------
+    {
+      f32x4* xw = xs + wave * kXs8Wave + q4 * kXs8Q4 + r16;
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb) xw[rb * kXs8Rb] = sacc[rb];
+    }
+    __syncthreads();
+    f32x2 sv;
+    {
+      const f32x2* xr = reinterpret_cast<const f32x2*>(xs + orb * kXs8Rb + oq4 * kXs8Q4 + ocol) + ohalf;
+      f32x2 a0 = xr[0 * 2 * kXs8Wave] + xr[1 * 2 * kXs8Wave], a1 = xr[2 * 2 * kXs8Wave] + xr[3 * 2 * kXs8Wave];
+      f32x2 a2 = xr[4 * 2 * kXs8Wave] + xr[5 * 2 * kXs8Wave], a3 = xr[6 * 2 * kXs8Wave] + xr[7 * 2 * kXs8Wave];
+      sv = (a0 + a1) + (a2 + a3);
+    }
+    // -- (d) online softmax of the own columns -----------------------------------------------------
+    float pv[2];
+    float m_tile = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+      float sc = (sv[v] + g0) * p.scale;
+      if constexpr (kTail) {
+        const int u = 32 * (orb >> 1) + 8 * oq4 + 4 * (orb & 1) + 2 * ohalf + v;
+        if (base + ocol_k * kTJ + u >= c1) sc = -INFINITY;
+      }
+      if (!olive) sc = -INFINITY;
+      pv[v] = sc;
+      m_tile = fmaxf(m_tile, sc);
+    }
+    m_tile = row_stride_max(m_tile, 2);                      // the 32 lanes of a column are 2 apart
+    m_tile = cross_row_max(m_tile);
+    const float m_new = fmaxf(m_run, m_tile);
+    const float m_ref = (m_new == -INFINITY) ? 0.0f : m_new;
+    const float alpha = __expf(m_run - m_ref);
+    pv[0] = __expf(pv[0] - m_ref);
+    pv[1] = __expf(pv[1] - m_ref);
+    l_run = l_run * alpha + (pv[0] + pv[1]);
+    m_run = m_new;
+    {
+      const int slot = (((orb >> 1) * 16 + ocol) * 4 + oq4) * 8 + 4 * (orb & 1) + 2 * ohalf;
+      uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[0], pv[1]}, f16x2));
+      *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(pse) + slot) = w;
+      w = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[0], pv[1]}, bf16x2));
+      *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(pte) + slot) = w;
+      const float lo0 = pv[0] - __builtin_bit_cast(float, (w & 0xffffu) << 16);
+      const float lo1 = pv[1] - __builtin_bit_cast(float, w & 0xffff0000u);
+      w = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo0, lo1}, bf16x2));
+      *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(ptl) + slot) = w;
+      if (lane < 2) alpha_s[ocol] = alpha;
+    }
+    __syncthreads();
+    // -- (e) bring the accumulators into this step's frame ------------------------------------------
+    {
+      const f32x4 al = *reinterpret_cast<const f32x4*>(alpha_s + 4 * q4);
+#pragma unroll
+      for (int t = 0; t < DVT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) oacc[t][v] *= al[v];
+#pragma unroll
+      for (int i = 0; i < CW; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float rc = racc[2 * i][v], rs = racc[2 * i + 1][v];
+          racc[2 * i][v] = al[v] * (tc[i] * rc + ts[i] * rs);
+          racc[2 * i + 1][v] = al[v] * (tc[i] * rs - ts[i] * rc);
+        }
+    }
+    // -- (f) V side, own orders: r' += P^T E ----------------------------------------------------------
+#pragma unroll
+    for (int x = 0; x < kXN; ++x) {
+      Frag<ES> ps;
+      ps.load(pse + ((x * 16 + r16) * 4 + q4) * 8);
+#pragma unroll
+      for (int i = 0; i < CW; ++i) {
+        mma_k32(racc[2 * i], ps, eB[i][0][x]);
+        mma_k32(racc[2 * i + 1], ps, eB[i][1][x]);
+      }
+    }
+    // -- (g) kept V dims: token block my_half of tile my_tile -----------------------------------------
+    {
+      Frag<T> pt, pl;
+      pt.load(pte + ((my_half * 16 + r16) * 4 + q4) * 8);
+      pl.load(ptl + ((my_half * 16 + r16) * 4 + q4) * 8);
+      if (col_k != my_tile) {
+        pt.zero();
+        pl.zero();
+      }
+#pragma unroll
+      for (int dt = 0; dt < DVT; ++dt) {
+        Frag<T> bv = vf[dt];
+        if (16 * dt + r16 >= Dvu) bv.zero();
+        if constexpr (kTail) {
+          const int tok0 = base + my_tile * kTJ + 32 * my_half + 8 * q4;
+          if (tok0 + 8 > c1) mask_tail(bv, c1 - tok0);
+        }
+        mma_k32(oacc[dt], pt, bv);
+        mma_k32(oacc[dt], pl, bv);
+      }
+    }
+  };
+
+  // record `chunk` of the head from the accumulators: its last step started at last_base
+  auto finish_chunk = [&](int chunk, int last_base, bool more) {
+    // ---- merge the tiles of a head --------------------------------------------------------------
+    float l_tot = row_stride_sum(l_run, 2);
+    l_tot = cross_row_sum(l_tot);
+    if (lane < 2) {
+      st_m[ocol] = m_run;
+      st_l[ocol] = l_tot;
+    }
+    __syncthreads();
+    const float mc = col_live ? st_m[r16] : -INFINITY;
+    const float lcol = st_l[r16];
+    const float mstar = row_stride_max(mc, GP);
+    const float fc = (mc != -INFINITY) ? __expf(mc - mstar) : 0.0f;
+    const float lstar = row_stride_sum(col_live ? lcol * fc : 0.0f, GP);
+    __syncthreads();
+
+    {
+      float f[4];
+      uint32_t phr[4];
+  #pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int row = 4 * q4 + v;
+        f[v] = __shfl(fc, row, kWave);
+        phr[v] = phase_of(p.t0 + last_base + (row / GP) * kTJ, p.ph_scale);
+      }
+  #pragma unroll
+      for (int i = 0; i < CW; ++i) {
+        const int c = wave * CW + i;
+        const uint32_t n = 16 * c + r16 + 1;
+        float cs[4], sn[4];
+        phase_cs<T>(n * phr[0], &cs[0], &sn[0]);
+        if constexpr (GP >= 4) {
+  #pragma unroll
+          for (int v = 1; v < 4; ++v) {
+            cs[v] = cs[0];
+            sn[v] = sn[0];
+          }
+        } else {
+  #pragma unroll
+          for (int v = 1; v < 4; ++v) phase_cs<T>(n * phr[v], &cs[v], &sn[v]);
+        }
+  #pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float rc = racc[2 * i][v], rs = racc[2 * i + 1][v];
+          float* dst = red_r + (4 * q4 + v) * pr + 32 * c + r16;
+          dst[0] = f[v] * (cs[v] * rc - sn[v] * rs);
+          dst[16] = f[v] * (sn[v] * rc + cs[v] * rs);
+        }
+      }
+      float* ro = red_o + wave * 16 * po;
+  #pragma unroll
+      for (int dt = 0; dt < DVT; ++dt)
+  #pragma unroll
+        for (int v = 0; v < 4; ++v) ro[(4 * q4 + v) * po + 16 * dt + r16] = f[v] * oacc[dt][v];
+    }
+    __syncthreads();
+
+    const size_t rec_h = static_cast<size_t>(p.Sm) * p.recm;
+    float* rec0 = p.part_m + (hq0 * p.Sm + chunk) * p.recm;
+    if (wave == 0 && lane < G) {
+      rec0[lane * rec_h + 0] = mstar;
+      rec0[lane * rec_h + 1] = lstar;
+    }
+    constexpr int no4 = 4 * DVT, nr4 = Mint / 4, per = no4 + nr4;
+    for (int it = tid; it < G * per; it += kBlock8) {
+      const int h = it / per, x4 = it - h * per;
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (x4 < no4) {
+        // kept dims of tile k were accumulated by waves 2 k and 2 k + 1
+  #pragma unroll
+        for (int k = 0; k < KT; ++k) {
+          v += *reinterpret_cast<const f32x4*>(red_o + (((2 * k) * 16 + k * GP + h) * po + 4 * x4));
+          v += *reinterpret_cast<const f32x4*>(red_o + (((2 * k + 1) * 16 + k * GP + h) * po + 4 * x4));
+        }
+      } else {
+        const int y = x4 - no4;
+  #pragma unroll
+        for (int k = 0; k < KT; ++k) v += *reinterpret_cast<const f32x4*>(red_r + ((k * GP + h) * pr + 4 * y));
+      }
+      *reinterpret_cast<f32x4*>(rec0 + h * rec_h + 4 + 4 * x4) = v;
+    }
+
+    if (more) __syncthreads();   // the exchange regions are reused by the next chunk's steps
+  };
+
+  const int wlast = w0 + (total - 1) * step;            // first row of the workgroup's last step
+  const int chunk0 = sm_idx * p.cpw;
+  {
+    int s = 0;
+    for (; s + 2 < total; s += 2) {
+      const int base = w0 + s * step;
+      do_step(kfA, vfA, base, std::false_type{});
+      load_step(kfA, vfA, min(base + 2 * step, wlast));
+      do_step(kfB, vfB, base + step, std::false_type{});
+      load_step(kfB, vfB, min(base + 3 * step, wlast));
+      if ((s + 2) % spc == 0) {                         // (spc is even whenever a workgroup has several chunks)
+        finish_chunk(chunk0 + (s + 1) / spc, base + step, true);
+        reset_chunk();
+      }
+    }
+    const int base = w0 + s * step;
+    if (total - s == 2) {
+      do_step(kfA, vfA, base, std::false_type{});
+      do_step(kfB, vfB, base + step, std::true_type{});
+    } else {
+      do_step(kfA, vfA, base, std::true_type{});
+    }
+    finish_chunk(chunk0 + (total - 1) / spc, wlast, false);
+  }
+}
+
+template <int CW, int DVT, int GP>
+__global__ __launch_bounds__(kBlock8, 1) void decode_partial_fast8(DecodeParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  if (static_cast<int>(blockIdx.x) < p.Smw) {
+    partial_middle_fast8<CW, DVT, GP>(p, smem);
+  } else {
+    if (threadIdx.x >= kBlock) return;   // the full-row path is written for four waves; the others leave before any barrier
+    if (p.D == 128) partial_full_fast<bf16_t>(p, smem);
+    else partial_full_rows<bf16_t>(p, smem);
+  }
 }
 
 template <typename T, int CW, int DVTM, bool KC1>
 __global__ __launch_bounds__(kBlock, (CW <= 2 && sizeof(T) == 2) ? 2 : 1) void decode_partial(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  if (static_cast<int>(blockIdx.x) < p.Sm) partial_middle_rows<T, CW, DVTM, KC1>(p, smem);
+  if (static_cast<int>(blockIdx.x) < p.Smw) partial_middle_rows<T, CW, DVTM, KC1>(p, smem);
   else partial_full_rows<T>(p, smem);
 }
 
@@ -2189,6 +2805,8 @@ __global__ __launch_bounds__(kFinBlock, kFin2Wide == 16 ? 2 : 4) void decode_fin
 // ---------------------------------------------------------------------------
 struct DecodePlan {
   int Gp, KT, Mint, cw, Sw, Sm, chunk_m, recm, recw;
+  int cpw, Smw;   // middle chunks per workgroup, middle workgroups per (sequence, KV head)
+  int fast;   // 0: general middle-row kernel; 4 / 8: the specialised one with that many waves
   unsigned lds_tab, lds_total;
   size_t off_gs, off_g0, off_qk, off_pm, off_pw, total;
 };
@@ -2247,8 +2865,23 @@ static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, 
   const unsigned Dkq = (((Dku + 7) & ~7) + 31) / 32 * 32;
   pl.recm = 4 + 16 * DVT + pl.Mint;
   pl.recw = 4 + D;
-  const unsigned redb = (16 * (pl.Mint + 4) + kWaves * 16 * (16 * DVT + 4)) * 4;
-  const unsigned tab = redb > kXchgBytes ? redb : kXchgBytes;
+  // the specialised kernels: bf16, groups of at most four query heads, 1 .. 32 kept dims on both sides,
+  // at most 512 series slots (eight waves once the series is that long)
+  pl.fast = 0;
+  if (dtype == FA_BF16 && N > 0 && pl.cw <= 4 && G <= 4 && Dku > 0 && Dku <= 32 && Dvu > 0 && Dvu <= 32)
+    pl.fast = pl.cw == 4 ? 8 : 4;
+  // an eight-wave workgroup takes a whole compute unit: when the caller's split makes more chunks than
+  // units, a workgroup walks several consecutive chunks (tables built once, one record per chunk)
+  pl.cpw = 1;
+  if (pl.fast == 8 && (pl.chunk_m / step) % 2 == 0) {
+    const long chunks = static_cast<long>(B) * Hkv * pl.Sm;
+    if (chunks > 256) pl.cpw = static_cast<int>((chunks + 255) / 256);
+  }
+  pl.Smw = (pl.Sm + pl.cpw - 1) / pl.cpw;
+  const unsigned nwaves = pl.fast == 8 ? kWaves8 : kWaves;
+  const unsigned redb = (16 * (pl.Mint + 4) + nwaves * 16 * (16 * DVT + 4)) * 4;
+  const unsigned xchg = pl.fast == 8 ? kXs8Bytes + 8 * 1024 : kXchgBytes;
+  const unsigned tab = redb > xchg ? redb : xchg;
   pl.lds_tab = (tab + 255u) & ~255u;
   const unsigned mid = pl.lds_tab + G * (pl.Mint + 32) * 4 + G * Dkq * ts;
   const unsigned wpath = 16 * FA_MAX_HEAD_DIM * ts + kWChunk * kMaxG * 4 + kWaves * 512 * 4 * 4;   // q, p tiles, partial sums
@@ -2291,7 +2924,7 @@ static int launch_partial(const DecodeParams& p, unsigned lds, hipStream_t st, K
       hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                           static_cast<int>(kMaxDynLds)) != hipSuccess)
     return FA_ERR_HIP;
-  dim3 g2(p.Sw + p.Sm, p.B * p.Hkv);
+  dim3 g2(p.Sw + p.Smw, p.B * p.Hkv);
   FA_LAUNCH_TIMED(tm, 1, kern, g2, dim3(kBlock), lds, st, p);
   return FA_OK;
 }
@@ -2324,8 +2957,20 @@ static int launch_partial_fast_one(const DecodeParams& p, unsigned lds, hipStrea
       hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                           static_cast<int>(kMaxDynLds)) != hipSuccess)
     return FA_ERR_HIP;
-  dim3 g2(p.Sw + p.Sm, p.B * p.Hkv);
+  dim3 g2(p.Sw + p.Smw, p.B * p.Hkv);
   FA_LAUNCH_TIMED(tm, 1, kern, g2, dim3(kBlock), lds, st, p);
+  return FA_OK;
+}
+
+template <int CW, int DVT, int GP>
+static int launch_partial_fast8_one(const DecodeParams& p, unsigned lds, hipStream_t st, KernelTimers* tm) {
+  auto kern = decode_partial_fast8<CW, DVT, GP>;
+  if (lds > 48u * 1024u &&
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          static_cast<int>(kMaxDynLds)) != hipSuccess)
+    return FA_ERR_HIP;
+  dim3 g2(p.Sw + p.Smw, p.B * p.Hkv);
+  FA_LAUNCH_TIMED(tm, 1, kern, g2, dim3(kBlock8), lds, st, p);
   return FA_OK;
 }
 
@@ -2339,9 +2984,14 @@ static int launch_partial_fast(const DecodeParams& p, const DecodePlan& pl, hipS
   switch (pl.cw) {
     case 1: FA_FAST(1);
     case 2: FA_FAST(2);
-    default: FA_FAST(4);
+    default: break;
   }
 #undef FA_FAST
+  // 512 slots: eight waves, two chunks each
+  return one_tile ? (one_head ? launch_partial_fast8_one<2, 1, 1>(p, pl.lds_total, st, tm)
+                              : launch_partial_fast8_one<2, 1, 4>(p, pl.lds_total, st, tm))
+                  : (one_head ? launch_partial_fast8_one<2, 2, 1>(p, pl.lds_total, st, tm)
+                              : launch_partial_fast8_one<2, 2, 4>(p, pl.lds_total, st, tm));
 }
 
 // tm (optional): per-kernel event pairs, for fa_decode_timed
@@ -2367,7 +3017,7 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
   int rc;
   if constexpr (sizeof(T) == 2) {
     // the specialised kernel: groups of at most four query heads, 1 .. 32 kept dims on both sides
-    if (p.Sm > 0 && pl.cw <= 4 && p.G <= 4 && p.Dku > 0 && p.Dku <= 32 && p.Dvu > 0 && p.Dvu <= 32) {
+    if (pl.fast != 0) {
       rc = launch_partial_fast(p, pl, st, tm);
       if (rc != FA_OK) return rc;
       return launch_finish<T>(p, st, tm, prior);
@@ -2476,6 +3126,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   p.M = M; p.T = T; p.t0 = t0; p.N = N; p.W = W;
   p.Gp = pl.Gp; p.KT = pl.KT; p.Mint = pl.Mint;
   p.Sw = pl.Sw; p.Sm = pl.Sm; p.chunk_m = pl.chunk_m; p.recm = pl.recm; p.recw = pl.recw;
+  p.cpw = pl.cpw; p.Smw = pl.Smw;
   p.lds_tab = pl.lds_tab;
   p.scale = scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(D));
   p.ph_scale = 4294967296.0 / static_cast<double>(T);
