@@ -124,8 +124,12 @@ def measure(cfg, steps, warmup, extras=False):
     n_sets = int(min(16, max(2, math.ceil(2.0 * LLC_BYTES / dec_bytes))))
     # what each kernel of the decode call has to move (the split-K records between them are overhead)
     bh = B * Hkv
-    kb = {"prepare": bh * M * cfg.Dkc * 4 + B * Hq * D * e + bh * D,
-          "partial": bh * N * (Dku + Dvu) * e + bh * W * D * 2 * e + B * Hq * D * e,
+    # (with more than 256 series slots the full-width sink / window rows are processed in the launch that
+    # forms the series coefficients, otherwise in the launch of the middle rows)
+    full_rows = bh * W * D * 2 * e
+    early = M > 257
+    kb = {"prepare": bh * M * cfg.Dkc * 4 + B * Hq * D * e + bh * D + (full_rows if early else 0),
+          "partial": bh * N * (Dku + Dvu) * e + B * Hq * D * e + (0 if early else full_rows),
           "finish": bh * M * cfg.Dvc * 4 + bh * D + B * Hq * D * 4}
 
     master = {k: dev(ctx[k]) for k in ("q", "k_mid", "v_mid", "k_full", "v_full", "kmask", "vmask")}
@@ -190,7 +194,8 @@ def measure(cfg, steps, warmup, extras=False):
                                      **hbm(kb[n], float(kd[i])), "traffic": traffic.get("decode_" + n)}
     dom = "decode_" + names[int(np.argmax(kd))]
     call_traffic = [traffic.get("decode_" + n) for n in names]
-    roof_dec = {"kernel": "fa_decode call = decode_prepare + decode_partial + decode_finish",
+    roof_dec = {"kernel": "fa_decode call = decode_prepare (series coefficients) + decode_partial (middle rows; "
+                          "full-width rows in either) + decode_finish",
                 "bound": "hbm", **hbm(dec_bytes, t_kernels), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "algorithmic_bytes": dec_bytes, "kernels_ms": round(t_kernels * 1e3, 5),
                 "traffic": (sum(call_traffic) if all(v is not None for v in call_traffic) else None),

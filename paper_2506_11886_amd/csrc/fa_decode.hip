@@ -77,6 +77,8 @@ struct DecodeParams {
   int Mint;         // series length: 2 * (M/2) padded to a compiled size
   int Sw, Sm;       // chunks of full-width rows / of middle rows (middle chunks come first)
   int cpw, Smw;     // middle chunks per workgroup and middle workgroups per (sequence, KV head): Sm unless cpw > 1
+  int nprep, Swp;   // workgroups per head of the series-coefficient part when the full-width rows share its launch;
+                    // chunks of full-width rows inside the middle-row launch (0 when they ran with the coefficients)
   int chunk_m;      // middle rows per chunk (multiple of the workgroup step)
   int recm, recw;   // floats per partial record: 4 + 16 ceil(Dvu/16) + Mint (middle), 4 + D (full rows)
   unsigned lds_tab; // bytes of the exchange / reduction region of a middle-row workgroup
@@ -352,7 +354,7 @@ __global__ __launch_bounds__(kBlock) void decode_prepare(DecodeParams p) {
 // registers, and the TPR shares meet by lane rotation.  256 / TPR rows per workgroup: 64 when
 // the (sequence, head) pairs alone fill the chip, 16 when there are few of them.
 template <typename T, int TPR>
-__global__ __launch_bounds__(kBlock) void decode_prepare2(DecodeParams p) {
+__device__ __forceinline__ void prepare2_rows(const DecodeParams& p) {
   constexpr int kRows = kBlock / TPR;
   constexpr int kV4 = (FA_MAX_HEAD_DIM / 4 + TPR - 1) / TPR;
   __shared__ __attribute__((aligned(16))) float qc[kMaxG * FA_MAX_HEAD_DIM];   // [G][Dkc] query at the compressed dims
@@ -430,6 +432,11 @@ __global__ __launch_bounds__(kBlock) void decode_prepare2(DecodeParams p) {
   }
 }
 
+template <typename T, int TPR>
+__global__ __launch_bounds__(kBlock) void decode_prepare2(DecodeParams p) {
+  prepare2_rows<T, TPR>(p);
+}
+
 // ---------------------------------------------------------------------------
 // 2a. full-width sink/window rows: plain single-query attention partial
 // ---------------------------------------------------------------------------
@@ -441,8 +448,8 @@ constexpr int kWRows = 64;      // rows per wave
 constexpr int kWBatch = 8;      // V rows a lane has in flight
 
 template <typename T>
-__device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigned char* smem) {
-  const int s = blockIdx.x - p.Smw, bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
+__device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigned char* smem, int s) {
+  const int bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
   const int G = p.G, D = p.D;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1244,10 +1251,10 @@ __device__ __forceinline__ float cross_row_sum(float v) {
 // B operands - is requested at the start, the softmax of a wave stays inside the wave, and the
 // waves meet once, at the end.
 template <typename T>
-__device__ __forceinline__ void partial_full_fast(const DecodeParams& p, unsigned char* smem) {
+__device__ __forceinline__ void partial_full_fast(const DecodeParams& p, unsigned char* smem, int s) {
   static_assert(sizeof(T) == 2, "16-bit elements");
   constexpr int D = 128, kH = 4;                        // head dim, query columns
-  const int s = blockIdx.x - p.Smw, bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
   const int G = p.G;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1385,6 +1392,26 @@ __device__ __forceinline__ void partial_full_fast(const DecodeParams& p, unsigne
         rec[0] = ms;
         rec[1] = l;
       }
+    }
+  }
+}
+
+// One launch for the two parts of a call that do not depend on each other: the series
+// coefficients g (the first p.nprep workgroups of a row of the grid) and the partial records of
+// the full-width rows (the others).  The first is a chain of round trips that leaves the chip
+// idle, the second is a stream: together they take about as long as the longer of the two.
+template <typename T, int TPR>
+__global__ __launch_bounds__(kBlock) void decode_prepare_window(DecodeParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  if (static_cast<int>(blockIdx.x) < p.nprep) {
+    prepare2_rows<T, TPR>(p);
+  } else {
+    const int s = blockIdx.x - p.nprep;
+    if constexpr (sizeof(T) == 2) {
+      if (p.D == 128 && p.G <= 4) partial_full_fast<T>(p, smem, s);
+      else partial_full_rows<T>(p, smem, s);
+    } else {
+      partial_full_rows<T>(p, smem, s);
     }
   }
 }
@@ -1813,8 +1840,8 @@ template <int CW, int DVT, int GP>
 __global__ __launch_bounds__(kBlock, CW <= 2 ? 2 : 1) void decode_partial_fast(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   if (static_cast<int>(blockIdx.x) < p.Smw) partial_middle_fast<CW, DVT, GP>(p, smem);
-  else if (p.D == 128) partial_full_fast<bf16_t>(p, smem);
-  else partial_full_rows<bf16_t>(p, smem);
+  else if (p.D == 128) partial_full_fast<bf16_t>(p, smem, blockIdx.x - p.Smw);
+  else partial_full_rows<bf16_t>(p, smem, blockIdx.x - p.Smw);
 }
 
 // ---------------------------------------------------------------------------
@@ -2273,8 +2300,8 @@ __global__ __launch_bounds__(kBlock8, 1) void decode_partial_fast8(DecodeParams 
     partial_middle_fast8<CW, DVT, GP>(p, smem);
   } else {
     if (threadIdx.x >= kBlock) return;   // the full-row path is written for four waves; the others leave before any barrier
-    if (p.D == 128) partial_full_fast<bf16_t>(p, smem);
-    else partial_full_rows<bf16_t>(p, smem);
+    if (p.D == 128) partial_full_fast<bf16_t>(p, smem, blockIdx.x - p.Smw);
+    else partial_full_rows<bf16_t>(p, smem, blockIdx.x - p.Smw);
   }
 }
 
@@ -2282,7 +2309,7 @@ template <typename T, int CW, int DVTM, bool KC1>
 __global__ __launch_bounds__(kBlock, (CW <= 2 && sizeof(T) == 2) ? 2 : 1) void decode_partial(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   if (static_cast<int>(blockIdx.x) < p.Smw) partial_middle_rows<T, CW, DVTM, KC1>(p, smem);
-  else partial_full_rows<T>(p, smem);
+  else partial_full_rows<T>(p, smem, blockIdx.x - p.Smw);
 }
 
 // ---------------------------------------------------------------------------
@@ -2806,6 +2833,8 @@ __global__ __launch_bounds__(kFinBlock, kFin2Wide == 16 ? 2 : 4) void decode_fin
 struct DecodePlan {
   int Gp, KT, Mint, cw, Sw, Sm, chunk_m, recm, recw;
   int cpw, Smw;   // middle chunks per workgroup, middle workgroups per (sequence, KV head)
+  int Swp;        // chunks of full-width rows that run inside the middle-row launch
+  unsigned lds_window;   // dynamic LDS of a full-width-row workgroup
   int fast;   // 0: general middle-row kernel; 4 / 8: the specialised one with that many waves
   unsigned lds_tab, lds_total;
   size_t off_gs, off_g0, off_qk, off_pm, off_pw, total;
@@ -2885,6 +2914,15 @@ static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, 
   pl.lds_tab = (tab + 255u) & ~255u;
   const unsigned mid = pl.lds_tab + G * (pl.Mint + 32) * 4 + G * Dkq * ts;
   const unsigned wpath = 16 * FA_MAX_HEAD_DIM * ts + kWChunk * kMaxG * 4 + kWaves * 512 * 4 * 4;   // q, p tiles, partial sums
+  // the specialised full-row path keeps only probabilities, per-wave sums and statistics there
+  const bool wfast = dtype == FA_BF16 && D == 128 && G <= 4;
+  pl.lds_window = wfast ? (kWaves * kWRows * 4 + kWaves * 4 * 128 + 64) * 4 : wpath;
+  // The eight-wave middle-row workgroups take a compute unit each, so full-width-row workgroups in their
+  // launch would run as a tail behind them: they run in the launch that forms the series coefficients
+  // instead (independent work that fills the chip while that chain of round trips is in flight).  With
+  // two middle-row workgroups per unit the full-width rows overlap with them and stay where they are
+  // (measured: moving them costs 1.5 us on 32 K tokens, 12 us on 8 x 4 K MHA).
+  pl.Swp = (pl.fast == 8 && Dkc > 0 && (Dkc & 3) == 0) ? 0 : pl.Sw;
   const unsigned t = mid > wpath ? mid : wpath;
   pl.lds_total = (t + 255u) & ~255u;
   if (pl.lds_total > kMaxDynLds) return false;
@@ -2924,7 +2962,7 @@ static int launch_partial(const DecodeParams& p, unsigned lds, hipStream_t st, K
       hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                           static_cast<int>(kMaxDynLds)) != hipSuccess)
     return FA_ERR_HIP;
-  dim3 g2(p.Sw + p.Smw, p.B * p.Hkv);
+  dim3 g2(p.Swp + p.Smw, p.B * p.Hkv);
   FA_LAUNCH_TIMED(tm, 1, kern, g2, dim3(kBlock), lds, st, p);
   return FA_OK;
 }
@@ -2957,7 +2995,7 @@ static int launch_partial_fast_one(const DecodeParams& p, unsigned lds, hipStrea
       hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                           static_cast<int>(kMaxDynLds)) != hipSuccess)
     return FA_ERR_HIP;
-  dim3 g2(p.Sw + p.Smw, p.B * p.Hkv);
+  dim3 g2(p.Swp + p.Smw, p.B * p.Hkv);
   FA_LAUNCH_TIMED(tm, 1, kern, g2, dim3(kBlock), lds, st, p);
   return FA_OK;
 }
@@ -2969,7 +3007,7 @@ static int launch_partial_fast8_one(const DecodeParams& p, unsigned lds, hipStre
       hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                           static_cast<int>(kMaxDynLds)) != hipSuccess)
     return FA_ERR_HIP;
-  dim3 g2(p.Sw + p.Smw, p.B * p.Hkv);
+  dim3 g2(p.Swp + p.Smw, p.B * p.Hkv);
   FA_LAUNCH_TIMED(tm, 1, kern, g2, dim3(kBlock8), lds, st, p);
   return FA_OK;
 }
@@ -3000,10 +3038,23 @@ static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_
   const int BH = p.B * p.Hkv;
   const hipError_t prior = hipPeekAtLastError();
   if (p.Sm > 0 && p.Dkc > 0 && (p.Dkc & 3) == 0) {
-    if (static_cast<long>(BH) * (p.Mint / 64 + 1) >= 256) {
-      FA_LAUNCH_TIMED(tm, 0, (decode_prepare2<T, 4>), dim3(p.Mint / 64 + 1, BH), dim3(kBlock), 0, st, p);
+    const bool wide = static_cast<long>(BH) * (p.Mint / 64 + 1) >= 256;
+    const int nprep = wide ? p.Mint / 64 + 1 : p.Mint / 16 + 1;
+    if (p.Sw > 0 && p.Swp == 0) {   // the full-width rows ride along
+      DecodeParams pp = p;
+      pp.nprep = nprep;
+      const unsigned lds = pl.lds_window;
+      auto kern = wide ? decode_prepare_window<T, 4> : decode_prepare_window<T, 16>;
+      // (the kernel also holds 16 KB of static LDS: the ceiling asked for is what this launch needs)
+      if (lds > 32u * 1024u &&
+          hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              static_cast<int>(lds)) != hipSuccess)
+        return FA_ERR_HIP;
+      FA_LAUNCH_TIMED(tm, 0, kern, dim3(nprep + p.Sw, BH), dim3(kBlock), lds, st, pp);
+    } else if (wide) {
+      FA_LAUNCH_TIMED(tm, 0, (decode_prepare2<T, 4>), dim3(nprep, BH), dim3(kBlock), 0, st, p);
     } else {
-      FA_LAUNCH_TIMED(tm, 0, (decode_prepare2<T, 16>), dim3(p.Mint / 16 + 1, BH), dim3(kBlock), 0, st, p);
+      FA_LAUNCH_TIMED(tm, 0, (decode_prepare2<T, 16>), dim3(nprep, BH), dim3(kBlock), 0, st, p);
     }
   } else if (p.Sm > 0) {
     if (static_cast<long>(BH) * ((p.Mint + 32) / 32) >= 512) {
@@ -3126,7 +3177,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   p.M = M; p.T = T; p.t0 = t0; p.N = N; p.W = W;
   p.Gp = pl.Gp; p.KT = pl.KT; p.Mint = pl.Mint;
   p.Sw = pl.Sw; p.Sm = pl.Sm; p.chunk_m = pl.chunk_m; p.recm = pl.recm; p.recw = pl.recw;
-  p.cpw = pl.cpw; p.Smw = pl.Smw;
+  p.cpw = pl.cpw; p.Smw = pl.Smw; p.Swp = pl.Swp; p.nprep = 0;
   p.lds_tab = pl.lds_tab;
   p.scale = scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(D));
   p.ph_scale = 4294967296.0 / static_cast<double>(T);
