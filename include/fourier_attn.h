@@ -220,11 +220,14 @@ int fa_append(const void* k_new, const void* v_new, int dtype,
  * Equivalent to
  *   fa_compress(k, ..., kmask, Dkc, ..., ck, k_keep, FA_KEEP_ROWS, kk_stride_bh, keep_offset, ...)
  *   fa_compress(v, ..., vmask, Dvc, ..., cv, v_keep, FA_KEEP_TOK8, vk_stride_bh, keep_offset, ...)
- * (the layouts fa_decode reads), with identical results; k and v share dtype,
- * shape [B,H,N,D] and strides.  When both sides qualify for the specialised
- * projection kernel (bf16, D = 128, at most 32 kept dims each, keep_offset a
- * multiple of 8) the two projections run as ONE launch and the two chunk
- * reductions as one: two kernel launches per call instead of four.
+ * (the layouts fa_decode reads); k and v share dtype, shape [B,H,N,D] and
+ * strides.  When both sides qualify for the specialised projection kernel
+ * (bf16, D = 128, at most 32 kept dims each, keep_offset a multiple of 8) the
+ * two projections run as ONE launch and the two chunk reductions as one: two
+ * kernel launches per call instead of four, and each tensor is cut into half
+ * as many token chunks, so that the pair is one round of workgroups.  Kept
+ * dims are identical to the two calls'; coefficients agree up to fp32
+ * summation order (the chunk boundaries differ).
  * workspace: >= fa_compress_kv_workspace_bytes_for(dtype, B, H, N, D, Dkc, Dvc, M)
  * (fa_compress_kv_workspace_bytes(...) covers either element type), 256-byte aligned.  Everything else (argument meaning, errors, asynchrony) as fa_compress.
  */

@@ -1019,8 +1019,10 @@ struct CompressPlan {
   size_t total;  // workspace bytes
 };
 
+// tensors: how many tensors share the projection launch (2 for the K | V pair: each then aims at half
+// the chip, so that the pair is ONE round of workgroups - half the chunk partials, one fixed cost)
 static CompressPlan make_compress_plan(int dtype, int B, int H, int N, int D, int Dc, int M,
-                                       int keep_layout, int keep_offset) {
+                                       int keep_layout, int keep_offset, int tensors = 1) {
   CompressPlan pl{};
   pl.nmax = M / 2;
   pl.MC = (Dc > 0 && pl.nmax > 0) ? (pl.nmax + kPairs - 1) / kPairs : 1;
@@ -1031,7 +1033,7 @@ static CompressPlan make_compress_plan(int dtype, int B, int H, int N, int D, in
   // LDS, 256 registers).  A second round of workgroups costs more (its fixed prologue / epilogue,
   // twice the chunk partials) than the idle tail of one round (measured: 256 vs 512 targets: step
   // -7 % on 16 x 8K, -15 % on 8 x 4K MHA where the reduction disappears altogether).
-  constexpr long kTargetWgs = 256;
+  const long kTargetWgs = 256 / tensors;
   long want = (kTargetWgs + groups - 1) / groups;
   const long cap = nblocks / 8 > 0 ? nblocks / 8 : 1;     // but at least 1024 tokens per chunk: the
   if (want > cap) want = cap;                             // chunk partials cost memory traffic
@@ -1118,7 +1120,8 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
                          int accumulate, float* coeffs, void* x_keep, int keep_layout,
                          int64_t keep_stride_bh, int keep_offset, void* workspace,
                          size_t workspace_bytes, void* hip_stream, fa::KernelTimers* tm,
-                         fa::CompressParams* only_params = nullptr, fa::CompressPlan* only_plan = nullptr) {
+                         fa::CompressParams* only_params = nullptr, fa::CompressPlan* only_plan = nullptr,
+                         int tensors = 1) {
   using namespace fa;
   const int st = check_compress_shapes(dtype, B, H, N, D, Dc, M, T, t0);
   if (st != FA_OK) return st;
@@ -1139,7 +1142,7 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
     return FA_ERR_SHAPE;
   if (reinterpret_cast<uintptr_t>(coeffs) & 15u) return FA_ERR_SHAPE;
 
-  const CompressPlan pl = make_compress_plan(dtype, B, H, N, D, Dc, M, keep_layout, keep_offset);
+  const CompressPlan pl = make_compress_plan(dtype, B, H, N, D, Dc, M, keep_layout, keep_offset, tensors);
   if (pl.total > 0) {
     if (!workspace) return FA_ERR_NULL;
     if (workspace_bytes < pl.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
@@ -1263,10 +1266,10 @@ static int compress_kv_impl(const void* k, const void* v, int dtype, int64_t sx_
   CompressParams pk{}, pv{};
   CompressPlan plk{}, plv{};
   int rc = compress_impl(k, dtype, sx_b, sx_h, sx_n, B, H, N, D, kmask, Dkc, M, T, t0, accumulate, ck, k_keep,
-                         FA_KEEP_ROWS, kk_stride_bh, keep_offset, ws, wk, hip_stream, nullptr, &pk, &plk);
+                         FA_KEEP_ROWS, kk_stride_bh, keep_offset, ws, wk, hip_stream, nullptr, &pk, &plk, 2);
   if (rc != FA_OK) return rc;
   rc = compress_impl(v, dtype, sx_b, sx_h, sx_n, B, H, N, D, vmask, Dvc, M, T, t0, accumulate, cv, v_keep,
-                     FA_KEEP_TOK8, vk_stride_bh, keep_offset, ws + wk, wv, hip_stream, nullptr, &pv, &plv);
+                     FA_KEEP_TOK8, vk_stride_bh, keep_offset, ws + wk, wv, hip_stream, nullptr, &pv, &plv, 2);
   if (rc != FA_OK) return rc;
   // One launch for both when each side takes the straight-line step with kept dims to write
   // (bf16, head dim 128, at most one kept vector per thread and block) and they split the tokens

@@ -454,11 +454,21 @@ def test_decode_multi_query_with_one_token_is_fa_decode():
 # K and V compressed by one call
 # --------------------------------------------------------------------------
 
+def _same_coeffs(a, b):
+    """Two evaluations of the same projection whose token chunks differ: fp32 sums in another order
+    (each chunk partial is an fp32 sum over at most a few thousand tokens, the partials meet in fp64)."""
+    a, b = a.double(), b.double()
+    if a.numel():
+        assert (a - b).abs().max().item() <= 2e-5 * max(a.abs().max().item(), 1e-30)
+
+
 @pytest.mark.parametrize("name", ["tiny", "tiny_bf16", "gqa8_oddM", "mha_ragged", "odd_dims", "middle_only", "m512",
                                   "all_compress_bf16", "wide_d256"])
 def test_compress_kv_is_the_two_calls(name):
-    """Bit-identical to fa_compress(K, rows) + fa_compress(V, groups of 8 tokens): the same kernels' arithmetic,
-    whether the pair runs as one launch (bf16, D = 128, few kept dims) or falls back to two calls."""
+    """fa_compress(K, rows) + fa_compress(V, groups of 8 tokens) in one call: kept dims bit-identical,
+    coefficients equal up to fp32 summation order (as one launch the pair may cut the tokens into fewer
+    chunks than the two calls), whether the pair runs as one launch (bf16, D = 128, few kept dims) or
+    falls back to two calls."""
     fa = _fa()
     cfg = next(c for c in SMALL if c.name == name)
     print(f"[case] compress_kv {cfg}", flush=True)
@@ -469,7 +479,8 @@ def test_compress_kv_is_the_two_calls(name):
     cv0, vk0 = fa.fa_compress(v, vm, cfg.Dvc, cfg.M, cfg.T, keep_layout=fa.FA_KEEP_TOK8)
     ck1, kk1, cv1, vk1 = fa.fa_compress_kv(k, v, km, vm, cfg.Dkc, cfg.Dvc, cfg.M, cfg.T)
     torch.cuda.synchronize()
-    assert torch.equal(ck0, ck1) and torch.equal(cv0, cv1)
+    _same_coeffs(ck0, ck1)
+    _same_coeffs(cv0, cv1)
     assert torch.equal(kk0.view(torch.int16) if kk0.dtype == torch.bfloat16 else kk0,
                        kk1.view(torch.int16) if kk1.dtype == torch.bfloat16 else kk1)
     assert torch.equal(vk0.view(torch.int16) if vk0.dtype == torch.bfloat16 else vk0,
@@ -487,6 +498,7 @@ def test_compress_kv_full_size():
     cv0, vk0 = fa.fa_compress(v, vm, cfg.Dvc, cfg.M, cfg.T, keep_layout=fa.FA_KEEP_TOK8)
     ck1, kk1, cv1, vk1 = fa.fa_compress_kv(k, v, km, vm, cfg.Dkc, cfg.Dvc, cfg.M, cfg.T)
     torch.cuda.synchronize()
-    assert torch.equal(ck0, ck1) and torch.equal(cv0, cv1)
+    _same_coeffs(ck0, ck1)
+    _same_coeffs(cv0, cv1)
     assert torch.equal(kk0.view(torch.int16), kk1.view(torch.int16)) and torch.equal(vk0.view(torch.int16), vk1.view(torch.int16))
 
