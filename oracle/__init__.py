@@ -15,6 +15,14 @@ Rules this package obeys:
     are all materialised explicitly).
 """
 
+from .legt import (  # noqa: F401
+    legt_positions,
+    legt_basis,
+    legt_weights,
+    legt_compress,
+    legt_reconstruct,
+    legt_mse,
+)
 from .fourier_kv import (  # noqa: F401
     basis_matrix,
     basis_weights,

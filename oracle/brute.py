@@ -85,3 +85,35 @@ def decode(q, Ck, kmask, Cv, vmask, T, t0, N, k_keep, v_keep, k_full, v_full, sc
                 o[x] += (pj / z) * row[x]
         outs.append(o)
     return outs
+
+
+# ---------------------------------------------------------------------------
+# translated-Legendre alternative (Section 3.2 / 5.1), stated without the recurrence
+# ---------------------------------------------------------------------------
+def legendre_explicit(m: int, x: float) -> float:
+    """P_m(x) from its explicit power series, with exact integer coefficients:
+    P_m(x) = 2^-m sum_k (-1)^k C(m, k) C(2m - 2k, m) x^(m - 2k)."""
+    s = 0.0
+    for k in range(m // 2 + 1):
+        s += (-1) ** k * math.comb(m, k) * math.comb(2 * m - 2 * k, m) * x ** (m - 2 * k)
+    return s / 2 ** m
+
+
+def legt_compress_rebuild(xs, M):
+    """(states, rebuilt values) of one dimension xs[0..N-1]: c_m = sum_j P_m(x_j) xs[j],
+    rebuilt[j] = sum_m (2m+1)/N c_m P_m(x_j), positions x_j = (2j+1)/N - 1."""
+    N = len(xs)
+    pos = [(2 * j + 1) / N - 1.0 for j in range(N)]
+    c = []
+    for m in range(M):
+        acc = 0.0
+        for j in range(N):
+            acc += legendre_explicit(m, pos[j]) * xs[j]
+        c.append(acc)
+    rebuilt = []
+    for j in range(N):
+        acc = 0.0
+        for m in range(M):
+            acc += (2 * m + 1) / N * c[m] * legendre_explicit(m, pos[j])
+        rebuilt.append(acc)
+    return c, rebuilt
