@@ -285,6 +285,23 @@ def measure(cfg, steps, warmup, extras=False):
             res["phases"]["select"] = {"ms": round(t_sel * 1e3, 5), "flop": sel_flop,
                                        "fp32_matrix_tflops": round(sel_flop / t_sel / 1e12, 1),
                                        "fp32_matrix_frac": round(sel_flop / t_sel / 1e12 / FP32_MATRIX_PEAK_TFLOPS, 4)}
+            # Fourier against translated Legendre at the same number of states (the paper's basis comparison,
+            # on the synthetic law): mean reconstruction error of the planted (smooth) dims and of the others
+            Ml = min(M, 256)
+            ws_l = torch.empty(max(256, fa.legt_workspace_bytes(B, Hkv, N, D, Ml)), dtype=torch.uint8, device="cuda")
+            x0 = sets[0]["k_mid"]
+            leg = lambda i: fa.fa_legt(x0, Ml, workspace=ws_l)
+            leg(0)
+            t_leg = timed_loop(torch, leg, 3)
+            _, mse_l = fa.fa_legt(x0, Ml, workspace=ws_l)
+            _, mse_f = fa.fa_select_dims(x0, Ml, cfg.Dkc, workspace=ws_s)
+            torch.cuda.synchronize()
+            planted = sets[0]["kmask"].bool()
+            res["phases"]["basis_comparison"] = {
+                "states": Ml, "legt_ms": round(t_leg * 1e3, 4),
+                "legt_fp32_vector_tflops": round(4.0 * B * Hkv * N * Ml * D / t_leg / 1e12, 2),
+                "mse_smooth_dims": {"fourier": float(mse_f[planted].mean()), "legt": float(mse_l[planted].mean())},
+                "mse_other_dims": {"fourier": float(mse_f[~planted].mean()), "legt": float(mse_l[~planted].mean())}}
     del sets, ws_c, ws_d
     torch.cuda.empty_cache()
     return res, ctx

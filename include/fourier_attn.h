@@ -21,6 +21,8 @@
  *                among themselves).
  *   fa_select_dims  Section 3.4: rank the head dimensions of a segment by
  *                their reconstruction error and mark the Dc best for compression.
+ *   fa_legt_compress / fa_legt_mse  Sections 3.2, 5.1: the translated-Legendre
+ *                basis of the paper's basis comparison.
  *
  * Conventions shared by every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
@@ -299,6 +301,35 @@ int fa_select_dims(const void* x, int dtype,
                    int B, int H, int N, int D, int M, int Dc,
                    uint8_t* dim_mask, float* mse,
                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * fa_legt_compress / fa_legt_mse -- the translated-Legendre (HiPPO-LegT) alternative basis that the
+ * paper compares its Fourier basis with (Section 3.2; Section 5.1 and its reconstruction figure):
+ * how well does each rebuild a KV dimension from the same number of states?  The paper gives no
+ * formula for its LegT; the window is taken to be the segment itself, its N tokens at the cell
+ * midpoints x_j = (2j+1)/N - 1 of [-1, 1]:
+ *     coeffs[b,h,m,d] = sum_j P_m(x_j) x[b,h,j,d]                      (fa_legt_compress)
+ *     mse[b,h,d] = (1/N) sum_j ( x[b,h,j,d] - sum_m (2m+1)/N coeffs[b,h,m,d] P_m(x_j) )^2   (fa_legt_mse)
+ * with P_m the Legendre polynomial of degree m and (2m+1)/N the inverse of its squared norm under
+ * the midpoint rule (sampled polynomials are orthogonal only up to that rule's O(1/N^2) error; the
+ * oracle makes the same approximation).  The Fourier counterpart of mse is fa_select_dims' output.
+ * All D head dims are processed (no mask): this is a calibration / ablation tool, not part of a
+ * decode step.
+ *
+ *   x         DEVICE, dtype elements [B,H,N,D], element strides, dim stride 1; read only
+ *   M         1 <= M <= N states per dimension (at most FA_MAX_STATES)
+ *   coeffs    DEVICE fp32 [B,H,M,D]: written by fa_legt_compress, read by fa_legt_mse
+ *   mse       DEVICE fp32 [B,H,D], written
+ *   workspace DEVICE, 256-byte aligned, >= fa_legt_workspace_bytes(...) bytes
+ * Asynchronous on hip_stream; nothing is allocated; arguments are checked on the host first.
+ */
+size_t fa_legt_workspace_bytes(int B, int H, int N, int D, int M);
+int fa_legt_compress(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n,
+                     int B, int H, int N, int D, int M, float* coeffs,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+int fa_legt_mse(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n,
+                int B, int H, int N, int D, int M, const float* coeffs, float* mse,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Measurement aids.  Same arguments and effect as fa_compress / fa_decode, but

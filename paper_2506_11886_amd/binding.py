@@ -83,6 +83,12 @@ def _load(path: str = _LIB_PATH):
     lib.fa_select_workspace_bytes.argtypes = [i32] * 6
     lib.fa_select_dims.restype = i32
     lib.fa_select_dims.argtypes = [vp, i32, i64, i64, i64, i32, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.fa_legt_workspace_bytes.restype = sz
+    lib.fa_legt_workspace_bytes.argtypes = [i32] * 5
+    lib.fa_legt_compress.restype = i32
+    lib.fa_legt_compress.argtypes = [vp, i32, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.fa_legt_mse.restype = i32
+    lib.fa_legt_mse.argtypes = [vp, i32, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.fa_status_string.restype = c.c_char_p
     lib.fa_status_string.argtypes = [i32]
     return lib
@@ -282,6 +288,32 @@ def fa_select_dims(x, M, Dc, want_mse=True, workspace=None, stream=None):
     if st != FA_OK:
         raise FourierAttnError(st, "fa_select_dims")
     return mask, mse
+
+
+def legt_workspace_bytes(B, H, N, D, M) -> int:
+    return int(lib.fa_legt_workspace_bytes(B, H, N, D, M))
+
+
+def fa_legt(x, M, workspace=None, stream=None, want_mse=True):
+    """Enqueue fa_legt_compress (and fa_legt_mse) on `stream` for x [B,H,N,D]: returns (coeffs fp32
+    [B,H,M,D], mse fp32 [B,H,D] or None)."""
+    B, H, N, D = x.shape
+    dev = x.device
+    coeffs = torch.empty((B, H, M, D), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(legt_workspace_bytes(B, H, N, D, M), 256), dtype=torch.uint8, device=dev)
+    st = lib.fa_legt_compress(_ptr(x), _dtype_code(x), x.stride(0), x.stride(1), x.stride(2), B, H, N, D, M,
+                              _ptr(coeffs), _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    if st != FA_OK:
+        raise FourierAttnError(st, "fa_legt_compress")
+    mse = None
+    if want_mse:
+        mse = torch.empty((B, H, D), dtype=torch.float32, device=dev)
+        st = lib.fa_legt_mse(_ptr(x), _dtype_code(x), x.stride(0), x.stride(1), x.stride(2), B, H, N, D, M,
+                             _ptr(coeffs), _ptr(mse), _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+        if st != FA_OK:
+            raise FourierAttnError(st, "fa_legt_mse")
+    return coeffs, mse
 
 
 def fa_decode_mq(q, ck, kmask, cv, vmask, M, T, t0, N, k_keep, v_keep, k_full, v_full,

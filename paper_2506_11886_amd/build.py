@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfourier_attn.so")
-SOURCES = ("fa_compress.hip", "fa_decode.hip", "fa_append.hip", "fa_select.hip")
+SOURCES = ("fa_compress.hip", "fa_decode.hip", "fa_append.hip", "fa_select.hip", "fa_legt.hip")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

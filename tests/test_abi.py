@@ -24,7 +24,8 @@ def test_library_exports_every_declared_symbol():
             "fa_decode_workspace_bytes", "fa_decode_default_splits", "fa_status_string",
             "fa_append", "fa_select_dims", "fa_select_workspace_bytes", "fa_decode_mq", "fa_compress_kv",
             "fa_compress_kv_workspace_bytes", "fa_decode_static", "fa_compress_workspace_bytes_for",
-            "fa_compress_kv_workspace_bytes_for"} <= names
+            "fa_compress_kv_workspace_bytes_for", "fa_legt_compress", "fa_legt_mse",
+            "fa_legt_workspace_bytes"} <= names
     for n in names:
         assert hasattr(fa.lib, n), n
 
@@ -188,3 +189,22 @@ def test_static_scratch_refuses_sizes_beyond_the_array():
     for c in CONFIGS:
         assert 0 < fa.decode_workspace_bytes(c.B, c.Hq, c.Hkv, c.D, c.Dkc, c.Dvc, c.M, c.N, c.W, c.num_splits) \
             <= fa.FA_STATIC_SCRATCH_BYTES
+
+
+def test_legt_rejects_bad_arguments_on_the_host():
+    fa = _fa()
+
+    def call(**kw):
+        d = dict(x=FAKE, dtype=1, sn=64, N=300, D=64, M=32, coeffs=FAKE, ws=FAKE, ws_bytes=1 << 30)
+        d.update(kw)
+        return fa.lib.fa_legt_compress(d["x"], d["dtype"], 8 * d["N"] * d["sn"], d["N"] * d["sn"], d["sn"], 1, 8, d["N"],
+                                       d["D"], d["M"], d["coeffs"], d["ws"], d["ws_bytes"], None)
+    assert call(M=301) == -2             # more states than tokens
+    assert call(D=60, sn=60) == -3
+    assert call(dtype=5) == -3
+    assert call(x=None) == -1
+    assert call(coeffs=None) == -1
+    assert call(sn=32) == -2             # rows overlap
+    assert call(ws_bytes=16) == -4
+    assert fa.lib.fa_legt_mse(FAKE, 1, 8 * 300 * 64, 300 * 64, 64, 1, 8, 300, 64, 32, FAKE, None, FAKE, 1 << 30, None) == -1
+    assert fa.legt_workspace_bytes(1, 8, 300, 64, 32) >= 1 * 8 * 32 * 64 * 4

@@ -402,6 +402,55 @@ def test_select_dims_full_size():
 
 
 # --------------------------------------------------------------------------
+# the translated-Legendre alternative basis (Sections 3.2, 5.1)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,M", [("tiny", 32), ("tiny_bf16", 17), ("gqa8_oddM", 63), ("mha_ragged", 128),
+                                    ("wide_d256_f32", 40), ("m512", 300)])
+def test_legt_matches_oracle(name, M):
+    """fa_legt_compress / fa_legt_mse on the K segment of a small shape against oracle/legt.py, every head:
+    states within the element type's tolerance of the largest state, errors within it of each dim's mean square."""
+    import oracle.legt as lg
+    fa = _fa()
+    cfg = next(c for c in SMALL if c.name == name)
+    print(f"[case] LegT M={M} {cfg}", flush=True)
+    ctx = cached_context(cfg)
+    x = to_dev(ctx["k_mid"], cfg)
+    coeffs, mse = fa.fa_legt(x, M)
+    torch.cuda.synchronize()
+    coeffs, mse = coeffs.cpu().numpy(), mse.cpu().numpy()
+    xh = x.float().cpu().numpy().astype(np.float64)
+    tol = cfg.tol if cfg.dtype == "f32" else 1e-5          # bf16 inputs are widened exactly: fp32 arithmetic either way
+    for b, h in sample_heads(cfg, None):
+        C = lg.legt_compress(xh[b, h], M)
+        fl = np.sqrt(cfg.N * np.mean(xh[b, h] ** 2))
+        assert rel_err(coeffs[b, h], C, fl) <= tol, ("states", b, h, rel_err(coeffs[b, h], C, fl))
+        want = lg.legt_mse(xh[b, h], M)
+        scale = np.mean(xh[b, h] ** 2, axis=0)
+        assert np.all(np.abs(mse[b, h] - want) <= 2e-5 * scale + 1e-12), (b, h, np.abs(mse[b, h] - want).max())
+
+
+def test_legt_full_size_segment():
+    """The bench workload's K segment (31740 tokens, 128 dims) at M = 256, two sampled heads."""
+    import oracle.legt as lg
+    fa = _fa()
+    cfg = CONFIGS[1]
+    ctx = cached_context(cfg)
+    x = to_dev(ctx["k_mid"], cfg)
+    coeffs, mse = fa.fa_legt(x, cfg.M)
+    torch.cuda.synchronize()
+    coeffs, mse = coeffs.cpu().numpy(), mse.cpu().numpy()
+    xh = x.float().cpu().numpy().astype(np.float64)
+    for b, h in sample_heads(cfg, 2, seed=3):
+        C = lg.legt_compress(xh[b, h], cfg.M)
+        fl = np.sqrt(cfg.N * np.mean(xh[b, h] ** 2))
+        assert rel_err(coeffs[b, h], C, fl) <= 1e-5
+        want = lg.legt_mse(xh[b, h], cfg.M)
+        scale = np.mean(xh[b, h] ** 2, axis=0)
+        assert np.all(np.abs(mse[b, h] - want) <= 2e-5 * scale + 1e-12)
+
+
+# --------------------------------------------------------------------------
 # several query tokens per step
 # --------------------------------------------------------------------------
 
