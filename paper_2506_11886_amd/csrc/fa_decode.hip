@@ -1621,9 +1621,8 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsig
         gp[2 * j] = gc * csv[j] + gsn * snv[j];
         gp[2 * j + 1] = gsn * csv[j] - gc * snv[j];
       }
-      Frag<ES> bg;
+      Frag<ES> bg;   // (columns without a query head get some head's values: their scores are never used)
       pack8(bg, gp);
-      if (!col_live) bg.zero();
 #pragma unroll
       for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], eA[i][rb], bg);
     }
@@ -1725,7 +1724,7 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsig
 #pragma unroll
       for (int dt = 0; dt < DVT; ++dt) {
         Frag<T> bv = vf[x][dt];
-        if (16 * dt + r16 >= Dvu) bv.zero();
+        if ((Dvu & 15) != 0 && 16 * dt + r16 >= Dvu) bv.zero();
         if constexpr (kTail) {
           const int tok0 = base + wave * kTJ + 32 * x + 8 * q4;
           if (tok0 + 8 > c1) mask_tail(bv, c1 - tok0);
@@ -2066,9 +2065,8 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
         gp[2 * j] = gc * csv[j] + gsn * snv[j];
         gp[2 * j + 1] = gsn * csv[j] - gc * snv[j];
       }
-      Frag<ES> bg;
+      Frag<ES> bg;   // (columns without a query head get some head's values: their scores are never used)
       pack8(bg, gp);
-      if (!col_live) bg.zero();
 #pragma unroll
       for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], eA[i][rb], bg);
     }
@@ -2170,7 +2168,7 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
 #pragma unroll
       for (int dt = 0; dt < DVT; ++dt) {
         Frag<T> bv = vf[dt];
-        if (16 * dt + r16 >= Dvu) bv.zero();
+        if ((Dvu & 15) != 0 && 16 * dt + r16 >= Dvu) bv.zero();
         if constexpr (kTail) {
           const int tok0 = base + my_tile * kTJ + 32 * my_half + 8 * q4;
           if (tok0 + 8 > c1) mask_tail(bv, c1 - tok0);
