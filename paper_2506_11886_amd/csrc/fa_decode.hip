@@ -2854,6 +2854,15 @@ static int series_chunks_per_wave(int M) {   // compiled series lengths: 128, 25
 // better (measured: 3-5 steps per chunk is the flat optimum at two workgroups per unit).
 static int default_steps_per_chunk(int B, int Hkv, int N, int step, int cw, int Sw) {
   const long total_steps = static_cast<long>(B) * Hkv * ((N + step - 1) / step);
+  // a launch small enough for ONE workgroup per compute unit with at most six steps each runs
+  // faster that way than spread over two per unit (32 K tokens: 25 chunks per head 12.0 us, 42 chunks 13.1 us)
+  if (cw <= 2) {
+    const long one_each = 256 - static_cast<long>(B) * Hkv * Sw;
+    if (one_each >= 128) {
+      const long spc1 = (total_steps + one_each - 1) / one_each;
+      if (spc1 >= 1 && spc1 <= 6) return static_cast<int>(spc1);
+    }
+  }
   const long slots = cw <= 2 ? 512 : 256;
   long target = slots - static_cast<long>(B) * Hkv * Sw;
   if (target < 3 * slots / 4) target = 3 * slots / 4;
