@@ -2884,10 +2884,14 @@ static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, 
   pl.Mint = kWaves * pl.cw * 32;
   const int step = pl.KT * kTJ;
   pl.Sw = (W + kWChunk - 1) / kWChunk;
+  // full-width rows that ride in the launch of the series coefficients (see Swp below) take no
+  // compute unit away from the middle rows
+  const bool window_rides = dtype == FA_BF16 && N > 0 && pl.cw == 4 && G <= 4 && D - Dkc > 0 && D - Dkc <= 32 &&
+                            D - Dvc > 0 && D - Dvc <= 32 && Dkc > 0 && (Dkc & 3) == 0;
   if (N > 0) {
     int chunk;
     if (num_splits > 0) chunk = round_up((N + num_splits - 1) / num_splits, step);
-    else chunk = default_steps_per_chunk(B, Hkv, N, step, pl.cw, pl.Sw) * step;
+    else chunk = default_steps_per_chunk(B, Hkv, N, step, pl.cw, window_rides ? 0 : pl.Sw) * step;
     pl.chunk_m = chunk;
     pl.Sm = (N + chunk - 1) / chunk;
   } else {
@@ -2929,7 +2933,7 @@ static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, 
   // instead (independent work that fills the chip while that chain of round trips is in flight).  With
   // two middle-row workgroups per unit the full-width rows overlap with them and stay where they are
   // (measured: moving them costs 1.5 us on 32 K tokens, 12 us on 8 x 4 K MHA).
-  pl.Swp = (pl.fast == 8 && Dkc > 0 && (Dkc & 3) == 0) ? 0 : pl.Sw;
+  pl.Swp = (pl.fast == 8 && Dkc > 0 && (Dkc & 3) == 0) ? 0 : pl.Sw;   // (= window_rides)
   const unsigned t = mid > wpath ? mid : wpath;
   pl.lds_total = (t + 255u) & ~255u;
   if (pl.lds_total > kMaxDynLds) return false;
