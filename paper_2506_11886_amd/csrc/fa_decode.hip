@@ -1854,6 +1854,7 @@ __global__ __launch_bounds__(kBlock, CW <= 2 ? 2 : 1) void decode_partial_fast(D
 // two rows per lane.  The score exchange is padded so that the eight-byte reads of the owners
 // fall in distinct LDS banks.
 constexpr int kWaves8 = 8;
+constexpr float kSoftmaxSlack = 8.0f;   // how far a score may exceed its column's reference before the reference moves
 constexpr int kBlock8 = 64 * kWaves8;
 constexpr int kXs8Q4 = 18;                    // f32x4 cells per (row block, lane / 16): 16 columns + 2 pad cells
 constexpr int kXs8Rb = 4 * kXs8Q4;            // per row block
@@ -1953,12 +1954,16 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
   {
     const int n_max = p.M / 2;
     const float invT = 1.0f / static_cast<float>(p.T);
+    // The wave's accumulators hold the row blocks of a tile in an order of their own: local block l is row
+    // block (l + 2 my_half) & 3, so that the two blocks whose kept K rows this wave multiplies are always
+    // accumulators 0 and 1 (no branch on the wave's half in the steps).
     float cd[kRB], sd[kRB];
     int urow[kRB];
 #pragma unroll
-    for (int rb = 0; rb < kRB; ++rb) {
-      urow[rb] = 32 * (rb >> 1) + 4 * (rb & 1) + urow_lane;
-      table_cs<T>(1, urow[rb], p.T, invT, &cd[rb], &sd[rb]);
+    for (int l = 0; l < kRB; ++l) {
+      const int rb = (l + 2 * my_half) & 3;
+      urow[l] = 32 * (rb >> 1) + 4 * (rb & 1) + urow_lane;
+      table_cs<T>(1, urow[l], p.T, invT, &cd[l], &sd[l]);
     }
 #pragma unroll
     for (int i = 0; i < CW; ++i) {
@@ -2018,6 +2023,35 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
   bq.load(qk_s + hsafe * Dkq + 8 * q4);
   if (col_k != my_tile || !col_live) bq.zero();
 
+  // K-side series coefficients of this lane's column (tile, head) and four orders per slice, rotated to
+  // the origin of the column's tile in the first step; every later step turns them on by the angle of
+  // one step (angle addition, four multiply-adds per order: no table look-up, no evaluation in the loop)
+  float gk[CW][8], tkc[CW][4], tks[CW][4];
+  {
+    const uint32_t ph_k = phase_of(p.t0 + w0 + col_k * kTJ, p.ph_scale);
+    const uint32_t ph_step = phase_of(step, p.ph_scale);
+#pragma unroll
+    for (int i = 0; i < CW; ++i) {
+      const uint32_t n0 = 16 * (wave * CW + i) + 4 * q4 + 1;
+      const float* gl = gs_s + hsafe * kPitchG + 32 * (wave * CW + i) + 8 * q4;
+      const f32x4 ga = *reinterpret_cast<const f32x4*>(gl), gb = *reinterpret_cast<const f32x4*>(gl + 4);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float cs, sn;
+        phase_cs<T>((n0 + j) * ph_k, &cs, &sn);
+        const float gc = (j < 2) ? ga[2 * (j & 1)] : gb[2 * (j & 1)];
+        const float gsn = (j < 2) ? ga[2 * (j & 1) + 1] : gb[2 * (j & 1) + 1];
+        gk[i][2 * j] = gc * cs + gsn * sn;
+        gk[i][2 * j + 1] = gsn * cs - gc * sn;
+        phase_cs<T>((n0 + j) * ph_step, &tkc[i][j], &tks[i][j]);
+      }
+    }
+  }
+
+  // where the local row blocks go in the score exchange: blocks 0, 1 are row blocks 2 my_half, 2 my_half + 1
+  f32x4* const xw_lo = xs + wave * kXs8Wave + q4 * kXs8Q4 + r16 + 2 * my_half * kXs8Rb;
+  f32x4* const xw_hi = xs + wave * kXs8Wave + q4 * kXs8Q4 + r16 + 2 * (1 - my_half) * kXs8Rb;
+
   f32x4 racc[2 * CW];
   f32x4 oacc[DVT];
   float m_run, l_run;
@@ -2037,54 +2071,29 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // -- (a) series on the K side, own orders -----------------------------------------
-    const uint32_t ph_k = phase_of(p.t0 + base + col_k * kTJ, p.ph_scale);
+    // -- (a) series on the K side, own orders: S += E g'(tile origin); g' moves on to the next step ---
 #pragma unroll
     for (int i = 0; i < CW; ++i) {
-      const uint32_t n0 = 16 * (wave * CW + i) + 4 * q4 + 1;
-      float csv[4], snv[4];
-      if constexpr (GP >= 4) {
-        float cs, sn;
-        phase_cs<T>((n0 + (lane & 3)) * ph_k, &cs, &sn);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          csv[j] = quad_bcast(cs, j);
-          snv[j] = quad_bcast(sn, j);
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) phase_cs<T>((n0 + j) * ph_k, &csv[j], &snv[j]);
-      }
-      const float* gl = gs_s + hsafe * kPitchG + 32 * (wave * CW + i) + 8 * q4;
-      const f32x4 ga = *reinterpret_cast<const f32x4*>(gl), gb = *reinterpret_cast<const f32x4*>(gl + 4);
-      float gp[8];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float gc = (j < 2) ? ga[2 * (j & 1)] : gb[2 * (j & 1)];
-        const float gsn = (j < 2) ? ga[2 * (j & 1) + 1] : gb[2 * (j & 1) + 1];
-        gp[2 * j] = gc * csv[j] + gsn * snv[j];
-        gp[2 * j + 1] = gsn * csv[j] - gc * snv[j];
-      }
       Frag<ES> bg;   // (columns without a query head get some head's values: their scores are never used)
-      pack8(bg, gp);
+      pack8(bg, gk[i]);
 #pragma unroll
       for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], eA[i][rb], bg);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float gc = gk[i][2 * j], gsn = gk[i][2 * j + 1];
+        gk[i][2 * j] = tkc[i][j] * gc + tks[i][j] * gsn;
+        gk[i][2 * j + 1] = tkc[i][j] * gsn - tks[i][j] * gc;
+      }
     }
-    // -- (b) kept K dims: two row blocks of tile my_tile --------------------------------------------
-    if (my_half == 0) {
-      mma_k32(sacc[0], kf[0], bq);
-      mma_k32(sacc[1], kf[1], bq);
-    } else {
-      mma_k32(sacc[2], kf[0], bq);
-      mma_k32(sacc[3], kf[1], bq);
-    }
+    // -- (b) kept K dims: two row blocks of tile my_tile (local blocks 0 and 1) ----------------------
+    mma_k32(sacc[0], kf[0], bq);
+    mma_k32(sacc[1], kf[1], bq);
 
     // -- (c) the partial scores of the eight waves meet; this wave sums its two columns --------
-    {
-      f32x4* xw = xs + wave * kXs8Wave + q4 * kXs8Q4 + r16;
-#pragma unroll
-      for (int rb = 0; rb < kRB; ++rb) xw[rb * kXs8Rb] = sacc[rb];
-    }
+    xw_lo[0] = sacc[0];
+    xw_lo[kXs8Rb] = sacc[1];
+    xw_hi[0] = sacc[2];
+    xw_hi[kXs8Rb] = sacc[3];
     __syncthreads();
     f32x2 sv;
     {
@@ -2094,6 +2103,10 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
       sv = (a0 + a1) + (a2 + a3);
     }
     // -- (d) online softmax of the own columns -----------------------------------------------------
+    // The reference m_run of a column only has to keep exp(score - m_run) inside the range of the
+    // 16-bit probabilities, not to be the maximum: it moves when a score of one of the wave's columns
+    // exceeds it by more than kSoftmaxSlack (always in a chunk's first step), and only then is there a
+    // maximum to reduce and a factor to apply.
     float pv[2];
     float m_tile = -INFINITY;
 #pragma unroll
@@ -2107,15 +2120,18 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
       pv[v] = sc;
       m_tile = fmaxf(m_tile, sc);
     }
-    m_tile = row_stride_max(m_tile, 2);                      // the 32 lanes of a column are 2 apart
-    m_tile = cross_row_max(m_tile);
-    const float m_new = fmaxf(m_run, m_tile);
-    const float m_ref = (m_new == -INFINITY) ? 0.0f : m_new;
-    const float alpha = __expf(m_run - m_ref);
+    float alpha = 1.0f;
+    if (__builtin_amdgcn_ballot_w64(m_tile > m_run + kSoftmaxSlack) != 0) {   // (uniform over the wave)
+      m_tile = row_stride_max(m_tile, 2);                    // the 32 lanes of a column are 2 apart
+      m_tile = cross_row_max(m_tile);
+      const float m_new = fmaxf(m_run, m_tile);
+      alpha = __expf(m_run - ((m_new == -INFINITY) ? 0.0f : m_new));
+      m_run = m_new;
+    }
+    const float m_ref = (m_run == -INFINITY) ? 0.0f : m_run;
     pv[0] = __expf(pv[0] - m_ref);
     pv[1] = __expf(pv[1] - m_ref);
     l_run = l_run * alpha + (pv[0] + pv[1]);
-    m_run = m_new;
     {
       const int slot = (((orb >> 1) * 16 + ocol) * 4 + oq4) * 8 + 4 * (orb & 1) + 2 * ohalf;
       uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pv[0], pv[1]}, f16x2));
@@ -2132,17 +2148,27 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
     // -- (e) bring the accumulators into this step's frame ------------------------------------------
     {
       const f32x4 al = *reinterpret_cast<const f32x4*>(alpha_s + 4 * q4);
+      const bool moved = al[0] != 1.0f || al[1] != 1.0f || al[2] != 1.0f || al[3] != 1.0f;
+      if (__builtin_amdgcn_ballot_w64(moved) != 0) {   // some column's reference moved: factors to apply
 #pragma unroll
-      for (int t = 0; t < DVT; ++t)
+        for (int t = 0; t < DVT; ++t)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) oacc[t][v] *= al[v];
+          for (int v = 0; v < 4; ++v) oacc[t][v] *= al[v];
+#pragma unroll
+        for (int i = 0; i < CW; ++i)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            racc[2 * i][v] *= al[v];
+            racc[2 * i + 1][v] *= al[v];
+          }
+      }
 #pragma unroll
       for (int i = 0; i < CW; ++i)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const float rc = racc[2 * i][v], rs = racc[2 * i + 1][v];
-          racc[2 * i][v] = al[v] * (tc[i] * rc + ts[i] * rs);
-          racc[2 * i + 1][v] = al[v] * (tc[i] * rs - ts[i] * rc);
+          racc[2 * i][v] = tc[i] * rc + ts[i] * rs;
+          racc[2 * i + 1][v] = tc[i] * rs - ts[i] * rc;
         }
     }
     // -- (f) V side, own orders: r' += P^T E ----------------------------------------------------------
