@@ -2918,6 +2918,13 @@ static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, 
     int chunk;
     if (num_splits > 0) chunk = round_up((N + num_splits - 1) / num_splits, step);
     else chunk = default_steps_per_chunk(B, Hkv, N, step, pl.cw, window_rides ? 0 : pl.Sw) * step;
+    // a record list has room for kMaxPartials entries per query head: very long contexts (or a
+    // caller's very fine split) take longer chunks instead of being refused
+    if (pl.Sw < kMaxPartials) {
+      const int room = kMaxPartials - pl.Sw;
+      const int least = round_up((N + room - 1) / room, step);
+      if (chunk < least) chunk = least;
+    }
     pl.chunk_m = chunk;
     pl.Sm = (N + chunk - 1) / chunk;
   } else {
