@@ -90,7 +90,41 @@ struct DecodeParams {
   float* part_m;    // [B,Hq,Sm,recm]
   float* part_w;    // [B,Hq,Sw,recw]
   float* out;       // [B,Hq,D]
+  const int32_t* seq_n;   // [B] middle rows of each sequence (<= N), or null: N for all
+  const int32_t* seq_w;   // [B] full-width rows of each sequence (<= W), or null: W for all
+  int Sw_rec;       // full-row records reserved per query head (= Sw of the longest sequence)
 };
+
+// What a workgroup uses of one sequence: its row counts, the chunking that follows from them and
+// where its records go.  The three-launch kernels take the call's own values; the one-launch form
+// resolves them per sequence.
+struct SeqView {
+  int N, W, Sm, Sw, chunk_m;
+  float* part_m;
+  float* part_w;
+};
+__device__ __forceinline__ SeqView call_view(const DecodeParams& p) {
+  return SeqView{p.N, p.W, p.Sm, p.Sw, p.chunk_m, p.part_m, p.part_w};
+}
+
+// LDS of a workgroup of the one-launch form, after the exchange region of the middle-row phase:
+// series coefficients [G][Mint + 32] | packed kept q [G][32] | constant-term coefficients | the
+// middle-row record [G][recm] | the full-row record [G][recw] | C_v of the pair [M][Dvc] (1 KB aligned)
+struct FusedLds {
+  unsigned gs, qk, g0, recm, recw, cv, total;
+};
+__host__ __device__ __forceinline__ FusedLds fused_lds(unsigned lds_tab, int G, int Mint, int recm, int recw, int M,
+                                                       int Dvc) {
+  FusedLds L;
+  L.gs = lds_tab;
+  L.qk = L.gs + G * (Mint + 32) * 4;
+  L.g0 = L.qk + G * 32 * 2;
+  L.recm = L.g0 + 64;
+  L.recw = L.recm + G * recm * 4;
+  L.cv = (L.recw + G * recw * 4 + 1023u) & ~1023u;
+  L.total = L.cv + ((static_cast<unsigned>(M) * Dvc * 4 + 1023u) & ~1023u);
+  return L;
+}
 
 // ---------------------------------------------------------------------------
 // small helpers
@@ -354,16 +388,16 @@ __global__ __launch_bounds__(kBlock) void decode_prepare(DecodeParams p) {
 // registers, and the TPR shares meet by lane rotation.  256 / TPR rows per workgroup: 64 when
 // the (sequence, head) pairs alone fill the chip, 16 when there are few of them.
 template <typename T, int TPR>
-__device__ __forceinline__ void prepare2_rows(const DecodeParams& p) {
+__device__ __forceinline__ void prepare2_rows(const DecodeParams& p, const int bh, const int blk) {
   constexpr int kRows = kBlock / TPR;
   constexpr int kV4 = (FA_MAX_HEAD_DIM / 4 + TPR - 1) / TPR;
   __shared__ __attribute__((aligned(16))) float qc[kMaxG * FA_MAX_HEAD_DIM];   // [G][Dkc] query at the compressed dims
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int b = bh / p.Hkv, hkv = bh % p.Hkv;
   const int Dkc = p.Dkc, D = p.D, G = p.G;
   const int row = tid / TPR, seg = tid % TPR;
-  const int m = blockIdx.x * kRows + row;            // basis function of this thread's row (0 .. Mint)
+  const int m = blk * kRows + row;            // basis function of this thread's row (0 .. Mint)
   const int c4n = Dkc / 4;
 
   // C_k row, the mask row and q of the group: all requested up front, clamped, never predicated
@@ -395,10 +429,10 @@ __device__ __forceinline__ void prepare2_rows(const DecodeParams& p) {
       const int h = it / D, d = it % D;
       const int r = dim_rank(kbal, d);
       if (r < 0) qc[h * Dkc + (-r - 1)] = to_f32(qe[i]);
-      else if (blockIdx.x == 0) qkeep[h * Dkq + r] = qe[i];
+      else if (blk == 0) qkeep[h * Dkq + r] = qe[i];
     }
   }
-  if (blockIdx.x == 0) {
+  if (blk == 0) {
     const int npad = Dkq - p.Dku;
     for (int it = tid; it < G * npad; it += kBlock) qkeep[(it / npad) * Dkq + p.Dku + it % npad] = T{};
   }
@@ -434,7 +468,7 @@ __device__ __forceinline__ void prepare2_rows(const DecodeParams& p) {
 
 template <typename T, int TPR>
 __global__ __launch_bounds__(kBlock) void decode_prepare2(DecodeParams p) {
-  prepare2_rows<T, TPR>(p);
+  prepare2_rows<T, TPR>(p, blockIdx.y, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -1251,19 +1285,19 @@ __device__ __forceinline__ float cross_row_sum(float v) {
 // B operands - is requested at the start, the softmax of a wave stays inside the wave, and the
 // waves meet once, at the end.
 template <typename T>
-__device__ __forceinline__ void partial_full_fast(const DecodeParams& p, unsigned char* smem, int s) {
+__device__ __forceinline__ void partial_full_fast(const DecodeParams& p, const SeqView& sv, unsigned char* smem, const int bh, int s) {
   static_assert(sizeof(T) == 2, "16-bit elements");
   constexpr int D = 128, kH = 4;                        // head dim, query columns
-  const int bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int b = bh / p.Hkv, hkv = bh % p.Hkv;
   const int G = p.G;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int q4 = lane >> 4, r16 = lane & 15;
   const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
   const int jw = s * kWChunk + wave * kWRows;
-  const int nw = max(0, min(kWRows, p.W - jw));
-  const int jlast = p.W - 1;
-  const int jvis = p.W - p.Tq + r16 / p.Gq;             // last row the query token of column r16 may see
+  const int nw = max(0, min(kWRows, sv.W - jw));
+  const int jlast = sv.W - 1;
+  const int jvis = sv.W - p.Tq + r16 / p.Gq;             // last row the query token of column r16 may see
 
   float* pw = reinterpret_cast<float*>(smem) + wave * kWRows * kH;          // [64 rows][4 columns] probabilities
   float* red = reinterpret_cast<float*>(smem) + kWaves * kWRows * kH;      // [waves][4 columns][128 dims]
@@ -1386,7 +1420,7 @@ __device__ __forceinline__ void partial_full_fast(const DecodeParams& p, unsigne
         l += f * wl[w * kH + h];
         v += f * *reinterpret_cast<const f32x4*>(red + (w * kH + h) * D + 4 * d4);
       }
-      float* rec = p.part_w + ((hq0 + h) * p.Sw + s) * p.recw;
+      float* rec = sv.part_w + ((hq0 + h) * sv.Sw + s) * p.recw;
       *reinterpret_cast<f32x4*>(rec + 4 + 4 * d4) = v;
       if (d4 == 0) {
         rec[0] = ms;
@@ -1404,11 +1438,11 @@ template <typename T, int TPR>
 __global__ __launch_bounds__(kBlock) void decode_prepare_window(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   if (static_cast<int>(blockIdx.x) < p.nprep) {
-    prepare2_rows<T, TPR>(p);
+    prepare2_rows<T, TPR>(p, blockIdx.y, blockIdx.x);
   } else {
     const int s = blockIdx.x - p.nprep;
     if constexpr (sizeof(T) == 2) {
-      if (p.D == 128 && p.G <= 4) partial_full_fast<T>(p, smem, s);
+      if (p.D == 128 && p.G <= 4) partial_full_fast<T>(p, call_view(p), smem, blockIdx.y, s);
       else partial_full_rows<T>(p, smem, s);
     } else {
       partial_full_rows<T>(p, smem, s);
@@ -1416,8 +1450,11 @@ __global__ __launch_bounds__(kBlock) void decode_prepare_window(DecodeParams p) 
   }
 }
 
-template <int CW, int DVT, int GP>
-__device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsigned char* smem) {
+// FUSED: the series coefficients, the constant-term coefficient and the packed query are already in
+// this workgroup's LDS (written by fused_coeffs), not in the workspace
+template <int CW, int DVT, int GP, bool FUSED = false>
+__device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const SeqView& sv, unsigned char* smem,
+                                                    const int bh, const int sm_idx) {
   using T = bf16_t;
   using ES = f16_t;
   constexpr int Mint = kWaves * CW * 32;
@@ -1425,13 +1462,13 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsig
   static_assert(GP == 1 || GP == 4, "score columns per tile");
   static_assert(DVT == 1 || DVT == 2, "kept V column tiles");
 
-  const int sm_idx = blockIdx.x, bh = blockIdx.y, b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int b = bh / p.Hkv, hkv = bh % p.Hkv;
   const int G = p.G;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int q4 = lane >> 4, r16 = lane & 15;
   const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
-  const int c0 = sm_idx * p.chunk_m, c1 = min(p.N, c0 + p.chunk_m);
+  const int c0 = sm_idx * sv.chunk_m, c1 = min(sv.N, c0 + sv.chunk_m);
   const int nsteps = (c1 - c0 + step - 1) / step;
   const int col_k = r16 / GP, col_h = r16 % GP;
   const bool col_live = col_k < KT && col_h < G;
@@ -1441,7 +1478,7 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsig
   const int Dvu = p.Dvu;
   const T* kk = static_cast<const T*>(p.k_keep) + bh * p.kk_stride;
   const T* vk = static_cast<const T*>(p.v_keep) + bh * p.vk_stride;
-  const int Nm1 = p.N - 1;
+  const int Nm1 = sv.N - 1;
 
   // ---- LDS carve-up (as partial_middle_rows) -------------------------------
   f32x4* xs = reinterpret_cast<f32x4*>(smem);
@@ -1458,6 +1495,7 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsig
   constexpr int kPitchG = Mint + 32;
   float* gs_s = reinterpret_cast<float*>(smem + p.lds_tab);
   T* qk_s = reinterpret_cast<T*>(gs_s + G * kPitchG);
+  const float* g0_s = reinterpret_cast<const float*>(qk_s + G * 32);
 
   // this wave's kept operands of the step at `base`: the four row blocks and the two token
   // blocks of tile `wave`.  Rows are clamped into the slab (rows past the chunk are masked at the
@@ -1487,16 +1525,21 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsig
   constexpr int kGLoads = (Mint + kBlock - 1) / kBlock;   // G <= 4 heads of Mint floats, as float4
   const int ng4 = G * Mint / 4;
   f32x4 gv[kGLoads];
+  if constexpr (!FUSED) {
 #pragma unroll
-  for (int i = 0; i < kGLoads; ++i)
-    gv[i] = *reinterpret_cast<const f32x4*>(p.gs + hq0 * Mint + 4 * min(tid + i * kBlock, ng4 - 1));
+    for (int i = 0; i < kGLoads; ++i)
+      gv[i] = *reinterpret_cast<const f32x4*>(p.gs + hq0 * Mint + 4 * min(tid + i * kBlock, ng4 - 1));
+  }
   const int ocol = 4 * wave + (lane & 3), orb = lane >> 4, oq4 = (lane >> 2) & 3;
   const int ocol_k = ocol / GP, ocol_h = ocol % GP;
   const bool olive = ocol_k < KT && ocol_h < G;
-  const float g0 = p.g0[hq0 + min(ocol_h, G - 1)];
+  float g0 = 0.0f;
   // packed query at the kept K dims: G rows of 32 elements = at most 16 vectors of 8
   Frag<T> qv;
-  qv.load(static_cast<const T*>(p.qkeep) + hq0 * Dkq + 8 * min(tid, G * 4 - 1));
+  if constexpr (!FUSED) {
+    g0 = p.g0[hq0 + min(ocol_h, G - 1)];
+    qv.load(static_cast<const T*>(p.qkeep) + hq0 * Dkq + 8 * min(tid, G * 4 - 1));
+  }
   Frag<T> kfA[4], kfB[4];
   Frag<T> vfA[2][DVT], vfB[2][DVT];
   load_step(kfA, vfA, c0);
@@ -1567,13 +1610,16 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsig
   }
 
   // ---- series coefficients and packed query into LDS ---------------------------------------------
+  if constexpr (!FUSED) {
 #pragma unroll
-  for (int i = 0; i < kGLoads; ++i) {
-    const int v4 = tid + i * kBlock;
-    if (v4 < ng4) *reinterpret_cast<f32x4*>(gs_s + (4 * v4 / Mint) * kPitchG + (4 * v4) % Mint) = gv[i];
+    for (int i = 0; i < kGLoads; ++i) {
+      const int v4 = tid + i * kBlock;
+      if (v4 < ng4) *reinterpret_cast<f32x4*>(gs_s + (4 * v4 / Mint) * kPitchG + (4 * v4) % Mint) = gv[i];
+    }
+    if (tid < G * 4) *reinterpret_cast<Frag<T>*>(qk_s + 8 * tid) = qv;
   }
-  if (tid < G * 4) *reinterpret_cast<Frag<T>*>(qk_s + 8 * tid) = qv;
   __syncthreads();
+  if constexpr (FUSED) g0 = g0_s[min(ocol_h, G - 1)];
   // this lane's B operand of the kept-K products: q of its column's head, only in the columns of tile `wave`
   Frag<T> bq;
   bq.load(qk_s + hsafe * Dkq + 8 * q4);
@@ -1812,8 +1858,10 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsig
   __syncthreads();
 
   // record of head h: [max, sum, -, -, acc over the kept dims (16 DVT), r (Mint, V-side order)]
-  const size_t rec_h = static_cast<size_t>(p.Sm) * p.recm;
-  float* rec0 = p.part_m + (hq0 * p.Sm + sm_idx) * p.recm;
+  // (FUSED: the record stays in LDS, past the regions read here)
+  const size_t rec_h = FUSED ? static_cast<size_t>(p.recm) : static_cast<size_t>(sv.Sm) * p.recm;
+  float* rec0 = FUSED ? reinterpret_cast<float*>(smem + fused_lds(p.lds_tab, G, Mint, p.recm, p.recw, p.M, p.Dvc).recm)
+                      : sv.part_m + (hq0 * sv.Sm + sm_idx) * p.recm;
   if (wave == 0 && lane < G) {
     rec0[lane * rec_h + 0] = mstar;
     rec0[lane * rec_h + 1] = lstar;
@@ -1838,8 +1886,8 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, unsig
 template <int CW, int DVT, int GP>
 __global__ __launch_bounds__(kBlock, CW <= 2 ? 2 : 1) void decode_partial_fast(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  if (static_cast<int>(blockIdx.x) < p.Smw) partial_middle_fast<CW, DVT, GP>(p, smem);
-  else if (p.D == 128) partial_full_fast<bf16_t>(p, smem, blockIdx.x - p.Smw);
+  if (static_cast<int>(blockIdx.x) < p.Smw) partial_middle_fast<CW, DVT, GP>(p, call_view(p), smem, blockIdx.y, blockIdx.x);
+  else if (p.D == 128) partial_full_fast<bf16_t>(p, call_view(p), smem, blockIdx.y, blockIdx.x - p.Smw);
   else partial_full_rows<bf16_t>(p, smem, blockIdx.x - p.Smw);
 }
 
@@ -2324,7 +2372,7 @@ __global__ __launch_bounds__(kBlock8, 1) void decode_partial_fast8(DecodeParams 
     partial_middle_fast8<CW, DVT, GP>(p, smem);
   } else {
     if (threadIdx.x >= kBlock) return;   // the full-row path is written for four waves; the others leave before any barrier
-    if (p.D == 128) partial_full_fast<bf16_t>(p, smem, blockIdx.x - p.Smw);
+    if (p.D == 128) partial_full_fast<bf16_t>(p, call_view(p), smem, blockIdx.y, blockIdx.x - p.Smw);
     else partial_full_rows<bf16_t>(p, smem, blockIdx.x - p.Smw);
   }
 }
@@ -2609,7 +2657,8 @@ constexpr int kFin2Batch = 4;    // independent requests per batch: narrow colum
 // kFin2Wide: independent 128-bit requests per batch of the series sums and of the C_v band: 16 when a
 // launch has few workgroups (long record lists, registers to spare), 8 with four workgroups per unit
 template <int kFin2Wide>
-__global__ __launch_bounds__(kFinBlock, kFin2Wide == 16 ? 2 : 4) void decode_finish2(DecodeParams p, int NS) {
+__device__ __forceinline__ void finish2_slice(const DecodeParams& p, const SeqView& sv, const int NS, const int bh,
+                                              const int g, const int sl) {
   constexpr int kNW = kFinBlock / 64;
   constexpr int kSP = kMaxPartials / kFinBlock;
   __shared__ float es[kMaxPartials];
@@ -2619,21 +2668,15 @@ __global__ __launch_bounds__(kFinBlock, kFin2Wide == 16 ? 2 : 4) void decode_fin
   __shared__ int dim_of[FA_MAX_HEAD_DIM];           // output dim of each rank of this slice
   __shared__ float wmax[kNW], wsum[kNW], wsum_m[kNW];
 
-  // workgroup -> (KV head, query head of the group, slice): the G * NS workgroups of a KV head share an XCD
-  const int per_kv = p.G * NS;
-  const int L = blockIdx.x, xcd = L & 7, slot = L >> 3;
-  const int bh = (slot / per_kv) * 8 + xcd;
-  if (bh >= p.B * p.Hkv) return;
-  const int within = slot % per_kv, g = within / NS, sl = within % NS;
   const int b = bh / p.Hkv, hkv = bh % p.Hkv;
   const int hq = b * p.Hq + hkv * p.G + g;
 
-  const int D = p.D, M = p.M, Sm = p.Sm, Sw = p.Sw, S = Sm + Sw, Dvc = p.Dvc, Dvu = p.Dvu, Mint = p.Mint;
+  const int D = p.D, M = p.M, Sm = sv.Sm, Sw = sv.Sw, S = Sm + Sw, Dvc = p.Dvc, Dvu = p.Dvu, Mint = p.Mint;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int Dva = 16 * ((Dvu + 15) / 16);
   const int recm = p.recm, recw = p.recw;
-  const float* pm = p.part_m + static_cast<size_t>(hq) * Sm * recm;
-  const float* pw = p.part_w + static_cast<size_t>(hq) * Sw * recw;
+  const float* pm = sv.part_m + static_cast<size_t>(hq) * Sm * recm;
+  const float* pw = sv.part_w + static_cast<size_t>(hq) * Sw * recw;
   const bool do_cv = Sm > 0 && Dvc > 0;
   // this slice's ranks
   const int cbw = (((Dvc + NS - 1) / NS) + 3) & ~3, cb0 = sl * cbw, cbn = max(0, min(cbw, Dvc - cb0));
@@ -2851,6 +2894,397 @@ __global__ __launch_bounds__(kFinBlock, kFin2Wide == 16 ? 2 : 4) void decode_fin
   }
 }
 
+template <int kFin2Wide>
+__global__ __launch_bounds__(kFinBlock, kFin2Wide == 16 ? 2 : 4) void decode_finish2(DecodeParams p, int NS) {
+  // workgroup -> (KV head, query head of the group, slice): the G * NS workgroups of a KV head share an XCD
+  const int per_kv = p.G * NS;
+  const int L = blockIdx.x, xcd = L & 7, slot = L >> 3;
+  const int bh = (slot / per_kv) * 8 + xcd;
+  if (bh >= p.B * p.Hkv) return;
+  const int within = slot % per_kv;
+  finish2_slice<kFin2Wide>(p, call_view(p), NS, bh, within / NS, within % NS);
+}
+
+// ---------------------------------------------------------------------------
+// 4. the whole call in one launch: one workgroup per (sequence, KV head)
+// ---------------------------------------------------------------------------
+// With many (sequence, KV head) pairs nothing has to be split to fill the chip, and a call of
+// three launches is mostly launch latency and dependent round trips.  Here a workgroup runs the
+// phases of its pair back to back - series coefficients, all middle rows as one chunk, the
+// full-width rows, the merge with diag(w) C_v - and the pieces of state that the three-launch
+// form passes through the workspace (g, packed q, one record per phase) stay with the workgroup
+// that wrote them (same compute unit, same first-level cache).  Sequences may differ in length:
+// a workgroup takes its own counts from seq_n / seq_w.
+// g = diag(w) C_k q[D^kc], the constant-term coefficient and q at the kept K dims, formed by the
+// workgroup that uses them and left in the LDS places the middle-row phase reads.  Four threads
+// share a row of C_k (interleaved 128-bit vectors); the rows of all NP passes of 64 rows are
+// requested before anything is waited for.  The query at the compressed dims is staged at the
+// start of the exchange region, which the middle-row phase only writes after its own barrier.
+template <int NP>
+__device__ __forceinline__ void fused_coeffs(const DecodeParams& p, unsigned char* smem, const int bh) {
+  using T = bf16_t;
+  constexpr int D = 128, kV = D / 16;          // 128-bit vectors of a row per thread (compressed dims <= 124)
+  constexpr int Mint = (NP - 1) * 64, kPitchG = Mint + 32;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int Dkc = p.Dkc, G = p.G, M = p.M;
+  const int row = tid >> 2, seg = tid & 3, c4n = Dkc / 4;
+  float* qc = reinterpret_cast<float*>(smem);                    // [G][Dkc]
+  float* gs_s = reinterpret_cast<float*>(smem + p.lds_tab);      // [G][Mint + 32]
+  T* qk_s = reinterpret_cast<T*>(gs_s + G * kPitchG);            // [G][32]
+  float* g0_s = reinterpret_cast<float*>(qk_s + G * 32);         // [G]
+
+  const float* ck0 = p.ck + static_cast<size_t>(bh) * M * Dkc;
+  f32x4 cv4[NP][kV];
+#pragma unroll
+  for (int ps = 0; ps < NP; ++ps) {
+    const float* ckr = ck0 + static_cast<size_t>(min(row + 64 * ps, M - 1)) * Dkc;
+#pragma unroll
+    for (int i = 0; i < kV; ++i)
+      if (4 * i < c4n) cv4[ps][i] = *reinterpret_cast<const f32x4*>(ckr + 4 * min(seg + 4 * i, c4n - 1));
+  }
+  uint64_t kbal[4];
+  mask_ballots(p.kmask + static_cast<size_t>(bh) * D, D, lane, kbal);
+  const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
+  const T* q = static_cast<const T*>(p.q) + hq0 * D;
+  const int nqe = G * D;   // <= 512
+  T qe[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) qe[i] = q[min(tid + i * kBlock, nqe - 1)];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int it = tid + i * kBlock;
+    if (it < nqe) {
+      const int h = it >> 7, d = it & 127;
+      const int r = dim_rank(kbal, d);
+      if (r < 0) qc[h * Dkc + (-r - 1)] = to_f32(qe[i]);
+      else qk_s[h * 32 + r] = qe[i];
+    }
+  }
+  {
+    const int npad = 32 - p.Dku;
+    if (tid < G * npad) qk_s[(tid / npad) * 32 + p.Dku + tid % npad] = T{};
+  }
+  __syncthreads();
+#pragma unroll
+  for (int ps = 0; ps < NP; ++ps) {
+    const int m = row + 64 * ps;
+    const float w = (m < M) ? basis_weight((m + 1) / 2, p.T) : 0.0f;
+    for (int h = 0; h < G; ++h) {
+      const float* qh = qc + h * Dkc;
+      float acc = 0.0f;
+#pragma unroll
+      for (int i = 0; i < kV; ++i) {
+        if (4 * i < c4n) {
+          const int c4 = seg + 4 * i;
+          const f32x4 qv = *reinterpret_cast<const f32x4*>(qh + 4 * min(c4, c4n - 1));
+          const f32x4 c = cv4[ps][i];
+          const float d4 = (c[0] * qv[0] + c[1] * qv[1]) + (c[2] * qv[2] + c[3] * qv[3]);
+          acc += (c4 < c4n) ? d4 : 0.0f;
+        }
+      }
+      acc += __shfl_xor(acc, 1, kWave);
+      acc += __shfl_xor(acc, 2, kWave);
+      if (seg == 0 && m <= Mint) {
+        if (m == 0) g0_s[h] = acc * w;
+        else gs_s[h * kPitchG + (m - 1)] = acc * w;
+      }
+    }
+  }
+  // (the barrier that publishes g sits in the middle-row phase, after its table build)
+}
+
+// All full-width rows of a pair in one pass: wave w takes rows 256 s + 64 w .. + 63 of every chunk
+// s, keeps a running (max, sum, accumulator) of its own across the chunks, and requests the rows
+// of the next chunk as soon as the registers of the current one are free.  The waves meet once,
+// at the end, and leave ONE record.  Same arithmetic per chunk as partial_full_fast.
+template <typename T>
+__device__ __forceinline__ void fused_full_rows(const DecodeParams& p, const SeqView& sv, unsigned char* smem,
+                                                const int bh, const unsigned lds_recw) {
+  static_assert(sizeof(T) == 2, "16-bit elements");
+  constexpr int D = 128, kH = 4;
+  const int b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int G = p.G;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q4 = lane >> 4, r16 = lane & 15;
+  const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
+  const int W = sv.W, jlast = W - 1;
+  const int nch = (W + kWChunk - 1) / kWChunk;
+  const int jvis = W - p.Tq + r16 / p.Gq;
+
+  float* pw = reinterpret_cast<float*>(smem) + wave * kWRows * kH;          // [64 rows][4 columns] probabilities
+  float* red = reinterpret_cast<float*>(smem) + kWaves * kWRows * kH;      // [waves][4 columns][128 dims]
+  float* wm = red + kWaves * kH * D;                                        // [waves][4] maxima
+  float* wl = wm + kWaves * kH;                                             // [waves][4] sums
+  float* wa = wl + kWaves * kH;                                             // [waves][4] rescale factors of a chunk
+
+  const T* kbase = static_cast<const T*>(p.k_full) + bh * p.full_stride;
+  const T* vbase = static_cast<const T*>(p.v_full) + bh * p.full_stride;
+  const int dc = lane & 15, rg = lane >> 4;
+  Frag<T> ka[4][kRB], vf[16];
+  auto load_k = [&](int s) {
+    const int jw = s * kWChunk + wave * kWRows;
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) {
+      const T* krow = kbase + static_cast<int64_t>(min(jw + 16 * rb + r16, jlast)) * D + 8 * q4;
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) ka[cc][rb].load(krow + cc * 32);
+    }
+  };
+  auto load_v = [&](int s) {
+    const int jw = s * kWChunk + wave * kWRows;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) vf[i].load(vbase + static_cast<int64_t>(min(jw + rg + 4 * i, jlast)) * D + dc * 8);
+  };
+  load_k(0);
+  Frag<T> qb[4];
+  {
+    const T* q = static_cast<const T*>(p.q) + (hq0 + min(r16, G - 1)) * D + 8 * q4;
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) qb[cc].load(q + cc * 32);
+  }
+  load_v(0);
+  if (r16 >= G) {
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) qb[cc].zero();
+  }
+  float m_run = -INFINITY, l_run = 0.0f;
+  float acc[kH][8];
+#pragma unroll
+  for (int h = 0; h < kH; ++h)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
+
+  for (int s = 0; s < nch; ++s) {
+    const int jw = s * kWChunk + wave * kWRows;
+    const int nw = max(0, min(kWRows, W - jw));
+    f32x4 sacc[kRB];
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+      for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], ka[cc][rb], qb[cc]);
+    load_k(min(s + 1, nch - 1));   // (the last chunk is asked for once more: never used, never waited for alone)
+    float m_w = -INFINITY;
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int r = 16 * rb + 4 * q4 + v;
+        const float scv = (r < nw && r16 < G && jw + r <= jvis) ? sacc[rb][v] * p.scale : -INFINITY;
+        sacc[rb][v] = scv;
+        m_w = fmaxf(m_w, scv);
+      }
+    m_w = cross_row_max(m_w);
+    const float m_new = fmaxf(m_run, m_w);
+    const float m_ref = (m_new == -INFINITY) ? 0.0f : m_new;
+    const float alpha = __expf(m_run - m_ref);   // m_run = -inf -> 0
+    float l_w = 0.0f;
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const float e = __expf(sacc[rb][v] - m_ref);   // masked rows hold -inf -> 0
+        l_w += e;
+        if (r16 < kH) pw[(16 * rb + 4 * q4 + v) * kH + r16] = e;
+      }
+    l_w = cross_row_sum(l_w);
+    l_run = l_run * alpha + l_w;
+    m_run = m_new;
+    if (lane < kH) wa[wave * kH + lane] = alpha;
+    // written by this wave, read by this wave: the LDS operations of a wave complete in order
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const f32x4 al = *reinterpret_cast<const f32x4*>(wa + wave * kH);
+#pragma unroll
+    for (int h = 0; h < kH; ++h)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[h][e] *= al[h];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int r = rg + 4 * i;
+      const f32x4 p4 = *reinterpret_cast<const f32x4*>(pw + r * kH);   // rows past the end hold zeros
+      float x[8];
+      unpack8(vf[i], x);
+#pragma unroll
+      for (int h = 0; h < kH; ++h)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] += p4[h] * x[e];
+    }
+    load_v(min(s + 1, nch - 1));
+    // the next chunk's probabilities overwrite pw: this wave's reads above come first (in-order LDS)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+  // the four row groups of the wave meet in its first 16 lanes
+#pragma unroll
+  for (int h = 0; h < kH; ++h)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[h][e] = cross_row_sum(acc[h][e]);
+  if (rg == 0) {
+#pragma unroll
+    for (int h = 0; h < kH; ++h) {
+      float* dst = red + (wave * kH + h) * D + dc * 8;
+      *reinterpret_cast<f32x4*>(dst) = f32x4{acc[h][0], acc[h][1], acc[h][2], acc[h][3]};
+      *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[h][4], acc[h][5], acc[h][6], acc[h][7]};
+    }
+  }
+  if (lane < kH) {
+    wm[wave * kH + lane] = m_run;
+    wl[wave * kH + lane] = l_run;
+  }
+  __syncthreads();
+  if (tid < kH * (D / 4)) {
+    const int h = tid / (D / 4), d4 = tid % (D / 4);
+    if (h < G) {
+      float ms = wm[h];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) ms = fmaxf(ms, wm[w * kH + h]);
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      float l = 0.0f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float mw = wm[w * kH + h];
+        const float f = (mw == -INFINITY) ? 0.0f : __expf(mw - ms);
+        l += f * wl[w * kH + h];
+        v += f * *reinterpret_cast<const f32x4*>(red + (w * kH + h) * D + 4 * d4);
+      }
+      float* rec = reinterpret_cast<float*>(smem + lds_recw) + h * p.recw;   // past everything this phase uses
+      *reinterpret_cast<f32x4*>(rec + 4 + 4 * d4) = v;
+      if (d4 == 0) {
+        rec[0] = ms;
+        rec[1] = l;
+      }
+    }
+  }
+}
+
+// C_v of the pair goes straight from global memory into LDS (no registers, nothing waits for it
+// here): every wave copies 1 KB blocks, lane i of a block supplying bytes 16 i .. 16 i + 15.  The
+// last block may reach past the matrix: its lanes re-read the last vector (the stash is padded).
+__device__ __forceinline__ void fused_stash_cv(const DecodeParams& p, unsigned char* smem, const int bh,
+                                               const unsigned lds_cv) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const unsigned bytes = static_cast<unsigned>(p.M) * p.Dvc * 4u;
+  const unsigned nblk = (bytes + 1023u) >> 10;
+  const char* src = reinterpret_cast<const char*>(p.cv + static_cast<size_t>(bh) * p.M * p.Dvc);
+  for (unsigned blk = wave; blk < nblk; blk += kWaves) {
+    const unsigned off = min(blk * 1024u + 16u * lane, bytes - 16u);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + off),
+                                     (__attribute__((address_space(3))) void*)(smem + lds_cv + blk * 1024u), 16, 0, 0);
+  }
+}
+
+// Merge of the pair's two records (middle rows, full-width rows) with diag(w) C_v, all out of
+// LDS: out[d] = (e_m (C_v^T diag(w) r | kept accumulator) + e_w acc_w[d]) / (e_m l_m + e_w l_w).
+__device__ __forceinline__ void fused_finish(const DecodeParams& p, unsigned char* smem, const int bh,
+                                             const FusedLds& L, const bool has_m, const bool has_w) {
+  constexpr int D = 128;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int b = bh / p.Hkv, hkv = bh % p.Hkv;
+  const int G = p.G, M = p.M, Dvc = p.Dvc, Mint = p.Mint;
+  const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
+  const float* recm = reinterpret_cast<const float*>(smem + L.recm);
+  const float* recw = reinterpret_cast<const float*>(smem + L.recw);
+  const float* cv_s = reinterpret_cast<const float*>(smem + L.cv);
+  const int Dva = 16 * ((p.Dvu + 15) / 16);
+  const int pitch_r = M + 4;
+  float* rr = reinterpret_cast<float*>(smem);                       // [G][M + 4] weighted series sums, basis order
+  f32x4* part4 = reinterpret_cast<f32x4*>(smem + 8192);             // [G][row groups][column quads]
+
+  uint64_t vbal[4];
+  mask_ballots(p.vmask + static_cast<size_t>(bh) * D, D, lane, vbal);
+
+  const bool do_cv = has_m && Dvc > 0;
+  const int nq = max(Dvc / 4, 1), ngrp = kBlock / nq;
+  if (do_cv) {
+    for (int it = tid; it < G * Mint; it += kBlock) {   // record order: 32 * chunk + 16 * (cos | sin) + order
+      const int h = it / Mint, ig = it - h * Mint;
+      const int n = 16 * (ig >> 5) + (ig & 15) + 1, cs = (ig >> 4) & 1;
+      const int mm = 2 * n - 1 + cs;
+      if (mm < M) rr[h * pitch_r + mm] = recm[h * p.recm + 4 + Dva + ig] * basis_weight(n, p.T);
+    }
+    if (tid < G) rr[tid * pitch_r] = recm[tid * p.recm + 1] * basis_weight(0, p.T);   // the sum of the probabilities
+  }
+  // (the waits of this barrier also cover the stash: it was requested before the middle-row phase)
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (do_cv) {
+    const int cq = tid % nq, rg = tid / nq;
+    f32x4 o4[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) o4[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (rg < ngrp) {
+      for (int mm = rg; mm < M; mm += ngrp) {
+        const f32x4 c = *reinterpret_cast<const f32x4*>(cv_s + mm * Dvc + 4 * cq);
+#pragma unroll
+        for (int h = 0; h < 4; ++h)
+          if (h < G) o4[h] += rr[h * pitch_r + mm] * c;
+      }
+#pragma unroll
+      for (int h = 0; h < 4; ++h)
+        if (h < G) part4[(h * ngrp + rg) * nq + cq] = o4[h];
+    }
+  }
+  __syncthreads();
+  if (tid < D) {
+    const int r = dim_rank(vbal, tid);
+    for (int h = 0; h < G; ++h) {
+      const float mm_ = has_m ? recm[h * p.recm + 0] : -INFINITY, lm = has_m ? recm[h * p.recm + 1] : 0.0f;
+      const float mw = has_w ? recw[h * p.recw + 0] : -INFINITY, lw = has_w ? recw[h * p.recw + 1] : 0.0f;
+      const float mx = fmaxf(mm_, mw);
+      const float em = (mm_ == -INFINITY) ? 0.0f : __expf(mm_ - mx);
+      const float ew = (mw == -INFINITY) ? 0.0f : __expf(mw - mx);
+      float v = 0.0f;
+      if (has_m) {
+        if (r < 0) {
+          const int c = -r - 1;
+          const float* src = reinterpret_cast<const float*>(part4 + h * ngrp * nq) + c;   // column c = quad c / 4, element c % 4
+          float a = 0.0f;
+          for (int gi = 0; gi < ngrp; ++gi) a += src[4 * gi * nq];
+          v = em * a;
+        } else {
+          v = em * recm[h * p.recm + 4 + r];
+        }
+      }
+      if (has_w) v += ew * recw[h * p.recw + 4 + tid];
+      p.out[(hq0 + h) * D + tid] = v / (em * lm + ew * lw);
+    }
+  }
+}
+
+template <int CW, int DVT, int GP>
+__global__ __launch_bounds__(kBlock, 1) void decode_fused(DecodeParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using T = bf16_t;
+  constexpr int Mint = kWaves * CW * 32;
+  const int bh = blockIdx.x, b = bh / p.Hkv;
+  SeqView sv;
+  sv.N = p.seq_n ? min(max(p.seq_n[b], 0), p.N) : p.N;
+  sv.W = p.seq_w ? min(max(p.seq_w[b], 0), p.W) : p.W;
+  sv.Sm = sv.N > 0 ? 1 : 0;
+  sv.Sw = sv.W > 0 ? 1 : 0;
+  sv.chunk_m = max(sv.N, 1);
+  sv.part_m = nullptr;   // the records of both phases stay in LDS
+  sv.part_w = nullptr;
+  const FusedLds L = fused_lds(p.lds_tab, p.G, Mint, p.recm, p.recw, p.M, p.Dvc);
+  if (sv.N > 0) {
+    fused_coeffs<2 * CW + 1>(p, smem, bh);
+    if (p.Dvc > 0) fused_stash_cv(p, smem, bh, L.cv);
+    partial_middle_fast<CW, DVT, GP, true>(p, sv, smem, bh, 0);
+  }
+  if (sv.W > 0) {
+    __syncthreads();
+    fused_full_rows<T>(p, sv, smem, bh, L.recw);
+  }
+  __syncthreads();
+  fused_finish(p, smem, bh, L, sv.N > 0, sv.W > 0);
+}
+
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
@@ -2860,7 +3294,9 @@ struct DecodePlan {
   int Swp;        // chunks of full-width rows that run inside the middle-row launch
   unsigned lds_window;   // dynamic LDS of a full-width-row workgroup
   int fast;   // 0: general middle-row kernel; 4 / 8: the specialised one with that many waves
+  bool fused; // the whole call as one launch (one workgroup per (sequence, KV head))
   unsigned lds_tab, lds_total;
+  unsigned lds_fused;    // dynamic LDS of a workgroup of the one-launch form
   size_t off_gs, off_g0, off_qk, off_pm, off_pw, total;
 };
 
@@ -2899,8 +3335,18 @@ static int default_steps_per_chunk(int B, int Hkv, int N, int step, int cw, int 
   return static_cast<int>(spc);
 }
 
+// shapes the one-launch form covers: those of the specialised four-wave middle-row kernel whose
+// other phases have a streaming form (head dim 128, compressed counts in multiples of 4)
+static bool fused_shape(int dtype, int Hq, int Hkv, int D, int Dkc, int Dvc, int M, int N) {
+  const int G = Hq / Hkv, Dku = D - Dkc, Dvu = D - Dvc;
+  const int cw = series_chunks_per_wave(M);
+  return dtype == FA_BF16 && D == 128 && G <= 4 && cw >= 1 && cw <= 2 && N > 0 && Dku > 0 && Dku <= 32 &&
+         Dvu > 0 && Dvu <= 32 && Dkc > 0 && (Dkc & 3) == 0 && (Dvc & 3) == 0;
+}
+constexpr int kFusedMinPairs = 192;   // (sequence, KV head) pairs from which the one-launch form is the default
+
 static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, int Dkc, int Dvc, int M,
-                      int N, int W, int num_splits) {
+                      int N, int W, int num_splits, int fused_mode = 0) {   // fused_mode: 0 by shape, -1 never
   const int G = Hq / Hkv;
   pl.Gp = 1;
   while (pl.Gp < G) pl.Gp *= 2;
@@ -2910,6 +3356,12 @@ static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, 
   pl.Mint = kWaves * pl.cw * 32;
   const int step = pl.KT * kTJ;
   pl.Sw = (W + kWChunk - 1) / kWChunk;
+  pl.fused = fused_shape(dtype, Hq, Hkv, D, Dkc, Dvc, M, N) &&
+             fused_mode >= 0 && (num_splits == 1 || (num_splits == 0 && static_cast<long>(B) * Hkv >= kFusedMinPairs));
+  if (pl.fused) {   // one middle chunk and one record of full-width rows per (sequence, KV head)
+    num_splits = 1;
+    pl.Sw = W > 0 ? 1 : 0;
+  }
   // full-width rows that ride in the launch of the series coefficients (see Swp below) take no
   // compute unit away from the middle rows
   const bool window_rides = dtype == FA_BF16 && N > 0 && pl.cw == 4 && G <= 4 && D - Dkc > 0 && D - Dkc <= 32 &&
@@ -2956,17 +3408,24 @@ static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, 
   const unsigned xchg = pl.fast == 8 ? kXs8Bytes + 8 * 1024 : kXchgBytes;
   const unsigned tab = redb > xchg ? redb : xchg;
   pl.lds_tab = (tab + 255u) & ~255u;
-  const unsigned mid = pl.lds_tab + G * (pl.Mint + 32) * 4 + G * Dkq * ts;
+  const unsigned mid = pl.lds_tab + G * (pl.Mint + 32) * 4 + G * Dkq * ts + 64;   // (+ constant-term coefficients)
   const unsigned wpath = 16 * FA_MAX_HEAD_DIM * ts + kWChunk * kMaxG * 4 + kWaves * 512 * 4 * 4;   // q, p tiles, partial sums
   // the specialised full-row path keeps only probabilities, per-wave sums and statistics there
   const bool wfast = dtype == FA_BF16 && D == 128 && G <= 4;
-  pl.lds_window = wfast ? (kWaves * kWRows * 4 + kWaves * 4 * 128 + 64) * 4 : wpath;
+  pl.lds_window = wfast ? (kWaves * kWRows * 4 + kWaves * 4 * 128 + 64) * 4 : wpath;   // (64: maxima, sums, factors)
   // The eight-wave middle-row workgroups take a compute unit each, so full-width-row workgroups in their
   // launch would run as a tail behind them: they run in the launch that forms the series coefficients
   // instead (independent work that fills the chip while that chain of round trips is in flight).  With
   // two middle-row workgroups per unit the full-width rows overlap with them and stay where they are
   // (measured: moving them costs 1.5 us on 32 K tokens, 12 us on 8 x 4 K MHA).
   pl.Swp = (pl.fast == 8 && Dkc > 0 && (Dkc & 3) == 0) ? 0 : pl.Sw;   // (= window_rides)
+  {
+    const FusedLds L = fused_lds(pl.lds_tab, G, pl.Mint, pl.recm, pl.recw, M, Dvc);
+    pl.lds_fused = L.total > pl.lds_window ? L.total : pl.lds_window;
+    // a stash of C_v that does not fit next to the other regions: the three-launch form
+    if (pl.fused && pl.lds_fused > kMaxDynLds)
+      return make_plan(pl, dtype, B, Hq, Hkv, D, Dkc, Dvc, M, N, W, num_splits, -1);
+  }
   const unsigned t = mid > wpath ? mid : wpath;
   pl.lds_total = (t + 255u) & ~255u;
   if (pl.lds_total > kMaxDynLds) return false;
@@ -3076,10 +3535,41 @@ static int launch_partial_fast(const DecodeParams& p, const DecodePlan& pl, hipS
                               : launch_partial_fast8_one<2, 2, 4>(p, pl.lds_total, st, tm));
 }
 
+template <int CW, int DVT, int GP>
+static int launch_fused_one(const DecodeParams& p, unsigned lds, hipStream_t st, KernelTimers* tm) {
+  auto kern = decode_fused<CW, DVT, GP>;
+  if (lds > 32u * 1024u &&
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          static_cast<int>(lds)) != hipSuccess)
+    return FA_ERR_HIP;
+  FA_LAUNCH_TIMED(tm, 1, kern, dim3(p.B * p.Hkv), dim3(kBlock), lds, st, p);
+  return FA_OK;
+}
+
+static int launch_fused(const DecodeParams& p, const DecodePlan& pl, hipStream_t st, KernelTimers* tm) {
+  const hipError_t prior = hipPeekAtLastError();
+  const bool one_tile = p.Dvu <= 16, one_head = p.G == 1;
+  const unsigned lds = pl.lds_fused;
+  int rc;
+#define FA_FUSED(CW_)                                                                  \
+  rc = one_tile ? (one_head ? launch_fused_one<CW_, 1, 1>(p, lds, st, tm)               \
+                            : launch_fused_one<CW_, 1, 4>(p, lds, st, tm))              \
+                : (one_head ? launch_fused_one<CW_, 2, 1>(p, lds, st, tm)               \
+                            : launch_fused_one<CW_, 2, 4>(p, lds, st, tm))
+  if (pl.cw == 1) FA_FUSED(1);
+  else FA_FUSED(2);
+#undef FA_FUSED
+  if (rc != FA_OK) return rc;
+  return (hipPeekAtLastError() == hipSuccess || prior != hipSuccess) ? FA_OK : FA_ERR_HIP;
+}
+
 // tm (optional): per-kernel event pairs, for fa_decode_timed
 template <typename T>
 static int launch_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_t st, KernelTimers* tm) {
   const int BH = p.B * p.Hkv;
+  if constexpr (sizeof(T) == 2) {
+    if (pl.fused) return launch_fused(p, pl, st, tm);
+  }
   const hipError_t prior = hipPeekAtLastError();
   if (p.Sm > 0 && p.Dkc > 0 && (p.Dkc & 3) == 0) {
     const bool wide = static_cast<long>(BH) * (p.Mint / 64 + 1) >= 256;
@@ -3223,6 +3713,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   p.Sw = pl.Sw; p.Sm = pl.Sm; p.chunk_m = pl.chunk_m; p.recm = pl.recm; p.recw = pl.recw;
   p.cpw = pl.cpw; p.Smw = pl.Smw; p.Swp = pl.Swp; p.nprep = 0;
   p.lds_tab = pl.lds_tab;
+  p.seq_n = nullptr; p.seq_w = nullptr; p.Sw_rec = pl.Sw;
   p.scale = scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(D));
   p.ph_scale = 4294967296.0 / static_cast<double>(T);
   char* ws = static_cast<char*>(workspace);
