@@ -93,6 +93,7 @@ struct DecodeParams {
   const int32_t* seq_n;   // [B] middle rows of each sequence (<= N), or null: N for all
   const int32_t* seq_w;   // [B] full-width rows of each sequence (<= W), or null: W for all
   int Sw_rec;       // full-row records reserved per query head (= Sw of the longest sequence)
+  int wrb;          // 16-row blocks per wave of a full-width-row workgroup: 4 (256 rows per workgroup) or 1 (64)
 };
 
 // What a workgroup uses of one sequence: its row counts, the chunking that follows from them and
@@ -1284,7 +1285,8 @@ __device__ __forceinline__ float cross_row_sum(float v) {
 // needs from global memory - its 64 K rows, its 64 V rows and the queries, which go straight into
 // B operands - is requested at the start, the softmax of a wave stays inside the wave, and the
 // waves meet once, at the end.
-template <typename T>
+// RB: 16-row blocks per wave (4: 256 rows per workgroup; 1: 64 rows, for launches with few workgroups)
+template <typename T, int RB = kRB>
 __device__ __forceinline__ void partial_full_fast(const DecodeParams& p, const SeqView& sv, unsigned char* smem, const int bh, int s) {
   static_assert(sizeof(T) == 2, "16-bit elements");
   constexpr int D = 128, kH = 4;                        // head dim, query columns
@@ -1294,8 +1296,9 @@ __device__ __forceinline__ void partial_full_fast(const DecodeParams& p, const S
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int q4 = lane >> 4, r16 = lane & 15;
   const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
-  const int jw = s * kWChunk + wave * kWRows;
-  const int nw = max(0, min(kWRows, sv.W - jw));
+  constexpr int kRowsW = 16 * RB;                      // rows per wave
+  const int jw = (s * kWaves + wave) * kRowsW;
+  const int nw = max(0, min(kRowsW, sv.W - jw));
   const int jlast = sv.W - 1;
   const int jvis = sv.W - p.Tq + r16 / p.Gq;             // last row the query token of column r16 may see
 
@@ -1307,9 +1310,9 @@ __device__ __forceinline__ void partial_full_fast(const DecodeParams& p, const S
   // ---- global operands ------------------------------------------------------------------------
   const T* kbase = static_cast<const T*>(p.k_full) + bh * p.full_stride;
   const T* vbase = static_cast<const T*>(p.v_full) + bh * p.full_stride;
-  Frag<T> ka[4][kRB];
+  Frag<T> ka[4][RB];
 #pragma unroll
-  for (int rb = 0; rb < kRB; ++rb) {
+  for (int rb = 0; rb < RB; ++rb) {
     const T* krow = kbase + static_cast<int64_t>(min(jw + 16 * rb + r16, jlast)) * D + 8 * q4;
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) ka[cc][rb].load(krow + cc * 32);
@@ -1322,27 +1325,27 @@ __device__ __forceinline__ void partial_full_fast(const DecodeParams& p, const S
   }
   // V rows of this lane: 8 dims (dc) of rows rg, rg + 4, ...
   const int dc = lane & 15, rg = lane >> 4;
-  Frag<T> vf[16];
+  Frag<T> vf[4 * RB];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) vf[i].load(vbase + static_cast<int64_t>(min(jw + rg + 4 * i, jlast)) * D + dc * 8);
+  for (int i = 0; i < 4 * RB; ++i) vf[i].load(vbase + static_cast<int64_t>(min(jw + rg + 4 * i, jlast)) * D + dc * 8);
 
   // ---- scores of the wave's 64 rows: lane (column r16, q4) gets rows 16 rb + 4 q4 + v -----------
   if (r16 >= G) {
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) qb[cc].zero();
   }
-  f32x4 sacc[kRB];
+  f32x4 sacc[RB];
 #pragma unroll
-  for (int rb = 0; rb < kRB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int rb = 0; rb < RB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int cc = 0; cc < 4; ++cc)
 #pragma unroll
-    for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], ka[cc][rb], qb[cc]);
+    for (int rb = 0; rb < RB; ++rb) mma_k32(sacc[rb], ka[cc][rb], qb[cc]);
 
   // ---- softmax over the wave's rows, per column ---------------------------------------------------
   float m_w = -INFINITY;
 #pragma unroll
-  for (int rb = 0; rb < kRB; ++rb)
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int r = 16 * rb + 4 * q4 + v;
@@ -1354,7 +1357,7 @@ __device__ __forceinline__ void partial_full_fast(const DecodeParams& p, const S
   const float m_ref = (m_w == -INFINITY) ? 0.0f : m_w;
   float l_w = 0.0f;
 #pragma unroll
-  for (int rb = 0; rb < kRB; ++rb)
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const float e = __expf(sacc[rb][v] - m_ref);   // masked rows hold -inf -> 0
@@ -1379,7 +1382,7 @@ __device__ __forceinline__ void partial_full_fast(const DecodeParams& p, const S
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
+  for (int i = 0; i < 4 * RB; ++i) {
     const int r = rg + 4 * i;
     const f32x4 p4 = *reinterpret_cast<const f32x4*>(pw + r * kH);   // rows past the end hold zeros
     float x[8];
@@ -1442,8 +1445,12 @@ __global__ __launch_bounds__(kBlock) void decode_prepare_window(DecodeParams p) 
   } else {
     const int s = blockIdx.x - p.nprep;
     if constexpr (sizeof(T) == 2) {
-      if (p.D == 128 && p.G <= 4) partial_full_fast<T>(p, call_view(p), smem, blockIdx.y, s);
-      else partial_full_rows<T>(p, smem, s);
+      if (p.D == 128 && p.G <= 4) {
+        if (p.wrb == 1) partial_full_fast<T, 1>(p, call_view(p), smem, blockIdx.y, s);
+        else partial_full_fast<T>(p, call_view(p), smem, blockIdx.y, s);
+      } else {
+        partial_full_rows<T>(p, smem, s);
+      }
     } else {
       partial_full_rows<T>(p, smem, s);
     }
@@ -3290,6 +3297,7 @@ __global__ __launch_bounds__(kBlock, 1) void decode_fused(DecodeParams p) {
 // ---------------------------------------------------------------------------
 struct DecodePlan {
   int Gp, KT, Mint, cw, Sw, Sm, chunk_m, recm, recw;
+  int wrb;        // 16-row blocks per wave of a full-width-row workgroup
   int cpw, Smw;   // middle chunks per workgroup, middle workgroups per (sequence, KV head)
   int Swp;        // chunks of full-width rows that run inside the middle-row launch
   unsigned lds_window;   // dynamic LDS of a full-width-row workgroup
@@ -3366,6 +3374,14 @@ static bool make_plan(DecodePlan& pl, int dtype, int B, int Hq, int Hkv, int D, 
   // compute unit away from the middle rows
   const bool window_rides = dtype == FA_BF16 && N > 0 && pl.cw == 4 && G <= 4 && D - Dkc > 0 && D - Dkc <= 32 &&
                             D - Dvc > 0 && D - Dvc <= 32 && Dkc > 0 && (Dkc & 3) == 0;
+  // ... and when they would be few workgroups of 256 rows each, every one of them bound by what a single
+  // compute unit can keep in flight, they go in workgroups of 64 rows instead (four times as many units)
+  pl.wrb = 4;
+  // (inside the middle-row launch they are better off as few long workgroups: 32 K tokens 13.6 -> 16.6 us with 64-row ones)
+  if (window_rides && D == 128 && static_cast<long>(B) * Hkv * pl.Sw < 128 && (W + 63) / 64 <= kMaxPartials / 2) {
+    pl.wrb = 1;
+    pl.Sw = (W + 63) / 64;
+  }
   if (N > 0) {
     int chunk;
     if (num_splits > 0) chunk = round_up((N + num_splits - 1) / num_splits, step);
@@ -3713,7 +3729,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   p.Sw = pl.Sw; p.Sm = pl.Sm; p.chunk_m = pl.chunk_m; p.recm = pl.recm; p.recw = pl.recw;
   p.cpw = pl.cpw; p.Smw = pl.Smw; p.Swp = pl.Swp; p.nprep = 0;
   p.lds_tab = pl.lds_tab;
-  p.seq_n = nullptr; p.seq_w = nullptr; p.Sw_rec = pl.Sw;
+  p.seq_n = nullptr; p.seq_w = nullptr; p.Sw_rec = pl.Sw; p.wrb = pl.wrb;
   p.scale = scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(D));
   p.ph_scale = 4294967296.0 / static_cast<double>(T);
   char* ws = static_cast<char*>(workspace);
