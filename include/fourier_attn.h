@@ -140,7 +140,12 @@ size_t fa_compress_workspace_bytes_for(int dtype, int B, int H, int N, int D, in
  *   scale       softmax scale; <= 0 selects 1/sqrt(D).
  *   num_splits  token-axis chunks per (sequence, KV head) for the middle rows;
  *               0 lets the library choose.  The result does not depend on it
- *               beyond fp32 summation order.
+ *               beyond fp32 summation order.  With one chunk (num_splits = 1, or
+ *               the library's choice from 192 (sequence, KV head) pairs on) shapes
+ *               of the specialised bf16 kernel (D = 128, at most four query heads
+ *               per KV head, 1 .. 32 kept dims on both sides, M <= 256, Dkc and Dvc
+ *               multiples of 4) run as ONE launch: a workgroup per pair forms its
+ *               series coefficients, walks its rows and merges, all in LDS.
  *   out         [B,Hq,D] fp32.
  *   workspace   at least fa_decode_workspace_bytes(...) bytes, 256-byte aligned.
  *
@@ -160,6 +165,35 @@ int fa_decode(const void* q, int dtype,
 
 size_t fa_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int Dkc, int Dvc,
                                  int M, int N, int W, int num_splits);
+
+/*
+ * fa_decode_varlen -- fa_decode for a batch whose sequences stand at different positions
+ * (paper, Eq. 5: every sequence advances its own cache; batched serving).
+ *
+ * Same arguments, layouts, limits and workspace as fa_decode, with
+ *   N_max, seq_n   seq_n: device pointer to B int32; sequence b has seq_n[b] middle rows (the first
+ *                  seq_n[b] tokens of its k_keep / v_keep slabs).  Values are clamped into
+ *                  [0, N_max]; N_max takes the place of N in every size, stride and workspace
+ *                  rule.  seq_n = NULL: N_max rows for all.
+ *   W_max, seq_w   the same for the full-width rows (rows 0 .. seq_w[b] - 1 of the k_full / v_full
+ *                  slabs).  seq_w = NULL: W_max rows for all.
+ * The launch plan is that of fa_decode(N = N_max, W = W_max): chunks past a sequence's rows leave
+ * empty records; in the one-launch form (see num_splits) every workgroup simply walks its own
+ * counts.  A sequence without any row gets out = 0.  The lists are read by the kernels, not by
+ * the host: they may be written by earlier work on the same stream.
+ */
+int fa_decode_varlen(const void* q, int dtype,
+                     int B, int Hq, int Hkv, int D,
+                     const float* ck, const uint8_t* kmask, int Dkc,
+                     const float* cv, const uint8_t* vmask, int Dvc,
+                     int M, int T, int t0, int N_max, const int32_t* seq_n,
+                     const void* k_keep, int64_t kk_stride_bh,
+                     const void* v_keep, int64_t vk_stride_bh,
+                     const void* k_full, const void* v_full, int W_max, const int32_t* seq_w,
+                     int64_t full_stride_bh,
+                     float scale, int num_splits,
+                     float* out,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * fa_decode_static -- fa_decode for callers that cannot allocate or pass a workspace: code under

@@ -46,6 +46,7 @@ __all__ = [
     "decode_head_group",
     "compress_batched",
     "decode_batched",
+    "decode_varlen",
     "append_token",
     "reconstruction_mse",
     "select_dims",
@@ -184,6 +185,30 @@ def decode_batched(q, Ck, kmask, Cv, vmask, T, t0, N,
             out[b, h * G:(h + 1) * G] = decode_head_group(
                 q[b, h * G:(h + 1) * G], Ck[b, h], kmask[b, h], Cv[b, h], vmask[b, h],
                 T, t0, N, k_keep[b, h], v_keep[b, h], k_full[b, h], v_full[b, h], scale)
+    return out
+
+
+def decode_varlen(q, Ck, kmask, Cv, vmask, T, t0, seq_n, k_keep, v_keep, k_full, v_full, seq_w, scale=None):
+    """Eq. 6 for a batch whose sequences stand at different positions: sequence b has seq_n[b]
+    middle rows (the first seq_n[b] rows of its k_keep / v_keep, and coefficient states that hold
+    exactly those tokens) and seq_w[b] full-width rows (the first seq_w[b] rows of k_full /
+    v_full).  Every sequence is one decode_head_group call on its own rows: nothing of a longer
+    neighbour is visible to it.  A sequence without any row has no softmax; its output is zero.
+    q [B,Hq,d] -> out [B,Hq,d]."""
+    q = np.asarray(q, dtype=np.float64)
+    B, Hq, d = q.shape
+    Hkv = np.asarray(kmask).shape[1]
+    G = Hq // Hkv
+    out = np.zeros((B, Hq, d))
+    for b in range(B):
+        n, w = int(seq_n[b]), int(seq_w[b])
+        if n + w == 0:
+            continue
+        for h in range(Hkv):
+            out[b, h * G:(h + 1) * G] = decode_head_group(
+                q[b, h * G:(h + 1) * G], Ck[b, h], kmask[b, h], Cv[b, h], vmask[b, h], T, t0, n,
+                np.asarray(k_keep[b, h])[:n], np.asarray(v_keep[b, h])[:n],
+                np.asarray(k_full[b, h])[:w], np.asarray(v_full[b, h])[:w], scale)
     return out
 
 

@@ -59,6 +59,10 @@ def _load(path: str = _LIB_PATH):
                               f32, i32, vp, vp, sz, vp]
     lib.fa_decode_timed.restype = i32
     lib.fa_decode_timed.argtypes = lib.fa_decode.argtypes + [c.POINTER(c.c_float)]
+    lib.fa_decode_varlen.restype = i32
+    lib.fa_decode_varlen.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp, i32,
+                                     i32, i32, i32, i32, vp, vp, i64, vp, i64, vp, vp, i32, vp, i64,
+                                     f32, i32, vp, vp, sz, vp]
     lib.fa_decode_static.restype = i32
     lib.fa_decode_static.argtypes = lib.fa_decode.argtypes[:27] + [vp]
     lib.fa_decode_workspace_bytes.restype = sz
@@ -225,6 +229,36 @@ def fa_decode(q, ck, kmask, cv, vmask, M, T, t0, N, k_keep, v_keep, k_full, v_fu
         kernel_ms.extend(ms)
     if st != FA_OK:
         raise FourierAttnError(st, "fa_decode")
+    return out
+
+
+def fa_decode_varlen(q, ck, kmask, cv, vmask, M, T, t0, N_max, seq_n, k_keep, v_keep, k_full, v_full, seq_w,
+                     scale=0.0, num_splits=0, out=None, workspace=None, stream=None,
+                     kk_stride_bh=0, vk_stride_bh=0, full_stride_bh=0):
+    """Enqueue fa_decode_varlen: `seq_n` / `seq_w` are int32 device tensors [B] (or None) with each
+    sequence's middle-row and full-width-row counts; everything else as fa_decode."""
+    B, Hq, D = q.shape
+    Hkv = kmask.shape[1]
+    Dkc = ck.shape[-1] if ck is not None else 0
+    Dvc = cv.shape[-1] if cv is not None else 0
+    W = k_full.shape[2] if k_full is not None else 0
+    dev = q.device
+    for t in (seq_n, seq_w):
+        if t is not None and (t.dtype != torch.int32 or t.numel() != B or not t.is_contiguous()):
+            raise ValueError("seq_n / seq_w must be contiguous int32 tensors of B entries")
+    if out is None:
+        out = torch.empty((B, Hq, D), dtype=torch.float32, device=dev)
+    if workspace is None:
+        need = decode_workspace_bytes(B, Hq, Hkv, D, Dkc, Dvc, M, N_max, W, num_splits)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    st = lib.fa_decode_varlen(_ptr(q), _dtype_code(q), B, Hq, Hkv, D,
+                              _ptr(ck), _ptr(kmask), Dkc, _ptr(cv), _ptr(vmask), Dvc,
+                              M, T, t0, N_max, _ptr(seq_n), _ptr(k_keep), kk_stride_bh, _ptr(v_keep), vk_stride_bh,
+                              _ptr(k_full), _ptr(v_full), W, _ptr(seq_w), full_stride_bh,
+                              float(scale), num_splits, _ptr(out),
+                              _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    if st != FA_OK:
+        raise FourierAttnError(st, "fa_decode_varlen")
     return out
 
 

@@ -104,8 +104,27 @@ struct SeqView {
   float* part_m;
   float* part_w;
 };
-__device__ __forceinline__ SeqView call_view(const DecodeParams& p) {
-  return SeqView{p.N, p.W, p.Sm, p.Sw, p.chunk_m, p.part_m, p.part_w};
+// rows of sequence b: the call's counts, or the sequence's own (clamped into them) when the caller gave lists
+__device__ __forceinline__ int seq_middle_rows(const DecodeParams& p, int b) {
+  return p.seq_n ? min(max(p.seq_n[b], 0), p.N) : p.N;
+}
+__device__ __forceinline__ int seq_full_rows(const DecodeParams& p, int b) {
+  return p.seq_w ? min(max(p.seq_w[b], 0), p.W) : p.W;
+}
+__device__ __forceinline__ SeqView call_view(const DecodeParams& p, int b) {
+  return SeqView{seq_middle_rows(p, b), seq_full_rows(p, b), p.Sm, p.Sw, p.chunk_m, p.part_m, p.part_w};
+}
+
+// Middle-row chunks [chunk_lo, chunk_hi) of a (sequence, KV head) that lie past the sequence's rows:
+// records that say "nothing here" (maximum -inf, everything else zero), for every query head.
+__device__ __forceinline__ void write_empty_middle(const DecodeParams& p, size_t hq0, int chunk_lo, int chunk_hi,
+                                                   int nthreads) {
+  const int recm = p.recm, G = p.G;
+  const int per = (chunk_hi - chunk_lo) * recm;
+  for (int it = threadIdx.x; it < G * per; it += nthreads) {
+    const int h = it / per, x = it - h * per;
+    p.part_m[((hq0 + h) * p.Sm + chunk_lo) * recm + x] = (x % recm == 0) ? -INFINITY : 0.0f;
+  }
 }
 
 // LDS of a workgroup of the one-launch form, after the exchange region of the middle-row phase:
@@ -491,9 +510,10 @@ __device__ __forceinline__ void partial_full_rows(const DecodeParams& p, unsigne
   const int q4 = lane >> 4, r16 = lane & 15;
   const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
   const int jw = s * kWChunk + wave * kWRows;          // first row of this wave
-  const int nw = max(0, min(kWRows, p.W - jw));        // its valid rows (0: the wave only joins the barriers)
-  const int jlast = p.W - 1;
-  const int jvis = p.W - p.Tq + r16 / p.Gq;            // last row the query token of column r16 may see
+  const int Wb = seq_full_rows(p, b);
+  const int nw = max(0, min(kWRows, Wb - jw));         // its valid rows (0: the wave only joins the barriers)
+  const int jlast = max(Wb - 1, 0);
+  const int jvis = Wb - p.Tq + r16 / p.Gq;             // last row the query token of column r16 may see
 
   // LDS carve-up: q [16][D] | p tiles [4][64][16] | partial sums [parts][4][D]
   T* qf = reinterpret_cast<T*>(smem);
@@ -727,7 +747,12 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps unit ids scalar
   const int q4 = lane >> 4, r16 = lane & 15;
   const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
-  const int c0 = sm_idx * p.chunk_m, c1 = min(p.N, c0 + p.chunk_m);   // chunk of middle rows
+  const int Nb = seq_middle_rows(p, b);
+  const int c0 = sm_idx * p.chunk_m, c1 = min(Nb, c0 + p.chunk_m);    // chunk of middle rows
+  if (c0 >= Nb) {   // (only with per-sequence counts) nothing of this chunk belongs to the sequence
+    write_empty_middle(p, hq0, sm_idx, sm_idx + 1, kBlock);
+    return;
+  }
   const int step = KT * kTJ;                                           // rows per step
   const int col_k = r16 / Gp, col_h = r16 % Gp;                        // S column = (tile, head)
   const bool col_live = col_k < KT && col_h < G;
@@ -739,7 +764,7 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
   const bool vragged = (p.Dvu & 15) != 0;
   const T* kk = static_cast<const T*>(p.k_keep) + bh * p.kk_stride;
   const T* vk = static_cast<const T*>(p.v_keep) + bh * p.vk_stride;
-  const int Nm1 = p.N - 1;
+  const int Nm1 = Nb - 1;
   const int NV = KT >= 2 ? KT / 2 : 1;               // V^mu token blocks of this wave per step
 
   // ---- LDS carve-up -------------------------------------------------------
@@ -1299,7 +1324,7 @@ __device__ __forceinline__ void partial_full_fast(const DecodeParams& p, const S
   constexpr int kRowsW = 16 * RB;                      // rows per wave
   const int jw = (s * kWaves + wave) * kRowsW;
   const int nw = max(0, min(kRowsW, sv.W - jw));
-  const int jlast = sv.W - 1;
+  const int jlast = max(sv.W - 1, 0);
   const int jvis = sv.W - p.Tq + r16 / p.Gq;             // last row the query token of column r16 may see
 
   float* pw = reinterpret_cast<float*>(smem) + wave * kWRows * kH;          // [64 rows][4 columns] probabilities
@@ -1446,8 +1471,8 @@ __global__ __launch_bounds__(kBlock) void decode_prepare_window(DecodeParams p) 
     const int s = blockIdx.x - p.nprep;
     if constexpr (sizeof(T) == 2) {
       if (p.D == 128 && p.G <= 4) {
-        if (p.wrb == 1) partial_full_fast<T, 1>(p, call_view(p), smem, blockIdx.y, s);
-        else partial_full_fast<T>(p, call_view(p), smem, blockIdx.y, s);
+        if (p.wrb == 1) partial_full_fast<T, 1>(p, call_view(p, blockIdx.y / p.Hkv), smem, blockIdx.y, s);
+        else partial_full_fast<T>(p, call_view(p, blockIdx.y / p.Hkv), smem, blockIdx.y, s);
       } else {
         partial_full_rows<T>(p, smem, s);
       }
@@ -1476,6 +1501,12 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const
   const int q4 = lane >> 4, r16 = lane & 15;
   const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
   const int c0 = sm_idx * sv.chunk_m, c1 = min(sv.N, c0 + sv.chunk_m);
+  if constexpr (!FUSED) {
+    if (c0 >= sv.N) {   // (only with per-sequence counts) nothing of this chunk belongs to the sequence
+      write_empty_middle(p, hq0, sm_idx, sm_idx + 1, kBlock);
+      return;
+    }
+  }
   const int nsteps = (c1 - c0 + step - 1) / step;
   const int col_k = r16 / GP, col_h = r16 % GP;
   const bool col_live = col_k < KT && col_h < G;
@@ -1893,8 +1924,8 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const
 template <int CW, int DVT, int GP>
 __global__ __launch_bounds__(kBlock, CW <= 2 ? 2 : 1) void decode_partial_fast(DecodeParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  if (static_cast<int>(blockIdx.x) < p.Smw) partial_middle_fast<CW, DVT, GP>(p, call_view(p), smem, blockIdx.y, blockIdx.x);
-  else if (p.D == 128) partial_full_fast<bf16_t>(p, call_view(p), smem, blockIdx.y, blockIdx.x - p.Smw);
+  if (static_cast<int>(blockIdx.x) < p.Smw) partial_middle_fast<CW, DVT, GP>(p, call_view(p, blockIdx.y / p.Hkv), smem, blockIdx.y, blockIdx.x);
+  else if (p.D == 128) partial_full_fast<bf16_t>(p, call_view(p, blockIdx.y / p.Hkv), smem, blockIdx.y, blockIdx.x - p.Smw);
   else partial_full_rows<bf16_t>(p, smem, blockIdx.x - p.Smw);
 }
 
@@ -1933,9 +1964,16 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
   const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
   // the workgroup walks p.cpw consecutive chunks of its head (one record each): its rows are
   // [w0, w1), its steps are counted through all of them, a chunk ends every spc steps
-  const int w0 = sm_idx * p.cpw * p.chunk_m, w1 = min(p.N, w0 + p.cpw * p.chunk_m);
+  const int Nb = seq_middle_rows(p, b);
+  const int w0 = sm_idx * p.cpw * p.chunk_m, w1 = min(Nb, w0 + p.cpw * p.chunk_m);
   const int total = (w1 - w0 + step - 1) / step;
   const int spc = p.chunk_m / step;
+  {   // (only with per-sequence counts) chunks of this workgroup past the sequence's rows
+    const int first = sm_idx * p.cpw, last = min(first + p.cpw, p.Sm);
+    const int visited = w1 > w0 ? (total - 1) / spc + 1 : 0;
+    if (first + visited < last) write_empty_middle(p, hq0, first + visited, last, kBlock8);
+    if (visited == 0) return;
+  }
   const int c1 = w1;                                  // rows at or past it are masked (only the last step can hold any)
   const int col_k = r16 / GP, col_h = r16 % GP;
   const bool col_live = col_k < KT && col_h < G;
@@ -1945,7 +1983,7 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
   const int Dvu = p.Dvu;
   const T* kk = static_cast<const T*>(p.k_keep) + bh * p.kk_stride;
   const T* vk = static_cast<const T*>(p.v_keep) + bh * p.vk_stride;
-  const int Nm1 = p.N - 1;
+  const int Nm1 = Nb - 1;
   const int my_tile = wave >> 1, my_half = wave & 1;   // kept operands: tile, and which half of it
 
   // ---- LDS carve-up ----------------------------------------------------------------------------
@@ -2379,7 +2417,7 @@ __global__ __launch_bounds__(kBlock8, 1) void decode_partial_fast8(DecodeParams 
     partial_middle_fast8<CW, DVT, GP>(p, smem);
   } else {
     if (threadIdx.x >= kBlock) return;   // the full-row path is written for four waves; the others leave before any barrier
-    if (p.D == 128) partial_full_fast<bf16_t>(p, call_view(p), smem, blockIdx.y, blockIdx.x - p.Smw);
+    if (p.D == 128) partial_full_fast<bf16_t>(p, call_view(p, blockIdx.y / p.Hkv), smem, blockIdx.y, blockIdx.x - p.Smw);
     else partial_full_rows<bf16_t>(p, smem, blockIdx.x - p.Smw);
   }
 }
@@ -2645,7 +2683,7 @@ __global__ __launch_bounds__(kFinBlock) void decode_finish(DecodeParams p) {
       const float* src = reinterpret_cast<const float*>(red4) + 4 * (c >> 2) + (c & 3);
       for (int g = 0; g < ngrp; ++g) v += src[4 * g * nq];
     }
-    p.out[static_cast<size_t>(hq) * D + d0 + tid] = v / L;
+    p.out[static_cast<size_t>(hq) * D + d0 + tid] = L > 0.0f ? v / L : 0.0f;   // (a sequence without rows)
   }
 }
 
@@ -2896,7 +2934,7 @@ __device__ __forceinline__ void finish2_slice(const DecodeParams& p, const SeqVi
         for (int gi = 0; gi < nkg; ++gi) v += redk[gi * kcn + (tid - cbw)];
       if (Sw > 0)
         for (int gi = 0; gi < nwg; ++gi) v += redk[kFinBlock + gi * njn + tid];
-      p.out[static_cast<size_t>(hq) * D + dim_of[tid]] = v / Lsum;
+      p.out[static_cast<size_t>(hq) * D + dim_of[tid]] = Lsum > 0.0f ? v / Lsum : 0.0f;   // (a sequence without rows)
     }
   }
 }
@@ -2909,7 +2947,7 @@ __global__ __launch_bounds__(kFinBlock, kFin2Wide == 16 ? 2 : 4) void decode_fin
   const int bh = (slot / per_kv) * 8 + xcd;
   if (bh >= p.B * p.Hkv) return;
   const int within = slot % per_kv;
-  finish2_slice<kFin2Wide>(p, call_view(p), NS, bh, within / NS, within % NS);
+  finish2_slice<kFin2Wide>(p, SeqView{p.N, p.W, p.Sm, p.Sw, p.chunk_m, p.part_m, p.part_w}, NS, bh, within / NS, within % NS);
 }
 
 // ---------------------------------------------------------------------------
@@ -3016,7 +3054,7 @@ __device__ __forceinline__ void fused_full_rows(const DecodeParams& p, const Seq
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int q4 = lane >> 4, r16 = lane & 15;
   const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
-  const int W = sv.W, jlast = W - 1;
+  const int W = sv.W, jlast = max(W - 1, 0);
   const int nch = (W + kWChunk - 1) / kWChunk;
   const int jvis = W - p.Tq + r16 / p.Gq;
 
@@ -3259,7 +3297,8 @@ __device__ __forceinline__ void fused_finish(const DecodeParams& p, unsigned cha
         }
       }
       if (has_w) v += ew * recw[h * p.recw + 4 + tid];
-      p.out[(hq0 + h) * D + tid] = v / (em * lm + ew * lw);
+      const float lsum = em * lm + ew * lw;
+      p.out[(hq0 + h) * D + tid] = lsum > 0.0f ? v / lsum : 0.0f;   // (a sequence without rows)
     }
   }
 }
@@ -3271,8 +3310,8 @@ __global__ __launch_bounds__(kBlock, 1) void decode_fused(DecodeParams p) {
   constexpr int Mint = kWaves * CW * 32;
   const int bh = blockIdx.x, b = bh / p.Hkv;
   SeqView sv;
-  sv.N = p.seq_n ? min(max(p.seq_n[b], 0), p.N) : p.N;
-  sv.W = p.seq_w ? min(max(p.seq_w[b], 0), p.W) : p.W;
+  sv.N = seq_middle_rows(p, b);
+  sv.W = seq_full_rows(p, b);
   sv.Sm = sv.N > 0 ? 1 : 0;
   sv.Sw = sv.W > 0 ? 1 : 0;
   sv.chunk_m = max(sv.N, 1);
@@ -3676,8 +3715,10 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
                        const void* v_keep, int64_t vk_stride_bh, const void* k_full,
                        const void* v_full, int W, int64_t full_stride_bh, float scale,
                        int num_splits, float* out, void* workspace, size_t workspace_bytes,
-                       void* hip_stream, fa::KernelTimers* tm, int Tq = 1) {
+                       void* hip_stream, fa::KernelTimers* tm, int Tq = 1, const int32_t* seq_n = nullptr,
+                       const int32_t* seq_w = nullptr) {
   using namespace fa;
+  if ((seq_n || seq_w) && Tq != 1) return FA_ERR_UNSUPPORTED;
   // Tq query tokens per sequence are Tq * Hq query heads to every kernel (group index = token * G +
   // head); only the full-width rows know about tokens: the last Tq rows are the new tokens, and
   // query t sees new tokens 0 .. t
@@ -3729,7 +3770,7 @@ static int decode_impl(const void* q, int dtype, int B, int Hq, int Hkv, int D, 
   p.Sw = pl.Sw; p.Sm = pl.Sm; p.chunk_m = pl.chunk_m; p.recm = pl.recm; p.recw = pl.recw;
   p.cpw = pl.cpw; p.Smw = pl.Smw; p.Swp = pl.Swp; p.nprep = 0;
   p.lds_tab = pl.lds_tab;
-  p.seq_n = nullptr; p.seq_w = nullptr; p.Sw_rec = pl.Sw; p.wrb = pl.wrb;
+  p.seq_n = seq_n; p.seq_w = seq_w; p.Sw_rec = pl.Sw; p.wrb = pl.wrb;
   p.scale = scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(D));
   p.ph_scale = 4294967296.0 / static_cast<double>(T);
   char* ws = static_cast<char*>(workspace);
@@ -3753,6 +3794,17 @@ int fa_decode(const void* q, int dtype, int B, int Hq, int Hkv, int D, const flo
   return decode_impl(q, dtype, B, Hq, Hkv, D, ck, kmask, Dkc, cv, vmask, Dvc, M, T, t0, N, k_keep,
                      kk_stride_bh, v_keep, vk_stride_bh, k_full, v_full, W, full_stride_bh, scale,
                      num_splits, out, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+int fa_decode_varlen(const void* q, int dtype, int B, int Hq, int Hkv, int D, const float* ck,
+                     const uint8_t* kmask, int Dkc, const float* cv, const uint8_t* vmask, int Dvc, int M,
+                     int T, int t0, int N_max, const int32_t* seq_n, const void* k_keep, int64_t kk_stride_bh,
+                     const void* v_keep, int64_t vk_stride_bh, const void* k_full, const void* v_full,
+                     int W_max, const int32_t* seq_w, int64_t full_stride_bh, float scale, int num_splits,
+                     float* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return decode_impl(q, dtype, B, Hq, Hkv, D, ck, kmask, Dkc, cv, vmask, Dvc, M, T, t0, N_max, k_keep,
+                     kk_stride_bh, v_keep, vk_stride_bh, k_full, v_full, W_max, full_stride_bh, scale,
+                     num_splits, out, workspace, workspace_bytes, hip_stream, nullptr, 1, seq_n, seq_w);
 }
 
 int fa_decode_mq(const void* q, int dtype, int B, int Tq, int Hq, int Hkv, int D, const float* ck,

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 import torch
 
-from workloads import CONFIGS, PAPER_SETTING, random_variants, rel_err, small_variants
+from workloads import CONFIGS, PAPER_SETTING, one_launch_variants, random_variants, rel_err, small_variants
 from fa_testlib import (cached_context, oracle_decode_heads, oracle_state, rows_pad8, rows_to_tok8,
                         sample_heads, to_dev)
 
@@ -165,6 +165,98 @@ def test_decode_split_count_invariance(splits):
     cfg = SMALL[3]
     print(f"[case] split invariance {cfg.name} splits={splits}", flush=True)
     _check_decode(cfg, sample_heads(cfg, None), num_splits=splits)
+
+
+ONE_LAUNCH = one_launch_variants()
+
+
+@pytest.mark.parametrize("cfg", ONE_LAUNCH, ids=[c.name for c in ONE_LAUNCH])
+def test_decode_one_launch_form(cfg):
+    """num_splits = 1 on these shapes is the one-launch form (series coefficients, rows and merge in
+    one workgroup per (sequence, KV head)); the same shapes through the three launches as well."""
+    print(f"[case] one-launch decode {cfg}", flush=True)
+    ctx = cached_context(cfg)
+    heads = sample_heads(cfg, None)
+    st = oracle_state(cfg, ctx, heads)
+    _check_decode(cfg, heads, ctx, st, num_splits=1)
+    _check_decode(cfg, heads, ctx, st, num_splits=3)
+
+
+def _varlen_case(cfg, seq_n, seq_w, splits):
+    """fa_decode_varlen against oracle.decode_varlen: every sequence compressed over its own rows; the
+    slabs hold finite junk past a sequence's rows, which must not reach its output."""
+    import oracle.fourier_kv as fk
+    fa = _fa()
+    ctx = cached_context(cfg)
+    B, H, N, D, M, T = cfg.B, cfg.Hkv, cfg.N, cfg.D, cfg.M, cfg.T
+    rng = np.random.default_rng(cfg.index)
+    ck = np.zeros((B, H, M, cfg.Dkc)); cv = np.zeros((B, H, M, cfg.Dvc))
+    kk = rng.standard_normal((B, H, N, D - cfg.Dkc)).astype(np.float32) * 3.0
+    vk = rng.standard_normal((B, H, N, D - cfg.Dvc)).astype(np.float32) * 3.0
+    for b in range(B):
+        n = seq_n[b]
+        for h in range(H):
+            ck[b, h], kk[b, h, :n] = fk.compress_segment(ctx["k_mid"][b, h][:n], ctx["kmask"][b, h], M, T, cfg.t0)
+            cv[b, h], vk[b, h, :n] = fk.compress_segment(ctx["v_mid"][b, h][:n], ctx["vmask"][b, h], M, T, cfg.t0)
+    ck32, cv32 = ck.astype(np.float32), cv.astype(np.float32)
+    if cfg.dtype == "bf16":   # what the kernels are handed: values of the element type
+        kk = torch.from_numpy(kk).to(torch.bfloat16).float().numpy()
+        vk = torch.from_numpy(vk).to(torch.bfloat16).float().numpy()
+    want = fk.decode_varlen(ctx["q"], ck32.astype(np.float64), ctx["kmask"], cv32.astype(np.float64), ctx["vmask"],
+                            T, cfg.t0, seq_n, kk, vk, ctx["k_full"], ctx["v_full"], seq_w)
+    dn = torch.tensor(seq_n, dtype=torch.int32).cuda()
+    dw = torch.tensor(seq_w, dtype=torch.int32).cuda()
+    args = (to_dev(ctx["q"], cfg), to_dev(ck32), to_dev(ctx["kmask"]), to_dev(cv32), to_dev(ctx["vmask"]),
+            M, T, cfg.t0, N)
+    tail = (to_dev(rows_pad8(kk), cfg), to_dev(rows_to_tok8(vk), cfg), to_dev(ctx["k_full"], cfg),
+            to_dev(ctx["v_full"], cfg))
+    for ns in splits:
+        out = fa.fa_decode_varlen(*args, dn, *tail, dw, num_splits=ns)
+        torch.cuda.synchronize()
+        out = out.cpu().numpy()
+        assert np.isfinite(out).all(), (cfg.name, ns)
+        for b in range(B):
+            if seq_n[b] + seq_w[b] == 0:
+                assert not out[b].any(), (cfg.name, ns, b)
+            else:
+                assert rel_err(out[b], want[b]) <= cfg.tol, (cfg.name, ns, b, rel_err(out[b], want[b]))
+    # without lists the call is fa_decode
+    out = fa.fa_decode_varlen(*args, None, *tail, None, num_splits=splits[0])
+    ref = fa.fa_decode(*args, *tail, num_splits=splits[0])
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)
+
+
+def test_decode_varlen_one_launch_and_three_launch_forms():
+    """Sequences at different positions (one without middle rows, one without full-width rows, one
+    without any row): the specialised bf16 kernels in both forms."""
+    from dataclasses import replace
+    cfg = replace(ONE_LAUNCH[0], name="vl_g4_m200", index=51, B=5)
+    print(f"[case] varlen {cfg}", flush=True)
+    _varlen_case(cfg, [1500, 0, 777, 64, 0], [304, 304, 17, 0, 0], [1, 0, 5])
+    cfg = replace(ONE_LAUNCH[1], name="vl_mha_m100", index=52, B=4)
+    print(f"[case] varlen {cfg}", flush=True)
+    _varlen_case(cfg, [701, 1, 350, 8], [44, 1, 0, 30], [1, 2])
+
+
+def test_decode_varlen_general_kernels():
+    """The general middle-row kernel (fp32; bf16 with sixteen query heads per KV head) and the
+    eight-wave kernel for 512 series slots, the latter also with several chunks per workgroup."""
+    from dataclasses import replace
+    base = SMALL[0]
+    cfg = replace(base, name="vl_f32", index=53, B=3, Hq=4, Hkv=2, D=64, N=600, Lw=50, Dkc=40, Dvc=48, M=48,
+                  dtype="f32")
+    print(f"[case] varlen {cfg}", flush=True)
+    _varlen_case(cfg, [600, 1, 300], [54, 54, 2], [0, 4])
+    cfg = replace(base, name="vl_gqa16", index=54, B=2, Hq=16, Hkv=1, D=64, N=450, Lw=150, Dkc=40, Dvc=32, M=32,
+                  dtype="bf16")
+    print(f"[case] varlen {cfg}", flush=True)
+    _varlen_case(cfg, [450, 129], [154, 3], [0, 3])
+    # (48 pairs x 6 chunks of two steps: more chunks than compute units, two chunks per workgroup)
+    cfg = replace(base, name="vl_m512", index=55, B=6, Hq=32, Hkv=8, D=128, N=3000, Lw=40, Dkc=112, Dvc=112,
+                  M=512, dtype="bf16")
+    print(f"[case] varlen {cfg}", flush=True)
+    _varlen_case(cfg, [3000, 700, 0, 1300, 513, 2999], [44, 44, 9, 0, 1, 44], [0, 6])
 
 
 FULL_SIZE = {2: CONFIGS[1], 3: CONFIGS[2], 4: CONFIGS[3], 5: CONFIGS[4], 6: PAPER_SETTING}

@@ -256,6 +256,74 @@ def check_batched_wrappers():
             assert np.allclose(out[b, hq], one[0], atol=1e-13)
 
 
+def check_varlen_decode():
+    """decode_varlen: equal lengths = decode_batched; every sequence = vanilla attention over exactly
+    its own rows when the band is full (M = its row count = T); rows past a sequence's counts are
+    invisible to it, rows inside are not; a sequence without rows gives zeros."""
+    rng = np.random.default_rng(21)
+    B, Hkv, G, d, N, W, M = 3, 2, 2, 8, 12, 4, 5
+    T = 16
+    Xk = rng.standard_normal((B, Hkv, N, d)); Xv = rng.standard_normal((B, Hkv, N, d))
+    Kf = rng.standard_normal((B, Hkv, W, d)); Vf = rng.standard_normal((B, Hkv, W, d))
+    q = rng.standard_normal((B, Hkv * G, d))
+    km = np.zeros((B, Hkv, d), np.uint8); vm = np.zeros((B, Hkv, d), np.uint8)
+    for b in range(B):
+        for h in range(Hkv):
+            km[b, h, rng.choice(d, 3, replace=False)] = 1
+            vm[b, h, rng.choice(d, 5, replace=False)] = 1
+
+    def state(seq_n):
+        Ck = np.zeros((B, Hkv, M, 3)); Cv = np.zeros((B, Hkv, M, 5))
+        kk = rng.standard_normal((B, Hkv, N, d - 3)); vk = rng.standard_normal((B, Hkv, N, d - 5))   # rows past n: junk
+        for b in range(B):
+            for h in range(Hkv):
+                n = seq_n[b]
+                Ck[b, h], kk[b, h, :n] = fk.compress_segment(Xk[b, h, :n], km[b, h], M, T, 0)
+                Cv[b, h], vk[b, h, :n] = fk.compress_segment(Xv[b, h, :n], vm[b, h], M, T, 0)
+        return Ck, Cv, kk, vk
+
+    # equal lengths: the batched wrapper
+    full = [N] * B
+    Ck, Cv, kk, vk = state(full)
+    a = fk.decode_varlen(q, Ck, km, Cv, vm, T, 0, full, kk, vk, Kf, Vf, [W] * B)
+    b_ = fk.decode_batched(q, Ck, km, Cv, vm, T, 0, N, kk, vk, Kf, Vf)
+    assert np.allclose(a, b_, atol=1e-14)
+    # different lengths: each sequence alone
+    seq_n, seq_w = [12, 0, 7], [4, 3, 0]
+    Ck, Cv, kk, vk = state(seq_n)
+    out = fk.decode_varlen(q, Ck, km, Cv, vm, T, 0, seq_n, kk, vk, Kf, Vf, seq_w)
+    for b in range(B):
+        for h in range(Hkv):
+            n, w = seq_n[b], seq_w[b]
+            one = fk.decode_head_group(q[b, h * G:(h + 1) * G], Ck[b, h], km[b, h], Cv[b, h], vm[b, h], T, 0, n,
+                                       kk[b, h, :n], vk[b, h, :n], Kf[b, h, :w], Vf[b, h, :w])
+            assert np.allclose(out[b, h * G:(h + 1) * G], one, atol=1e-14)
+    # rows past the counts are invisible, rows inside are not
+    kk2, Kf2 = kk.copy(), Kf.copy()
+    kk2[2, :, 7:] += 100.0; Kf2[1, :, 3:] += 100.0
+    assert np.array_equal(fk.decode_varlen(q, Ck, km, Cv, vm, T, 0, seq_n, kk2, vk, Kf2, Vf, seq_w), out)
+    kk2 = kk.copy(); kk2[2, :, 6] += 1.0
+    assert not np.allclose(fk.decode_varlen(q, Ck, km, Cv, vm, T, 0, seq_n, kk2, vk, Kf, Vf, seq_w)[2], out[2])
+    # full band on a sequence's own rows (M = n = T): vanilla attention over exactly those rows
+    n, w = 7, 2
+    km0 = km[:1]; vm0 = vm[:1]
+    Ck1 = np.zeros((1, Hkv, n, 3)); Cv1 = np.zeros((1, Hkv, n, 5))
+    kk1 = np.zeros((1, Hkv, N, d - 3)); vk1 = np.zeros((1, Hkv, N, d - 5))
+    for h in range(Hkv):
+        Ck1[0, h], kk1[0, h, :n] = fk.compress_segment(Xk[0, h, :n], km0[0, h], n, n, 0)
+        Cv1[0, h], vk1[0, h, :n] = fk.compress_segment(Xv[0, h, :n], vm0[0, h], n, n, 0)
+    got = fk.decode_varlen(q[:1], Ck1, km0, Cv1, vm0, n, 0, [n], kk1, vk1, Kf[:1], Vf[:1], [w])
+    for h in range(Hkv):
+        Kt = np.concatenate([Kf[0, h, :w], Xk[0, h, :n]]); Vt = np.concatenate([Vf[0, h, :w], Xv[0, h, :n]])
+        for g in range(G):
+            s_ = Kt @ q[0, h * G + g] / np.sqrt(d)
+            p_ = np.exp(s_ - s_.max()); p_ /= p_.sum()
+            assert np.allclose(got[0, h * G + g], p_ @ Vt, atol=1e-10)
+    # no rows at all: zeros
+    z = fk.decode_varlen(q, Ck, km, Cv, vm, T, 0, [0, 0, 0], kk, vk, Kf, Vf, [0, 0, 0])
+    assert not z.any()
+
+
 ALL_CHECKS = (
     check_gram_is_inverse_weights,
     check_projector_matches_literal_eq4,
@@ -267,6 +335,7 @@ ALL_CHECKS = (
     check_brute_force,
     check_large_phase_is_exact,
     check_batched_wrappers,
+    check_varlen_decode,
 )
 
 

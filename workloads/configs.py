@@ -101,6 +101,27 @@ PAPER_SETTING = FAConfig("paper_k512_32k", 6, B=1, Hq=8, Hkv=2, D=128, dtype="bf
                          N=31740, Dkc=96, Dvc=96, M=1023)
 
 
+def one_launch_variants():
+    """Shapes of the one-launch decode form (bf16, D = 128, at most four query heads per KV head,
+    1 .. 32 kept dims on both sides, M <= 256, compressed counts in multiples of 4), covering its
+    compiled variants: series of 128 / 256 slots, one or two tiles of kept V dims, one or several
+    query heads per KV head; ragged row counts, no full-width rows, a period longer than the
+    segment that starts inside it."""
+    base = CONFIGS[0]
+    return (
+        replace(base, name="ol_g4_m200", index=41, B=2, Hq=8, Hkv=2, D=128, N=1500, Lw=300,
+                Dkc=96, Dvc=100, M=200, dtype="bf16", num_splits=1),
+        replace(base, name="ol_mha_m100", index=42, B=3, Hq=3, Hkv=3, D=128, N=701, Lw=40,
+                Dkc=112, Dvc=112, M=100, dtype="bf16", num_splits=1),
+        replace(base, name="ol_g2_m256_nowindow", index=43, B=1, Hq=4, Hkv=2, D=128, N=2049, Lw=0, Li=0,
+                Dkc=100, Dvc=120, M=256, dtype="bf16", num_splits=1),
+        replace(base, name="ol_g3_m31_t0", index=44, B=2, Hq=3, Hkv=1, D=128, N=517, Lw=259, Li=1,
+                Dkc=124, Dvc=96, M=31, dtype="bf16", num_splits=1, period=3000, t0=1400),
+        replace(base, name="ol_mha_m129_short", index=45, B=1, Hq=2, Hkv=2, D=128, N=130, Lw=5,
+                Dkc=96, Dvc=108, M=129, dtype="bf16", num_splits=1),
+    )
+
+
 def get_config(key) -> FAConfig:
     """Look a config up by 1-based index or by name."""
     for c in CONFIGS:
