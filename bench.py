@@ -188,14 +188,18 @@ def measure(cfg, steps, warmup, extras=False):
         return {"achieved": round(a, 1), "frac": round(a / HBM_PEAK_GBS, 4)}
 
     names = ("prepare", "partial", "finish")
+    what = ("fa_decode call = decode_prepare (series coefficients) + decode_partial (middle rows; "
+            "full-width rows in either) + decode_finish")
+    if kd[0] == 0.0 and kd[2] == 0.0:   # the one-launch form: one workgroup per (sequence, KV head) does it all
+        names, kd, kb = ("fused",), kd[1:2], {"fused": dec_bytes}
+        what = "fa_decode call = decode_fused (series coefficients, all rows and the merge in one launch)"
     per_kernel = {}
     for i, n in enumerate(names):
         per_kernel["decode_" + n] = {"ms": round(float(kd[i]) * 1e3, 5), "algorithmic_bytes": kb[n],
                                      **hbm(kb[n], float(kd[i])), "traffic": traffic.get("decode_" + n)}
     dom = "decode_" + names[int(np.argmax(kd))]
     call_traffic = [traffic.get("decode_" + n) for n in names]
-    roof_dec = {"kernel": "fa_decode call = decode_prepare (series coefficients) + decode_partial (middle rows; "
-                          "full-width rows in either) + decode_finish",
+    roof_dec = {"kernel": what,
                 "bound": "hbm", **hbm(dec_bytes, t_kernels), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "algorithmic_bytes": dec_bytes, "kernels_ms": round(t_kernels * 1e3, 5),
                 "traffic": (sum(call_traffic) if all(v is not None for v in call_traffic) else None),

@@ -1482,8 +1482,120 @@ __global__ __launch_bounds__(kBlock) void decode_prepare_window(DecodeParams p) 
   }
 }
 
-// FUSED: the series coefficients, the constant-term coefficient and the packed query are already in
-// this workgroup's LDS (written by fused_coeffs), not in the workspace
+// g = diag(w) C_k q[D^kc], the constant-term coefficient and q at the kept K dims, formed by the
+// workgroup that uses them and left in the LDS places the middle-row phase reads.  Four threads
+// share a row of C_k (interleaved 128-bit vectors); the rows of all NP passes of 64 rows are
+// requested by issue(), before anything is waited for; finish() runs after the caller's own
+// independent work (the table build of the middle-row phase).  The query at the compressed dims is
+// staged at the start of the exchange region, which the middle-row phase only writes after its
+// own barrier.
+template <int NP>
+struct FusedCoeffs {
+  using T = bf16_t;
+  static constexpr int D = 128, kV = D / 16;   // 128-bit vectors of a row per thread (compressed dims <= 124)
+  static constexpr int Mint = (NP - 1) * 64, kPitchG = Mint + 32;
+  f32x4 cv4[NP][kV];
+  uint8_t mb[2];
+  T qe[2];
+
+  __device__ __forceinline__ void issue(const DecodeParams& p, const int bh) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int b = bh / p.Hkv, hkv = bh % p.Hkv;
+    const int Dkc = p.Dkc, M = p.M;
+    const int row = tid >> 2, seg = tid & 3, c4n = Dkc / 4;
+    const float* ck0 = p.ck + static_cast<size_t>(bh) * M * Dkc;
+#pragma unroll
+    for (int ps = 0; ps < NP; ++ps) {
+      const float* ckr = ck0 + static_cast<size_t>(min(row + 64 * ps, M - 1)) * Dkc;
+#pragma unroll
+      for (int i = 0; i < kV; ++i)
+        if (4 * i < c4n) cv4[ps][i] = *reinterpret_cast<const f32x4*>(ckr + 4 * min(seg + 4 * i, c4n - 1));
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) mb[j] = p.kmask[static_cast<size_t>(bh) * D + lane + 64 * j];
+    const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * p.G;
+    const T* q = static_cast<const T*>(p.q) + hq0 * D;
+    const int nqe = p.G * D;   // <= 512
+#pragma unroll
+    for (int i = 0; i < 2; ++i) qe[i] = q[min(tid + i * kBlock, nqe - 1)];
+  }
+
+  __device__ __forceinline__ void finish(const DecodeParams& p, unsigned char* smem) {
+    const int tid = threadIdx.x;
+    const int Dkc = p.Dkc, G = p.G, M = p.M;
+    const int row = tid >> 2, seg = tid & 3, c4n = Dkc / 4;
+    float* qc = reinterpret_cast<float*>(smem);                    // [G][Dkc]
+    float* gs_s = reinterpret_cast<float*>(smem + p.lds_tab);      // [G][Mint + 32]
+    T* qk_s = reinterpret_cast<T*>(gs_s + G * kPitchG);            // [G][32]
+    float* g0_s = reinterpret_cast<float*>(qk_s + G * 32);         // [G]
+    uint64_t kbal[4];
+    kbal[0] = __ballot(mb[0] != 0);
+    kbal[1] = __ballot(mb[1] != 0);
+    kbal[2] = kbal[3] = 0;
+    const int nqe = G * D;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int it = tid + i * kBlock;
+      if (it < nqe) {
+        const int h = it >> 7, d = it & 127;
+        const int r = dim_rank(kbal, d);
+        if (r < 0) qc[h * Dkc + (-r - 1)] = to_f32(qe[i]);
+        else qk_s[h * 32 + r] = qe[i];
+      }
+    }
+    {
+      const int npad = 32 - p.Dku;
+      if (tid < G * npad) qk_s[(tid / npad) * 32 + p.Dku + tid % npad] = T{};
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ps = 0; ps < NP; ++ps) {
+      const int m = row + 64 * ps;
+      const float w = (m < M) ? basis_weight((m + 1) / 2, p.T) : 0.0f;
+      for (int h = 0; h < G; ++h) {
+        const float* qh = qc + h * Dkc;
+        float acc = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kV; ++i) {
+          if (4 * i < c4n) {
+            const int c4 = seg + 4 * i;
+            const f32x4 qv = *reinterpret_cast<const f32x4*>(qh + 4 * min(c4, c4n - 1));
+            const f32x4 c = cv4[ps][i];
+            const float d4 = (c[0] * qv[0] + c[1] * qv[1]) + (c[2] * qv[2] + c[3] * qv[3]);
+            acc += (c4 < c4n) ? d4 : 0.0f;
+          }
+        }
+        acc += __shfl_xor(acc, 1, kWave);
+        acc += __shfl_xor(acc, 2, kWave);
+        if (seg == 0 && m <= Mint) {
+          if (m == 0) g0_s[h] = acc * w;
+          else gs_s[h * kPitchG + (m - 1)] = acc * w;
+        }
+      }
+    }
+    // (the barrier that publishes g is the caller's)
+  }
+};
+
+// C_v of the pair goes straight from global memory into LDS (no registers, nothing waits for it
+// here): every wave copies 1 KB blocks, lane i of a block supplying bytes 16 i .. 16 i + 15.  The
+// last block may reach past the matrix: its lanes re-read the last vector (the stash is padded).
+__device__ __forceinline__ void fused_stash_cv(const DecodeParams& p, unsigned char* smem, const int bh,
+                                               const unsigned lds_cv) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const unsigned bytes = static_cast<unsigned>(p.M) * p.Dvc * 4u;
+  const unsigned nblk = (bytes + 1023u) >> 10;
+  const char* src = reinterpret_cast<const char*>(p.cv + static_cast<size_t>(bh) * p.M * p.Dvc);
+  for (unsigned blk = wave; blk < nblk; blk += kWaves) {
+    const unsigned off = min(blk * 1024u + 16u * lane, bytes - 16u);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + off),
+                                     (__attribute__((address_space(3))) void*)(smem + lds_cv + blk * 1024u), 16, 0, 0);
+  }
+}
+
+// FUSED (the one-launch form): the series coefficients, the constant-term coefficient and the packed
+// query are formed here, around the table build, and C_v is sent on its way into LDS
 template <int CW, int DVT, int GP, bool FUSED = false>
 __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const SeqView& sv, unsigned char* smem,
                                                     const int bh, const int sm_idx) {
@@ -1574,9 +1686,13 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const
   float g0 = 0.0f;
   // packed query at the kept K dims: G rows of 32 elements = at most 16 vectors of 8
   Frag<T> qv;
+  FusedCoeffs<FUSED ? 2 * CW + 1 : 1> coeffs;
   if constexpr (!FUSED) {
     g0 = p.g0[hq0 + min(ocol_h, G - 1)];
     qv.load(static_cast<const T*>(p.qkeep) + hq0 * Dkq + 8 * min(tid, G * 4 - 1));
+  } else {
+    coeffs.issue(p, bh);
+    if (p.Dvc > 0) fused_stash_cv(p, smem, bh, fused_lds(p.lds_tab, G, Mint, p.recm, p.recw, p.M, p.Dvc).cv);
   }
   Frag<T> kfA[4], kfB[4];
   Frag<T> vfA[2][DVT], vfB[2][DVT];
@@ -1655,6 +1771,8 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const
       if (v4 < ng4) *reinterpret_cast<f32x4*>(gs_s + (4 * v4 / Mint) * kPitchG + (4 * v4) % Mint) = gv[i];
     }
     if (tid < G * 4) *reinterpret_cast<Frag<T>*>(qk_s + 8 * tid) = qv;
+  } else {
+    coeffs.finish(p, smem);
   }
   __syncthreads();
   if constexpr (FUSED) g0 = g0_s[min(ocol_h, G - 1)];
@@ -1819,9 +1937,11 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const
     }
   };
 
-  // two steps per trip: the operands of a step are requested two steps ahead, clamped into the chunk
+  // (four steps of operands in flight, which the one-launch form has the registers for, made its
+  // 4 K-token chunks slower: 38.5 -> 41.5 us; the loop does not wait for memory)
   const int last_base = c0 + (nsteps - 1) * step;
   {
+    // two steps per trip: the operands of a step are requested two steps ahead, clamped into the chunk
     int s = 0;
     for (; s + 2 < nsteps; s += 2) {
       const int base = c0 + s * step;
@@ -2960,94 +3080,16 @@ __global__ __launch_bounds__(kFinBlock, kFin2Wide == 16 ? 2 : 4) void decode_fin
 // form passes through the workspace (g, packed q, one record per phase) stay with the workgroup
 // that wrote them (same compute unit, same first-level cache).  Sequences may differ in length:
 // a workgroup takes its own counts from seq_n / seq_w.
-// g = diag(w) C_k q[D^kc], the constant-term coefficient and q at the kept K dims, formed by the
-// workgroup that uses them and left in the LDS places the middle-row phase reads.  Four threads
-// share a row of C_k (interleaved 128-bit vectors); the rows of all NP passes of 64 rows are
-// requested before anything is waited for.  The query at the compressed dims is staged at the
-// start of the exchange region, which the middle-row phase only writes after its own barrier.
-template <int NP>
-__device__ __forceinline__ void fused_coeffs(const DecodeParams& p, unsigned char* smem, const int bh) {
-  using T = bf16_t;
-  constexpr int D = 128, kV = D / 16;          // 128-bit vectors of a row per thread (compressed dims <= 124)
-  constexpr int Mint = (NP - 1) * 64, kPitchG = Mint + 32;
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int b = bh / p.Hkv, hkv = bh % p.Hkv;
-  const int Dkc = p.Dkc, G = p.G, M = p.M;
-  const int row = tid >> 2, seg = tid & 3, c4n = Dkc / 4;
-  float* qc = reinterpret_cast<float*>(smem);                    // [G][Dkc]
-  float* gs_s = reinterpret_cast<float*>(smem + p.lds_tab);      // [G][Mint + 32]
-  T* qk_s = reinterpret_cast<T*>(gs_s + G * kPitchG);            // [G][32]
-  float* g0_s = reinterpret_cast<float*>(qk_s + G * 32);         // [G]
-
-  const float* ck0 = p.ck + static_cast<size_t>(bh) * M * Dkc;
-  f32x4 cv4[NP][kV];
-#pragma unroll
-  for (int ps = 0; ps < NP; ++ps) {
-    const float* ckr = ck0 + static_cast<size_t>(min(row + 64 * ps, M - 1)) * Dkc;
-#pragma unroll
-    for (int i = 0; i < kV; ++i)
-      if (4 * i < c4n) cv4[ps][i] = *reinterpret_cast<const f32x4*>(ckr + 4 * min(seg + 4 * i, c4n - 1));
-  }
-  uint64_t kbal[4];
-  mask_ballots(p.kmask + static_cast<size_t>(bh) * D, D, lane, kbal);
-  const size_t hq0 = static_cast<size_t>(b) * p.Hq + hkv * G;
-  const T* q = static_cast<const T*>(p.q) + hq0 * D;
-  const int nqe = G * D;   // <= 512
-  T qe[2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i) qe[i] = q[min(tid + i * kBlock, nqe - 1)];
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int it = tid + i * kBlock;
-    if (it < nqe) {
-      const int h = it >> 7, d = it & 127;
-      const int r = dim_rank(kbal, d);
-      if (r < 0) qc[h * Dkc + (-r - 1)] = to_f32(qe[i]);
-      else qk_s[h * 32 + r] = qe[i];
-    }
-  }
-  {
-    const int npad = 32 - p.Dku;
-    if (tid < G * npad) qk_s[(tid / npad) * 32 + p.Dku + tid % npad] = T{};
-  }
-  __syncthreads();
-#pragma unroll
-  for (int ps = 0; ps < NP; ++ps) {
-    const int m = row + 64 * ps;
-    const float w = (m < M) ? basis_weight((m + 1) / 2, p.T) : 0.0f;
-    for (int h = 0; h < G; ++h) {
-      const float* qh = qc + h * Dkc;
-      float acc = 0.0f;
-#pragma unroll
-      for (int i = 0; i < kV; ++i) {
-        if (4 * i < c4n) {
-          const int c4 = seg + 4 * i;
-          const f32x4 qv = *reinterpret_cast<const f32x4*>(qh + 4 * min(c4, c4n - 1));
-          const f32x4 c = cv4[ps][i];
-          const float d4 = (c[0] * qv[0] + c[1] * qv[1]) + (c[2] * qv[2] + c[3] * qv[3]);
-          acc += (c4 < c4n) ? d4 : 0.0f;
-        }
-      }
-      acc += __shfl_xor(acc, 1, kWave);
-      acc += __shfl_xor(acc, 2, kWave);
-      if (seg == 0 && m <= Mint) {
-        if (m == 0) g0_s[h] = acc * w;
-        else gs_s[h * kPitchG + (m - 1)] = acc * w;
-      }
-    }
-  }
-  // (the barrier that publishes g sits in the middle-row phase, after its table build)
-}
-
 // All full-width rows of a pair in one pass: wave w takes rows 256 s + 64 w .. + 63 of every chunk
 // s, keeps a running (max, sum, accumulator) of its own across the chunks, and requests the rows
 // of the next chunk as soon as the registers of the current one are free.  The waves meet once,
 // at the end, and leave ONE record.  Same arithmetic per chunk as partial_full_fast.
-template <typename T>
+// kH: query columns carried through the V side (1 for one query head per KV head, else 4).
+template <typename T, int kH>
 __device__ __forceinline__ void fused_full_rows(const DecodeParams& p, const SeqView& sv, unsigned char* smem,
                                                 const int bh, const unsigned lds_recw) {
   static_assert(sizeof(T) == 2, "16-bit elements");
-  constexpr int D = 128, kH = 4;
+  constexpr int D = 128, kHP = 4;   // (LDS pitches stay those of four columns)
   const int b = bh / p.Hkv, hkv = bh % p.Hkv;
   const int G = p.G;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -3058,11 +3100,11 @@ __device__ __forceinline__ void fused_full_rows(const DecodeParams& p, const Seq
   const int nch = (W + kWChunk - 1) / kWChunk;
   const int jvis = W - p.Tq + r16 / p.Gq;
 
-  float* pw = reinterpret_cast<float*>(smem) + wave * kWRows * kH;          // [64 rows][4 columns] probabilities
-  float* red = reinterpret_cast<float*>(smem) + kWaves * kWRows * kH;      // [waves][4 columns][128 dims]
-  float* wm = red + kWaves * kH * D;                                        // [waves][4] maxima
-  float* wl = wm + kWaves * kH;                                             // [waves][4] sums
-  float* wa = wl + kWaves * kH;                                             // [waves][4] rescale factors of a chunk
+  float* pw = reinterpret_cast<float*>(smem) + wave * kWRows * kHP;          // [64 rows][4 columns] probabilities
+  float* red = reinterpret_cast<float*>(smem) + kWaves * kWRows * kHP;      // [waves][4 columns][128 dims]
+  float* wm = red + kWaves * kHP * D;                                        // [waves][4] maxima
+  float* wl = wm + kWaves * kHP;                                             // [waves][4] sums
+  float* wa = wl + kWaves * kHP;                                             // [waves][4] rescale factors of a chunk
 
   const T* kbase = static_cast<const T*>(p.k_full) + bh * p.full_stride;
   const T* vbase = static_cast<const T*>(p.v_full) + bh * p.full_stride;
@@ -3133,17 +3175,17 @@ __device__ __forceinline__ void fused_full_rows(const DecodeParams& p, const Seq
       for (int v = 0; v < 4; ++v) {
         const float e = __expf(sacc[rb][v] - m_ref);   // masked rows hold -inf -> 0
         l_w += e;
-        if (r16 < kH) pw[(16 * rb + 4 * q4 + v) * kH + r16] = e;
+        if (r16 < kH) pw[(16 * rb + 4 * q4 + v) * kHP + r16] = e;
       }
     l_w = cross_row_sum(l_w);
     l_run = l_run * alpha + l_w;
     m_run = m_new;
-    if (lane < kH) wa[wave * kH + lane] = alpha;
+    if (lane < kH) wa[wave * kHP + lane] = alpha;
     // written by this wave, read by this wave: the LDS operations of a wave complete in order
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const f32x4 al = *reinterpret_cast<const f32x4*>(wa + wave * kH);
+    const f32x4 al = *reinterpret_cast<const f32x4*>(wa + wave * kHP);
 #pragma unroll
     for (int h = 0; h < kH; ++h)
 #pragma unroll
@@ -3151,7 +3193,7 @@ __device__ __forceinline__ void fused_full_rows(const DecodeParams& p, const Seq
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int r = rg + 4 * i;
-      const f32x4 p4 = *reinterpret_cast<const f32x4*>(pw + r * kH);   // rows past the end hold zeros
+      const f32x4 p4 = *reinterpret_cast<const f32x4*>(pw + r * kHP);   // rows past the end hold zeros
       float x[8];
       unpack8(vf[i], x);
 #pragma unroll
@@ -3172,14 +3214,14 @@ __device__ __forceinline__ void fused_full_rows(const DecodeParams& p, const Seq
   if (rg == 0) {
 #pragma unroll
     for (int h = 0; h < kH; ++h) {
-      float* dst = red + (wave * kH + h) * D + dc * 8;
+      float* dst = red + (wave * kHP + h) * D + dc * 8;
       *reinterpret_cast<f32x4*>(dst) = f32x4{acc[h][0], acc[h][1], acc[h][2], acc[h][3]};
       *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[h][4], acc[h][5], acc[h][6], acc[h][7]};
     }
   }
   if (lane < kH) {
-    wm[wave * kH + lane] = m_run;
-    wl[wave * kH + lane] = l_run;
+    wm[wave * kHP + lane] = m_run;
+    wl[wave * kHP + lane] = l_run;
   }
   __syncthreads();
   if (tid < kH * (D / 4)) {
@@ -3187,15 +3229,15 @@ __device__ __forceinline__ void fused_full_rows(const DecodeParams& p, const Seq
     if (h < G) {
       float ms = wm[h];
 #pragma unroll
-      for (int w = 1; w < kWaves; ++w) ms = fmaxf(ms, wm[w * kH + h]);
+      for (int w = 1; w < kWaves; ++w) ms = fmaxf(ms, wm[w * kHP + h]);
       f32x4 v = {0.f, 0.f, 0.f, 0.f};
       float l = 0.0f;
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) {
-        const float mw = wm[w * kH + h];
+        const float mw = wm[w * kHP + h];
         const float f = (mw == -INFINITY) ? 0.0f : __expf(mw - ms);
-        l += f * wl[w * kH + h];
-        v += f * *reinterpret_cast<const f32x4*>(red + (w * kH + h) * D + 4 * d4);
+        l += f * wl[w * kHP + h];
+        v += f * *reinterpret_cast<const f32x4*>(red + (w * kHP + h) * D + 4 * d4);
       }
       float* rec = reinterpret_cast<float*>(smem + lds_recw) + h * p.recw;   // past everything this phase uses
       *reinterpret_cast<f32x4*>(rec + 4 + 4 * d4) = v;
@@ -3204,23 +3246,6 @@ __device__ __forceinline__ void fused_full_rows(const DecodeParams& p, const Seq
         rec[1] = l;
       }
     }
-  }
-}
-
-// C_v of the pair goes straight from global memory into LDS (no registers, nothing waits for it
-// here): every wave copies 1 KB blocks, lane i of a block supplying bytes 16 i .. 16 i + 15.  The
-// last block may reach past the matrix: its lanes re-read the last vector (the stash is padded).
-__device__ __forceinline__ void fused_stash_cv(const DecodeParams& p, unsigned char* smem, const int bh,
-                                               const unsigned lds_cv) {
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const unsigned bytes = static_cast<unsigned>(p.M) * p.Dvc * 4u;
-  const unsigned nblk = (bytes + 1023u) >> 10;
-  const char* src = reinterpret_cast<const char*>(p.cv + static_cast<size_t>(bh) * p.M * p.Dvc);
-  for (unsigned blk = wave; blk < nblk; blk += kWaves) {
-    const unsigned off = min(blk * 1024u + 16u * lane, bytes - 16u);
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + off),
-                                     (__attribute__((address_space(3))) void*)(smem + lds_cv + blk * 1024u), 16, 0, 0);
   }
 }
 
@@ -3319,13 +3344,12 @@ __global__ __launch_bounds__(kBlock, 1) void decode_fused(DecodeParams p) {
   sv.part_w = nullptr;
   const FusedLds L = fused_lds(p.lds_tab, p.G, Mint, p.recm, p.recw, p.M, p.Dvc);
   if (sv.N > 0) {
-    fused_coeffs<2 * CW + 1>(p, smem, bh);
-    if (p.Dvc > 0) fused_stash_cv(p, smem, bh, L.cv);
     partial_middle_fast<CW, DVT, GP, true>(p, sv, smem, bh, 0);
   }
   if (sv.W > 0) {
     __syncthreads();
-    fused_full_rows<T>(p, sv, smem, bh, L.recw);
+    if constexpr (GP == 1) fused_full_rows<T, 1>(p, sv, smem, bh, L.recw);
+    else fused_full_rows<T, 4>(p, sv, smem, bh, L.recw);
   }
   __syncthreads();
   fused_finish(p, smem, bh, L, sv.N > 0, sv.W > 0);
