@@ -250,6 +250,28 @@ int fa_append(const void* k_new, const void* v_new, int dtype,
               void* hip_stream);
 
 /*
+ * fa_append_varlen -- fa_append for a batch whose sequences stand at different positions (Eq. 5 per
+ * sequence): every sequence has its own ring row and its own count of folded tokens.
+ *
+ *   seq_slot    device pointer to B int32: the ring row of sequence b that receives its new token.
+ *               A value outside [0, W) leaves that sequence untouched (a finished sequence).
+ *   seq_nmid    device pointer to B int32: the middle position the evicted token of sequence b
+ *               takes (= tokens folded so far); negative: that sequence's window is still
+ *               filling, nothing is folded and only the row is written.
+ *   n_cap       tokens the k_keep / v_keep slabs have room for (strides 0 = dense for n_cap
+ *               tokens); n_cap <= T.  A seq_nmid value >= n_cap is treated like a negative one.
+ * Everything else as fa_append with evict = 1.  The lists are read by the kernels.
+ */
+int fa_append_varlen(const void* k_new, const void* v_new, int dtype,
+                     int B, int Hkv, int D,
+                     void* k_full, void* v_full, int W, int64_t full_stride_bh, const int32_t* seq_slot,
+                     const uint8_t* kmask, int Dkc, const uint8_t* vmask, int Dvc,
+                     int M, int T, const int32_t* seq_nmid, int n_cap,
+                     float* ck, float* cv,
+                     void* k_keep, int64_t kk_stride_bh, void* v_keep, int64_t vk_stride_bh,
+                     void* hip_stream);
+
+/*
  * fa_compress_kv -- fa_compress for the K and the V segment of the same tokens in
  * one call (Eq. 2-4 applied to both caches, as prefill does).
  *

@@ -12,6 +12,6 @@ from .binding import (  # noqa: F401
     FA_MAX_HEAD_DIM, FA_MAX_GROUP, FA_MAX_STATES, FA_MAX_DECODE_STATES, FA_MAX_DECODE_STATES_F32, FA_MAX_KEPT_V_DIMS,
     FourierAttnError, lib, library_path, status_string,
     compress_workspace_bytes, decode_workspace_bytes, decode_default_splits,
-    fa_compress, fa_compress_kv, compress_kv_workspace_bytes, fa_decode, fa_decode_varlen, fa_decode_static, fa_decode_mq, fa_append, fa_select_dims, select_workspace_bytes, fa_legt, legt_workspace_bytes,
+    fa_compress, fa_compress_kv, compress_kv_workspace_bytes, fa_decode, fa_decode_varlen, fa_decode_static, fa_decode_mq, fa_append, fa_append_varlen, fa_select_dims, select_workspace_bytes, fa_legt, legt_workspace_bytes,
     keep_rows_from_tok8, tok8_numel, keep_rows_pitch,
 )

@@ -72,6 +72,9 @@ def _load(path: str = _LIB_PATH):
     lib.fa_append.restype = i32
     lib.fa_append.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i64, i32, i32,
                               vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, i64, vp, i64, vp]
+    lib.fa_append_varlen.restype = i32
+    lib.fa_append_varlen.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i64, vp,
+                                     vp, i32, vp, i32, i32, i32, vp, i32, vp, vp, vp, i64, vp, i64, vp]
     lib.fa_compress_kv_workspace_bytes.restype = sz
     lib.fa_compress_kv_workspace_bytes.argtypes = [i32] * 7
     lib.fa_compress_kv.restype = i32
@@ -301,6 +304,26 @@ def fa_append(k_new, v_new, k_full, v_full, slot, evict, kmask=None, vmask=None,
                        _stream_ptr(stream))
     if st != FA_OK:
         raise FourierAttnError(st, "fa_append")
+
+
+def fa_append_varlen(k_new, v_new, k_full, v_full, seq_slot, kmask, vmask, M, T, seq_nmid, n_cap,
+                     ck, cv, k_keep, v_keep, stream=None, kk_stride_bh=0, vk_stride_bh=0, full_stride_bh=0):
+    """Enqueue fa_append_varlen: `seq_slot` / `seq_nmid` are int32 device tensors [B] with each sequence's
+    ring row and fold position (negative fold position: the row is written, nothing is folded)."""
+    B, Hkv, D = k_new.shape
+    W = k_full.shape[2]
+    Dkc = ck.shape[-1] if ck is not None else 0
+    Dvc = cv.shape[-1] if cv is not None else 0
+    for t in (seq_slot, seq_nmid):
+        if t.dtype != torch.int32 or t.numel() != B or not t.is_contiguous():
+            raise ValueError("seq_slot / seq_nmid must be contiguous int32 tensors of B entries")
+    st = lib.fa_append_varlen(_ptr(k_new), _ptr(v_new), _dtype_code(k_new), B, Hkv, D,
+                              _ptr(k_full), _ptr(v_full), W, full_stride_bh, _ptr(seq_slot),
+                              _ptr(kmask), Dkc, _ptr(vmask), Dvc, M, T, _ptr(seq_nmid), int(n_cap),
+                              _ptr(ck), _ptr(cv), _ptr(k_keep), kk_stride_bh, _ptr(v_keep), vk_stride_bh,
+                              _stream_ptr(stream))
+    if st != FA_OK:
+        raise FourierAttnError(st, "fa_append_varlen")
 
 
 def select_workspace_bytes(dtype_code, B, H, N, D, M) -> int:

@@ -1123,6 +1123,7 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
                          fa::CompressParams* only_params = nullptr, fa::CompressPlan* only_plan = nullptr,
                          int tensors = 1) {
   using namespace fa;
+  const hipError_t prior = hipPeekAtLastError();   // (an error left by earlier, unrelated calls is not this call's)
   const int st = check_compress_shapes(dtype, B, H, N, D, Dc, M, T, t0);
   if (st != FA_OK) return st;
   if (!dim_mask || (Dc > 0 && !coeffs) || (N > 0 && !x)) return FA_ERR_NULL;
@@ -1222,7 +1223,7 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
     FA_LAUNCH_TIMED(tm, 1, compress_reduce, dim3(blocks), dim3(256), 0, stream, p.part, coeffs, total,
                     p.part_stride, pl.Sc, p.accumulate);
   }
-  return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
+  return (hipPeekAtLastError() == hipSuccess || prior != hipSuccess) ? FA_OK : FA_ERR_HIP;
 }
 
 int fa_compress(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n, int B, int H,
@@ -1256,6 +1257,7 @@ static int compress_kv_impl(const void* k, const void* v, int dtype, int64_t sx_
                             void* workspace, size_t workspace_bytes, void* hip_stream, fa::KernelTimers* tm,
                             fa::KernelTimers* tm2) {
   using namespace fa;
+  const hipError_t prior = hipPeekAtLastError();   // (an error left by earlier, unrelated calls is not this call's)
   if (dtype != FA_F32 && dtype != FA_BF16) return FA_ERR_UNSUPPORTED;
   const size_t wk = (fa_compress_workspace_bytes_for(dtype, B, H, N, D, Dkc, M) + 255) & ~size_t(255);
   const size_t wv = fa_compress_workspace_bytes_for(dtype, B, H, N, D, Dvc, M);
@@ -1312,7 +1314,7 @@ static int compress_kv_impl(const void* k, const void* v, int dtype, int64_t sx_
     const size_t tmax = r.total[0] > r.total[1] ? r.total[0] : r.total[1];
     FA_LAUNCH_TIMED(tm, 1, compress_reduce_kv, dim3(static_cast<unsigned>((tmax / 4 + 1 + 255) / 256), 2), dim3(256), 0, stream, r);
   }
-  return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
+  return (hipPeekAtLastError() == hipSuccess || prior != hipSuccess) ? FA_OK : FA_ERR_HIP;
 }
 
 int fa_compress_kv(const void* k, const void* v, int dtype, int64_t sx_b, int64_t sx_h, int64_t sx_n,

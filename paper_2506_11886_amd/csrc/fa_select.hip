@@ -176,6 +176,7 @@ int fa_select_dims(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t
                    int N, int D, int M, int Dc, uint8_t* dim_mask, float* mse, void* workspace,
                    size_t workspace_bytes, void* hip_stream) {
   using namespace fa;
+  const hipError_t prior = hipPeekAtLastError();   // (an error left by earlier, unrelated calls is not this call's)
   const int st = check_select_shapes(dtype, B, H, N, D, M, Dc);
   if (st != FA_OK) return st;
   if (!x || !dim_mask || !workspace) return FA_ERR_NULL;
@@ -199,7 +200,7 @@ int fa_select_dims(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t
   const dim3 g1(pl.chunks, B * H);
   if (dtype == FA_BF16) hipLaunchKernelGGL(select_energy<bf16_t>, g1, dim3(kSBlock), 0, stream, p);
   else hipLaunchKernelGGL(select_energy<float>, g1, dim3(kSBlock), 0, stream, p);
-  if (hipGetLastError() != hipSuccess) return FA_ERR_HIP;
+  if (hipPeekAtLastError() != hipSuccess && prior == hipSuccess) return FA_ERR_HIP;
 
   // all D dims, period T = N, fp32 arithmetic
   int rc;
@@ -214,7 +215,7 @@ int fa_select_dims(const void* x, int dtype, int64_t sx_b, int64_t sx_h, int64_t
   if (rc != FA_OK) return rc;
 
   hipLaunchKernelGGL(select_rank, dim3(B * H), dim3(kRBlock), 0, stream, p);
-  return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_HIP;
+  return (hipPeekAtLastError() == hipSuccess || prior != hipSuccess) ? FA_OK : FA_ERR_HIP;
 }
 
 }  // extern "C"

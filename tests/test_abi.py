@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(fa_[a-z_0-9]+)\s*\(", hdr))
     assert {"fa_compress", "fa_decode", "fa_compress_workspace_bytes",
             "fa_decode_workspace_bytes", "fa_decode_default_splits", "fa_status_string",
-            "fa_append", "fa_select_dims", "fa_select_workspace_bytes", "fa_decode_mq", "fa_compress_kv", "fa_decode_varlen",
+            "fa_append", "fa_select_dims", "fa_select_workspace_bytes", "fa_decode_mq", "fa_compress_kv", "fa_decode_varlen", "fa_append_varlen",
             "fa_compress_kv_workspace_bytes", "fa_decode_static", "fa_compress_workspace_bytes_for",
             "fa_compress_kv_workspace_bytes_for", "fa_legt_compress", "fa_legt_mse",
             "fa_legt_workspace_bytes"} <= names

@@ -425,6 +425,83 @@ def test_append_steps_match_oracle(name):
             assert np.array_equal(kf_g[b, h], kf) and np.array_equal(vf_g[b, h], vf), ("ring", b, h)
 
 
+def test_append_varlen_matches_oracle():
+    """fa_append_varlen: three sequences at different positions (one still filling its window, one
+    finished and left alone), several steps, then fa_decode_varlen over the streamed states; against
+    oracle.append_token per sequence and oracle.decode_varlen."""
+    import oracle.fourier_kv as fk
+    from dataclasses import replace
+    fa = _fa()
+    cfg = replace(ONE_LAUNCH[0], name="vl_append", index=56, B=3, N=400, Lw=20)
+    ctx = cached_context(cfg)
+    B, H, D, M, G = cfg.B, cfg.Hkv, cfg.D, cfg.M, cfg.G
+    Dku, Dvu = D - cfg.Dkc, D - cfg.Dvc
+    W, Li, T, cap = cfg.W, cfg.Li, 1024, cfg.N
+    ring = W - Li
+    steps = 5
+    # sequence 0: 300 rows folded so far, evicting; sequence 1: window still filling (its ring rows from
+    # Li + 3 on are free); sequence 2: finished (slot -1), untouched
+    n0 = [300, 0, 123]
+    rng = np.random.default_rng(77)
+    dt = torch.bfloat16
+    new_k = torch.from_numpy(rng.standard_normal((steps, B, H, D)).astype(np.float32)).to(dt)
+    new_v = torch.from_numpy(rng.standard_normal((steps, B, H, D)).astype(np.float32)).to(dt)
+    kmask, vmask = to_dev(ctx["kmask"]), to_dev(ctx["vmask"])
+    # oracle states of the prefixes, handed to the GPU as its starting state
+    ck = np.zeros((B, H, M, cfg.Dkc)); cv = np.zeros((B, H, M, cfg.Dvc))
+    kk = np.zeros((B, H, cap, Dku), np.float32); vk = np.zeros((B, H, cap, Dvu), np.float32)
+    for b in range(B):
+        for h in range(H):
+            ck[b, h], kk[b, h, :n0[b]] = fk.compress_segment(ctx["k_mid"][b, h][:n0[b]], ctx["kmask"][b, h], M, T, 0)
+            cv[b, h], vk[b, h, :n0[b]] = fk.compress_segment(ctx["v_mid"][b, h][:n0[b]], ctx["vmask"][b, h], M, T, 0)
+    ck_d, cv_d = to_dev(ck.astype(np.float32)), to_dev(cv.astype(np.float32))
+    kk_d, vk_d = to_dev(rows_pad8(kk), cfg), to_dev(rows_to_tok8(vk), cfg)
+    k_full, v_full = to_dev(ctx["k_full"], cfg), to_dev(ctx["v_full"], cfg)
+    wfill = Li + 3   # sequence 1 has this many valid full-width rows before the steps
+    o_state = {}
+    for b in range(B):
+        for h in range(H):
+            o_state[(b, h)] = [ck[b, h].astype(np.float32).astype(np.float64), cv[b, h].astype(np.float32).astype(np.float64),
+                               kk[b, h, :n0[b]].astype(np.float64), vk[b, h, :n0[b]].astype(np.float64),
+                               ctx["k_full"][b, h].astype(np.float64), ctx["v_full"][b, h].astype(np.float64)]
+    nk, nv = new_k.float().numpy().astype(np.float64), new_v.float().numpy().astype(np.float64)
+    for s in range(steps):
+        slot = [Li + s % ring, wfill + s, -1]
+        nmid = [n0[0] + s, -1, 0]
+        fa.fa_append_varlen(new_k[s].cuda(), new_v[s].cuda(), k_full, v_full,
+                            torch.tensor(slot, dtype=torch.int32).cuda(), kmask, vmask, M, T,
+                            torch.tensor(nmid, dtype=torch.int32).cuda(), cap, ck_d, cv_d, kk_d, vk_d)
+        for b in range(2):
+            for h in range(H):
+                st = o_state[(b, h)]
+                o_state[(b, h)] = list(fk.append_token(st[0], st[1], ctx["kmask"][b, h], ctx["vmask"][b, h], st[2], st[3],
+                                                       st[4], st[5], slot[b], nk[s, b, h], nv[s, b, h], T,
+                                                       max(nmid[b], 0), nmid[b] >= 0))
+    seq_n = [n0[0] + steps, 0, n0[2]]
+    seq_w = [W, wfill + steps, W]
+    out = fa.fa_decode_varlen(to_dev(ctx["q"], cfg), ck_d, kmask, cv_d, vmask, M, T, 0, cap,
+                              torch.tensor(seq_n, dtype=torch.int32).cuda(), kk_d, vk_d, k_full, v_full,
+                              torch.tensor(seq_w, dtype=torch.int32).cuda(), num_splits=1).cpu().numpy()
+    torch.cuda.synchronize()
+    ck_g, cv_g = ck_d.cpu().numpy(), cv_d.cpu().numpy()
+    kk_g = kk_d.float().cpu().numpy()[..., :Dku]
+    vk_g = fa.keep_rows_from_tok8(vk_d, cap, Dvu).float().cpu().numpy()
+    kf_g, vf_g = k_full.float().cpu().numpy(), v_full.float().cpu().numpy()
+    for b in range(B):
+        for h in range(H):
+            Ck, Cv, kko, vko, kf, vf = o_state[(b, h)]
+            n = seq_n[b]
+            fl = np.sqrt(max(n, 1) * np.mean(ctx["k_mid"][b, h][:, ctx["kmask"][b, h] == 1].astype(np.float64) ** 2))
+            assert rel_err(ck_g[b, h], Ck, fl) <= cfg.tol, ("ck", b, h)
+            fl = np.sqrt(max(n, 1) * np.mean(ctx["v_mid"][b, h][:, ctx["vmask"][b, h] == 1].astype(np.float64) ** 2))
+            assert rel_err(cv_g[b, h], Cv, fl) <= cfg.tol, ("cv", b, h)
+            assert np.array_equal(kk_g[b, h][:n], kko[:n]) and np.array_equal(vk_g[b, h][:n], vko[:n]), ("keep", b, h)
+            assert np.array_equal(kf_g[b, h], kf) and np.array_equal(vf_g[b, h], vf), ("ring", b, h)
+            want = fk.decode_head_group(ctx["q"][b, h * G:(h + 1) * G], Ck, ctx["kmask"][b, h], Cv, ctx["vmask"][b, h],
+                                        T, 0, n, kko[:n], vko[:n], kf[:seq_w[b]], vf[:seq_w[b]])
+            assert rel_err(out[b, h * G:(h + 1) * G], want) <= cfg.tol, ("out", b, h)
+
+
 def test_append_without_eviction_only_writes_the_row():
     fa = _fa()
     k_full = torch.zeros((2, 3, 9, 64), dtype=torch.bfloat16, device="cuda")
