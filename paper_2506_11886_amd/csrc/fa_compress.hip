@@ -1200,8 +1200,10 @@ static int compress_impl(const void* x, int dtype, int64_t sx_b, int64_t sx_h, i
       // straight-line block step when every thread has at most one vector of kept dims to store
       const int nvec = (x_keep == nullptr || Du == 0) ? 0 : (keep_layout == FA_KEEP_ROWS ? kFB * (keep_pitch / 8) : Du * (kFB / 8));
       const int km = (Dc == 0 || nvec > kCBlock) ? -1 : (nvec == 0 ? 0 : (keep_layout == FA_KEEP_ROWS ? 1 : 2));
+      // (column tiles compiled in: 6, 7 or 8 - a tile without compressed columns would still be multiplied)
 #define FA_LAUNCH_FAST(KM_) \
-  rc = narrow ? launch_project_fast<6, KM_>(p, pl, fast_lds, stream, tm) : launch_project_fast<8, KM_>(p, pl, fast_lds, stream, tm)
+  rc = narrow ? launch_project_fast<6, KM_>(p, pl, fast_lds, stream, tm) \
+     : (Dc <= 112 ? launch_project_fast<7, KM_>(p, pl, fast_lds, stream, tm) : launch_project_fast<8, KM_>(p, pl, fast_lds, stream, tm))
       if (km == 0) FA_LAUNCH_FAST(0);
       else if (km == 1) FA_LAUNCH_FAST(1);
       else if (km == 2) FA_LAUNCH_FAST(2);
@@ -1295,14 +1297,18 @@ static int compress_kv_impl(const void* k, const void* v, int dtype, int64_t sx_
   }
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   CompressParamsKV pp{pk, pv};
-  const bool narrow = (Dkc > Dvc ? Dkc : Dvc) <= 96;
+  // column tiles compiled in: 6, 7 or 8 (a tile without compressed columns would still be multiplied)
+  const int dmax = Dkc > Dvc ? Dkc : Dvc;
+  const void* kern = dmax <= 96 ? reinterpret_cast<const void*>(compress_project_fast_kv<6>)
+                   : (dmax <= 112 ? reinterpret_cast<const void*>(compress_project_fast_kv<7>)
+                                  : reinterpret_cast<const void*>(compress_project_fast_kv<8>));
   if (lds > 48u * 1024u &&
-      hipFuncSetAttribute(narrow ? reinterpret_cast<const void*>(compress_project_fast_kv<6>)
-                                 : reinterpret_cast<const void*>(compress_project_fast_kv<8>),
+      hipFuncSetAttribute(kern,
                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxCLds)) != hipSuccess)
     return FA_ERR_HIP;
   const dim3 grid(plk.Sc, plk.MC, 2 * B * H);
-  if (narrow) FA_LAUNCH_TIMED(tm, 0, compress_project_fast_kv<6>, grid, dim3(kCBlock), lds, stream, pp);
+  if (dmax <= 96) FA_LAUNCH_TIMED(tm, 0, compress_project_fast_kv<6>, grid, dim3(kCBlock), lds, stream, pp);
+  else if (dmax <= 112) FA_LAUNCH_TIMED(tm, 0, compress_project_fast_kv<7>, grid, dim3(kCBlock), lds, stream, pp);
   else FA_LAUNCH_TIMED(tm, 0, compress_project_fast_kv<8>, grid, dim3(kCBlock), lds, stream, pp);
   if (plk.Sc > 1) {
     ReducePair r{};

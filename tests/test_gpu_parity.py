@@ -241,7 +241,8 @@ def test_decode_varlen_one_launch_and_three_launch_forms():
 
 def test_decode_varlen_general_kernels():
     """The general middle-row kernel (fp32; bf16 with sixteen query heads per KV head) and the
-    eight-wave kernel for 512 series slots, the latter also with several chunks per workgroup."""
+    eight-wave kernel for 512 series slots, the latter also with more chunks asked for than there are
+    compute units (chunks are then joined)."""
     from dataclasses import replace
     base = SMALL[0]
     cfg = replace(base, name="vl_f32", index=53, B=3, Hq=4, Hkv=2, D=64, N=600, Lw=50, Dkc=40, Dvc=48, M=48,
@@ -252,7 +253,7 @@ def test_decode_varlen_general_kernels():
                   dtype="bf16")
     print(f"[case] varlen {cfg}", flush=True)
     _varlen_case(cfg, [450, 129], [154, 3], [0, 3])
-    # (48 pairs x 6 chunks of two steps: more chunks than compute units, two chunks per workgroup)
+    # (48 pairs x 6 chunks of two steps: more chunks than compute units, joined two by two)
     cfg = replace(base, name="vl_m512", index=55, B=6, Hq=32, Hkv=8, D=128, N=3000, Lw=40, Dkc=112, Dvc=112,
                   M=512, dtype="bf16")
     print(f"[case] varlen {cfg}", flush=True)
