@@ -534,13 +534,15 @@ def _select_case(cfg, M, nheads=None):
     for b, h in sample_heads(cfg, nheads):
         want_mask, want_mse = fk.select_dims(xh[b, h], M, cfg.Dkc)
         scale = np.mean(xh[b, h] ** 2, axis=0)          # mean square of each dim
-        assert np.all(np.abs(mse[b, h] - want_mse) <= 2e-5 * scale + 1e-12), (b, h, np.abs(mse[b, h] - want_mse).max())
+        # 5e-6 of a dim's mean square, inside the 1e-5 asked of fp32 work (the error path is fp32 for either
+        # element type; measured: at most 1.3e-6 on these shapes and on the 32 K-token workload)
+        assert np.all(np.abs(mse[b, h] - want_mse) <= 5e-6 * scale + 1e-12), (b, h, np.abs(mse[b, h] - want_mse).max())
         assert mask[b, h].sum() == cfg.Dkc
         # the selected set is unique wherever the errors are separated by more than the rounding floor
         order = np.argsort(want_mse, kind="stable")
         if 0 < cfg.Dkc < cfg.D:
             gap = want_mse[order[cfg.Dkc]] - want_mse[order[cfg.Dkc - 1]]
-            if gap > 1e-4 * scale.max():
+            if gap > 1e-5 * scale.max():   # (twice the tolerance of the errors themselves)
                 assert np.array_equal(mask[b, h], want_mask), (b, h)
         else:
             assert np.array_equal(mask[b, h], want_mask), (b, h)
