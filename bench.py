@@ -278,6 +278,23 @@ def measure(cfg, steps, warmup, extras=False):
             res["phases"]["decode_mq"] = {"query_tokens": Tq, "ms": round(t_mq * 1e3, 5),
                                           "ms_per_query_token": round(t_mq * 1e3 / Tq, 5),
                                           "wall_GBps": round(dec_bytes / t_mq / 1e9, 1)}
+        if B > 1:   # the same batch with its sequences at different positions (a quarter to all of the rows each)
+            g = torch.Generator().manual_seed(4000 + cfg.index)
+            seq_n = (torch.randint(N // 4, N + 1, (B,), generator=g)).to(torch.int32).cuda()
+            seq_w = torch.full((B,), W, dtype=torch.int32).cuda()
+            out_vl = torch.empty((B, Hq, D), dtype=torch.float32, device="cuda")
+
+            def decode_vl(i):
+                s = sets[i % n_sets]
+                fa.fa_decode_varlen(s["q"], s["ck"], s["kmask"], s["cv"], s["vmask"], M, T, 0, N, seq_n, s["kk"], s["vk"],
+                                    s["k_full"], s["v_full"], seq_w, num_splits=cfg.num_splits, out=out_vl, workspace=ws_d)
+            for i in range(4):
+                decode_vl(i)
+            t_vl = timed_loop(torch, decode_vl, steps)
+            rows = int(seq_n.sum().item()) + B * W
+            res["phases"]["decode_varlen"] = {"ms": round(t_vl * 1e3, 5), "context_tokens": rows,
+                                              "context_tokens_per_s": round(rows / t_vl, 1),
+                                              "mean_fill": round(float(seq_n.float().mean().item()) / N, 3)}
         if N >= M:
             ws_s = torch.empty(max(256, fa.select_workspace_bytes(fa.FA_BF16 if dt == torch.bfloat16 else fa.FA_F32,
                                                                   B, Hkv, N, D, M)), dtype=torch.uint8, device="cuda")
