@@ -193,12 +193,16 @@ def measure(cfg, steps, warmup, extras=False):
     if kd[0] == 0.0 and kd[2] == 0.0:   # the one-launch form: one workgroup per (sequence, KV head) does it all
         names, kd, kb = ("fused",), kd[1:2], {"fused": dec_bytes}
         what = "fa_decode call = decode_fused (series coefficients, all rows and the merge in one launch)"
+    def kernel_traffic(prefix):   # counter summary lines are keyed by kernel name (decode_prepare2, decode_partial_fast8, ...)
+        hits = [v for k, v in traffic.items() if k.startswith(prefix)]
+        return sum(hits) if hits else None
+
     per_kernel = {}
     for i, n in enumerate(names):
         per_kernel["decode_" + n] = {"ms": round(float(kd[i]) * 1e3, 5), "algorithmic_bytes": kb[n],
-                                     **hbm(kb[n], float(kd[i])), "traffic": traffic.get("decode_" + n)}
+                                     **hbm(kb[n], float(kd[i])), "traffic": kernel_traffic("decode_" + n)}
     dom = "decode_" + names[int(np.argmax(kd))]
-    call_traffic = [traffic.get("decode_" + n) for n in names]
+    call_traffic = [kernel_traffic("decode_" + n) for n in names]
     roof_dec = {"kernel": what,
                 "bound": "hbm", **hbm(dec_bytes, t_kernels), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "algorithmic_bytes": dec_bytes, "kernels_ms": round(t_kernels * 1e3, 5),
