@@ -1288,6 +1288,8 @@ __device__ __forceinline__ void partial_middle_rows(const DecodeParams& p, unsig
 // lane holds) instead of being transposed through LDS, which takes the barriers out of the
 // prologue.  The wave-wide maximum of the softmax uses the half- and row-swap lane permutes.
 
+constexpr float kSoftmaxSlack = 8.0f;   // how far a score may exceed its column's reference before the reference moves
+
 // max over the four 16-lane rows of a wave, per lane position, result in every lane
 __device__ __forceinline__ float cross_row_max(float v) {
   auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
@@ -1857,11 +1859,19 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const
       pv[v] = sc;
       m_tile = fmaxf(m_tile, sc);
     }
-    m_tile = row_stride_max(m_tile, 4);                      // the 16 lanes of a column are 4 apart
-    m_tile = cross_row_max(m_tile);
-    const float m_new = fmaxf(m_run, m_tile);
-    const float m_ref = (m_new == -INFINITY) ? 0.0f : m_new;
-    const float alpha = __expf(m_run - m_ref);   // m_run = -inf -> 0
+    // The reference m_run of a column only has to keep exp(score - m_run) inside the range of the
+    // 16-bit probabilities, not to be the maximum: it moves when a score of one of the wave's columns
+    // exceeds it by more than kSoftmaxSlack (always in a chunk's first step), and only then is there a
+    // maximum to reduce and a factor to apply.
+    float alpha = 1.0f;
+    if (__builtin_amdgcn_ballot_w64(m_tile > m_run + kSoftmaxSlack) != 0) {   // (uniform over the wave)
+      m_tile = row_stride_max(m_tile, 4);                    // the 16 lanes of a column are 4 apart
+      m_tile = cross_row_max(m_tile);
+      const float m_new = fmaxf(m_run, m_tile);
+      alpha = __expf(m_run - ((m_new == -INFINITY) ? 0.0f : m_new));   // m_run = -inf -> 0
+      m_run = m_new;
+    }
+    const float m_ref = (m_run == -INFINITY) ? 0.0f : m_run;
     float l_add = 0.0f;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
@@ -1869,7 +1879,6 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const
       l_add += pv[v];
     }
     l_run = l_run * alpha + l_add;
-    m_run = m_new;
     {
       const int slot = (((orb >> 1) * 16 + ocol) * 4 + oq4) * 8 + 4 * (orb & 1);
       u32x2d w;
@@ -1892,17 +1901,27 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const
     // -- (e) bring the accumulators into this step's frame (the first step scales zeros by zero) --
     {
       const f32x4 al = *reinterpret_cast<const f32x4*>(alpha_s + 4 * q4);
+      const bool moved = al[0] != 1.0f || al[1] != 1.0f || al[2] != 1.0f || al[3] != 1.0f;
+      if (__builtin_amdgcn_ballot_w64(moved) != 0) {   // some column's reference moved: factors to apply
 #pragma unroll
-      for (int t = 0; t < DVT; ++t)
+        for (int t = 0; t < DVT; ++t)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) oacc[t][v] *= al[v];
+          for (int v = 0; v < 4; ++v) oacc[t][v] *= al[v];
+#pragma unroll
+        for (int i = 0; i < CW; ++i)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            racc[2 * i][v] *= al[v];
+            racc[2 * i + 1][v] *= al[v];
+          }
+      }
 #pragma unroll
       for (int i = 0; i < CW; ++i)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const float rc = racc[2 * i][v], rs = racc[2 * i + 1][v];
-          racc[2 * i][v] = al[v] * (tc[i] * rc + ts[i] * rs);
-          racc[2 * i + 1][v] = al[v] * (tc[i] * rs - ts[i] * rc);
+          racc[2 * i][v] = tc[i] * rc + ts[i] * rs;
+          racc[2 * i + 1][v] = tc[i] * rs - ts[i] * rc;
         }
     }
     // -- (f) V side, own orders: r' += P^T E;  (g) kept V dims of tile `wave`: O += P^T V^mu -------
@@ -2059,7 +2078,6 @@ __global__ __launch_bounds__(kBlock, CW <= 2 ? 2 : 1) void decode_partial_fast(D
 // two rows per lane.  The score exchange is padded so that the eight-byte reads of the owners
 // fall in distinct LDS banks.
 constexpr int kWaves8 = 8;
-constexpr float kSoftmaxSlack = 8.0f;   // how far a score may exceed its column's reference before the reference moves
 constexpr int kBlock8 = 64 * kWaves8;
 constexpr int kXs8Q4 = 18;                    // f32x4 cells per (row block, lane / 16): 16 columns + 2 pad cells
 constexpr int kXs8Rb = 4 * kXs8Q4;            // per row block
