@@ -1790,6 +1790,42 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const
   for (int t = 0; t < DVT; ++t) oacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.0f;
 
+  // FUSED (a wave has the registers): the K-side coefficients of this lane's column (tile, head), four
+  // orders per slice, stay in registers rotated to the tile origin of the current step and are
+  // turned on by one step's angle after use (angle addition, four multiply-adds per order), instead
+  // of being evaluated from g in every step; they are taken afresh from g every 32 steps, so that the
+  // rounding of the turns never builds up over a long sequence.
+  float gk[FUSED ? CW : 1][8], tkc[FUSED ? CW : 1][4], tks[FUSED ? CW : 1][4];
+  auto seed_gk = [&](int base) {
+    if constexpr (FUSED) {
+      const uint32_t ph_k = phase_of(p.t0 + base + col_k * kTJ, p.ph_scale);
+#pragma unroll
+      for (int i = 0; i < CW; ++i) {
+        const uint32_t n0 = 16 * (wave * CW + i) + 4 * q4 + 1;
+        const float* gl = gs_s + hsafe * kPitchG + 32 * (wave * CW + i) + 8 * q4;
+        const f32x4 ga = *reinterpret_cast<const f32x4*>(gl), gb = *reinterpret_cast<const f32x4*>(gl + 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float cs, sn;
+          phase_cs<T>((n0 + j) * ph_k, &cs, &sn);
+          const float gc = (j < 2) ? ga[2 * (j & 1)] : gb[2 * (j & 1)];
+          const float gsn = (j < 2) ? ga[2 * (j & 1) + 1] : gb[2 * (j & 1) + 1];
+          gk[i][2 * j] = gc * cs + gsn * sn;
+          gk[i][2 * j + 1] = gsn * cs - gc * sn;
+        }
+      }
+    }
+  };
+  if constexpr (FUSED) {
+    const uint32_t ph_step = phase_of(step, p.ph_scale);
+#pragma unroll
+    for (int i = 0; i < CW; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        phase_cs<T>(static_cast<uint32_t>(16 * (wave * CW + i) + 4 * q4 + 1 + j) * ph_step, &tkc[i][j], &tks[i][j]);
+    seed_gk(c0);
+  }
+
   auto do_step = [&](Frag<T> (&kf)[4], Frag<T> (&vf)[2][DVT], int base, auto tail_tag) {
     constexpr bool kTail = decltype(tail_tag)::value;
     f32x4 sacc[kRB];
@@ -1797,37 +1833,53 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const
     for (int rb = 0; rb < kRB; ++rb) sacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // -- (a) series on the K side, own orders: S += E g'(tile origin) -----------------
-    const uint32_t ph_k = phase_of(p.t0 + base + col_k * kTJ, p.ph_scale);
+    if constexpr (FUSED) {
 #pragma unroll
-    for (int i = 0; i < CW; ++i) {
-      const uint32_t n0 = 16 * (wave * CW + i) + 4 * q4 + 1;
-      float csv[4], snv[4];
-      if constexpr (GP >= 4) {          // the 4 lanes of a quad share (tile, q4): one evaluation each
-        float cs, sn;
-        phase_cs<T>((n0 + (lane & 3)) * ph_k, &cs, &sn);
+      for (int i = 0; i < CW; ++i) {
+        Frag<ES> bg;   // (columns without a query head get some head's values: their scores are never used)
+        pack8(bg, gk[i]);
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], eA[i][rb], bg);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          csv[j] = quad_bcast(cs, j);
-          snv[j] = quad_bcast(sn, j);
+          const float gc = gk[i][2 * j], gsn = gk[i][2 * j + 1];
+          gk[i][2 * j] = tkc[i][j] * gc + tks[i][j] * gsn;
+          gk[i][2 * j + 1] = tkc[i][j] * gsn - tks[i][j] * gc;
         }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) phase_cs<T>((n0 + j) * ph_k, &csv[j], &snv[j]);
       }
-      const float* gl = gs_s + hsafe * kPitchG + 32 * (wave * CW + i) + 8 * q4;
-      const f32x4 ga = *reinterpret_cast<const f32x4*>(gl), gb = *reinterpret_cast<const f32x4*>(gl + 4);
-      float gp[8];
+    } else {
+      const uint32_t ph_k = phase_of(p.t0 + base + col_k * kTJ, p.ph_scale);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float gc = (j < 2) ? ga[2 * (j & 1)] : gb[2 * (j & 1)];
-        const float gsn = (j < 2) ? ga[2 * (j & 1) + 1] : gb[2 * (j & 1) + 1];
-        gp[2 * j] = gc * csv[j] + gsn * snv[j];
-        gp[2 * j + 1] = gsn * csv[j] - gc * snv[j];
+      for (int i = 0; i < CW; ++i) {
+        const uint32_t n0 = 16 * (wave * CW + i) + 4 * q4 + 1;
+        float csv[4], snv[4];
+        if constexpr (GP >= 4) {          // the 4 lanes of a quad share (tile, q4): one evaluation each
+          float cs, sn;
+          phase_cs<T>((n0 + (lane & 3)) * ph_k, &cs, &sn);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            csv[j] = quad_bcast(cs, j);
+            snv[j] = quad_bcast(sn, j);
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) phase_cs<T>((n0 + j) * ph_k, &csv[j], &snv[j]);
+        }
+        const float* gl = gs_s + hsafe * kPitchG + 32 * (wave * CW + i) + 8 * q4;
+        const f32x4 ga = *reinterpret_cast<const f32x4*>(gl), gb = *reinterpret_cast<const f32x4*>(gl + 4);
+        float gp[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float gc = (j < 2) ? ga[2 * (j & 1)] : gb[2 * (j & 1)];
+          const float gsn = (j < 2) ? ga[2 * (j & 1) + 1] : gb[2 * (j & 1) + 1];
+          gp[2 * j] = gc * csv[j] + gsn * snv[j];
+          gp[2 * j + 1] = gsn * csv[j] - gc * snv[j];
+        }
+        Frag<ES> bg;   // (columns without a query head get some head's values: their scores are never used)
+        pack8(bg, gp);
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], eA[i][rb], bg);
       }
-      Frag<ES> bg;   // (columns without a query head get some head's values: their scores are never used)
-      pack8(bg, gp);
-#pragma unroll
-      for (int rb = 0; rb < kRB; ++rb) mma_k32(sacc[rb], eA[i][rb], bg);
     }
     // -- (b) kept K dims of tile `wave`: A = K^mu rows, B = q masked to the tile's columns --
 #pragma unroll
@@ -1963,6 +2015,9 @@ __device__ __forceinline__ void partial_middle_fast(const DecodeParams& p, const
     int s = 0;
     for (; s + 2 < nsteps; s += 2) {
       const int base = c0 + s * step;
+      if constexpr (FUSED) {
+        if ((s & 31) == 0 && s > 0) seed_gk(base);
+      }
       do_step(kfA, vfA, base, std::false_type{});
       load_step(kfA, vfA, min(base + 2 * step, last_base));
       do_step(kfB, vfB, base + step, std::false_type{});
@@ -2446,29 +2501,29 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
     {
       float f[4];
       uint32_t phr[4];
-  #pragma unroll
+#pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int row = 4 * q4 + v;
         f[v] = __shfl(fc, row, kWave);
         phr[v] = phase_of(p.t0 + last_base + (row / GP) * kTJ, p.ph_scale);
       }
-  #pragma unroll
+#pragma unroll
       for (int i = 0; i < CW; ++i) {
         const int c = wave * CW + i;
         const uint32_t n = 16 * c + r16 + 1;
         float cs[4], sn[4];
         phase_cs<T>(n * phr[0], &cs[0], &sn[0]);
         if constexpr (GP >= 4) {
-  #pragma unroll
+#pragma unroll
           for (int v = 1; v < 4; ++v) {
             cs[v] = cs[0];
             sn[v] = sn[0];
           }
         } else {
-  #pragma unroll
+#pragma unroll
           for (int v = 1; v < 4; ++v) phase_cs<T>(n * phr[v], &cs[v], &sn[v]);
         }
-  #pragma unroll
+#pragma unroll
         for (int v = 0; v < 4; ++v) {
           const float rc = racc[2 * i][v], rs = racc[2 * i + 1][v];
           float* dst = red_r + (4 * q4 + v) * pr + 32 * c + r16;
@@ -2477,9 +2532,9 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
         }
       }
       float* ro = red_o + wave * 16 * po;
-  #pragma unroll
+#pragma unroll
       for (int dt = 0; dt < DVT; ++dt)
-  #pragma unroll
+#pragma unroll
         for (int v = 0; v < 4; ++v) ro[(4 * q4 + v) * po + 16 * dt + r16] = f[v] * oacc[dt][v];
     }
     __syncthreads();
@@ -2496,14 +2551,14 @@ __device__ __forceinline__ void partial_middle_fast8(const DecodeParams& p, unsi
       f32x4 v = {0.f, 0.f, 0.f, 0.f};
       if (x4 < no4) {
         // kept dims of tile k were accumulated by waves 2 k and 2 k + 1
-  #pragma unroll
+#pragma unroll
         for (int k = 0; k < KT; ++k) {
           v += *reinterpret_cast<const f32x4*>(red_o + (((2 * k) * 16 + k * GP + h) * po + 4 * x4));
           v += *reinterpret_cast<const f32x4*>(red_o + (((2 * k + 1) * 16 + k * GP + h) * po + 4 * x4));
         }
       } else {
         const int y = x4 - no4;
-  #pragma unroll
+#pragma unroll
         for (int k = 0; k < KT; ++k) v += *reinterpret_cast<const f32x4*>(red_r + ((k * GP + h) * pr + 4 * y));
       }
       *reinterpret_cast<f32x4*>(rec0 + h * rec_h + 4 + 4 * x4) = v;

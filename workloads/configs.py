@@ -106,7 +106,7 @@ def one_launch_variants():
     1 .. 32 kept dims on both sides, M <= 256, compressed counts in multiples of 4), covering its
     compiled variants: series of 128 / 256 slots, one or two tiles of kept V dims, one or several
     query heads per KV head; ragged row counts, no full-width rows, a period longer than the
-    segment that starts inside it."""
+    segment that starts inside it, a sequence of many steps."""
     base = CONFIGS[0]
     return (
         replace(base, name="ol_g4_m200", index=41, B=2, Hq=8, Hkv=2, D=128, N=1500, Lw=300,
@@ -119,6 +119,10 @@ def one_launch_variants():
                 Dkc=124, Dvc=96, M=31, dtype="bf16", num_splits=1, period=3000, t0=1400),
         replace(base, name="ol_mha_m129_short", index=45, B=1, Hq=2, Hkv=2, D=128, N=130, Lw=5,
                 Dkc=96, Dvc=108, M=129, dtype="bf16", num_splits=1),
+        # more than 32 steps of 256 rows in one workgroup (the register-resident series coefficients are
+        # taken afresh every 32 steps)
+        replace(base, name="ol_g4_long", index=46, B=1, Hq=4, Hkv=1, D=128, N=17111, Lw=20,
+                Dkc=104, Dvc=112, M=90, dtype="bf16", num_splits=1),
     )
 
 
