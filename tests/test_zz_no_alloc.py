@@ -38,3 +38,22 @@ def test_static_scratch_decode_matches_workspace_decode_twice_in_a_row():
         torch.cuda.synchronize()
         assert torch.isfinite(out).all()
         assert torch.equal(out, want), (cfg.name, (out - want).abs().max().item())
+
+
+def test_static_scratch_decode_in_the_one_launch_form():
+    """The same two calls in a row on shapes that run as one launch (num_splits = 1): that form keeps all
+    of its state in LDS, the static array is not even touched."""
+    import paper_2506_11886_amd as fa
+    from workloads import one_launch_variants
+    shapes = one_launch_variants()
+    for cfg in (shapes[0], shapes[4]):
+        print(f"[case] static scratch, one launch {cfg}", flush=True)
+        args = _inputs(cfg)
+        want = fa.fa_decode(*args, num_splits=1)
+        out = torch.full((cfg.B, cfg.Hq, cfg.D), float("nan"), dtype=torch.float32, device="cuda")
+        before = torch.cuda.memory_allocated()
+        fa.fa_decode_static(*args, num_splits=1, out=out)
+        assert torch.cuda.memory_allocated() == before
+        torch.cuda.synchronize()
+        assert torch.isfinite(out).all()
+        assert torch.equal(out, want), (cfg.name, (out - want).abs().max().item())
