@@ -208,3 +208,37 @@ def test_legt_rejects_bad_arguments_on_the_host():
     assert call(ws_bytes=16) == -4
     assert fa.lib.fa_legt_mse(FAKE, 1, 8 * 300 * 64, 300 * 64, 64, 1, 8, 300, 64, 32, FAKE, None, FAKE, 1 << 30, None) == -1
     assert fa.legt_workspace_bytes(1, 8, 300, 64, 32) >= 1 * 8 * 32 * 64 * 4
+
+
+def test_varlen_entry_points_reject_bad_arguments_on_the_host():
+    """fa_decode_varlen validates like fa_decode (N_max, W_max in the place of N, W); fa_append_varlen
+    needs both lists and a capacity inside the period."""
+    fa = _fa()
+
+    def decode_vl(**kw):
+        a = dict(q=FAKE, dtype=1, B=2, Hq=8, Hkv=2, D=128, ck=FAKE, kmask=FAKE, Dkc=96, cv=FAKE, vmask=FAKE,
+                 Dvc=96, M=32, T=512, t0=0, N=512, seq_n=FAKE, k_keep=FAKE, kks=0, v_keep=FAKE, vks=0,
+                 k_full=FAKE, v_full=FAKE, W=16, seq_w=FAKE, fs=0, scale=0.0, splits=0, out=FAKE, ws=FAKE,
+                 ws_bytes=0, stream=None)
+        a.update(kw)
+        return fa.lib.fa_decode_varlen(a["q"], a["dtype"], a["B"], a["Hq"], a["Hkv"], a["D"], a["ck"], a["kmask"],
+                                       a["Dkc"], a["cv"], a["vmask"], a["Dvc"], a["M"], a["T"], a["t0"], a["N"],
+                                       a["seq_n"], a["k_keep"], a["kks"], a["v_keep"], a["vks"], a["k_full"],
+                                       a["v_full"], a["W"], a["seq_w"], a["fs"], a["scale"], a["splits"], a["out"],
+                                       a["ws"], a["ws_bytes"], a["stream"])
+    assert decode_vl(Hq=7) == -2 and decode_vl(N=0, W=0) == -2 and decode_vl(q=None) == -1
+    assert decode_vl(ws_bytes=16) == -4 and decode_vl(seq_n=None, seq_w=None, ws_bytes=16) == -4
+
+    def append_vl(**kw):
+        a = dict(k_new=FAKE, v_new=FAKE, dtype=1, B=2, Hkv=2, D=64, k_full=FAKE, v_full=FAKE, W=8, fs=0,
+                 seq_slot=FAKE, kmask=FAKE, Dkc=48, vmask=FAKE, Dvc=48, M=16, T=100, seq_nmid=FAKE, n_cap=50,
+                 ck=FAKE, cv=FAKE, k_keep=FAKE, kks=0, v_keep=FAKE, vks=0, stream=None)
+        a.update(kw)
+        return fa.lib.fa_append_varlen(a["k_new"], a["v_new"], a["dtype"], a["B"], a["Hkv"], a["D"], a["k_full"],
+                                       a["v_full"], a["W"], a["fs"], a["seq_slot"], a["kmask"], a["Dkc"], a["vmask"],
+                                       a["Dvc"], a["M"], a["T"], a["seq_nmid"], a["n_cap"], a["ck"], a["cv"],
+                                       a["k_keep"], a["kks"], a["v_keep"], a["vks"], a["stream"])
+    assert append_vl(seq_slot=None) == -1 and append_vl(seq_nmid=None) == -1
+    assert append_vl(n_cap=0) == -2 and append_vl(n_cap=101) == -2
+    assert append_vl(kks=8) == -2            # a slab pitch below n_cap tokens
+    assert append_vl(M=0) == -2 and append_vl(D=60) == -3 and append_vl(kmask=None) == -1
